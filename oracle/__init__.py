@@ -1,0 +1,304 @@
+"""CPU ORACLE -- TEST INFRASTRUCTURE ONLY.
+
+Plain, slow reference implementations of the random-forest proximity path,
+written from the paper's definitions.  Integer steps and the float64 products
+live in oracle_core.c (loaded with ctypes); the dense linear-algebra steps are
+numpy / scipy library calls in float64.  Nothing here is shared with the HIP
+library.  Only tests, the smoke check and the benchmark's CPU-baseline leg may
+import this package; the product path never does.
+
+Parity status: every function below is pinned by tests/test_oracle_*.py
+against brute force, closed forms, invariants or library routines.  The paper
+prints no proximity, eigenvalue or MDS value for any worked example, so no
+paper-printed numbers are involved; the paper's MDS-correlation table needs its
+own data and forests and stays "parity unpinned" (context only).
+"""
+from __future__ import annotations
+
+import ctypes
+import subprocess
+from pathlib import Path
+from typing import Tuple
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_LIB_PATH = _HERE / "liboracle_core.so"
+_lib = None
+
+SQUARED = 0   # dissimilarity squared before double-centring (the paper's Step 1-2)
+LINEAR = 1    # 1 - P itself taken as the squared distance
+
+
+def build_core(force: bool = False) -> Path:
+    """Compiles oracle_core.c with gcc (in-tree)."""
+    src = _HERE / "oracle_core.c"
+    if force or not _LIB_PATH.exists() or _LIB_PATH.stat().st_mtime < src.stat().st_mtime:
+        subprocess.run(["gcc", "-O2", "-std=c99", "-fopenmp", "-Wall", "-shared", "-fPIC", str(src), "-o",
+                        str(_LIB_PATH)], check=True)
+    return _LIB_PATH
+
+
+def _core():
+    global _lib
+    if _lib is None:
+        build_core()
+        lib = ctypes.CDLL(str(_LIB_PATH))
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        lib.orc_leaf_assign.restype = ctypes.c_int
+        lib.orc_leaf_assign.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp]
+        lib.orc_counts_rows.restype = None
+        lib.orc_counts_rows.argtypes = [vp, i64, i32, i64, i64, vp]
+        lib.orc_oob_rows.restype = None
+        lib.orc_oob_rows.argtypes = [vp, vp, i64, i32, i64, i64, vp, vp]
+        lib.orc_pv_implicit.restype = ctypes.c_int
+        lib.orc_pv_implicit.argtypes = [vp, i64, i32, i64, vp, i32, vp]
+        lib.orc_pv_rows.restype = None
+        lib.orc_pv_rows.argtypes = [vp, i64, i32, i64, i64, vp, i32, vp]
+        _lib = lib
+    return _lib
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+# --------------------------------------------------------------------------- a1: leaf assignment
+def leaf_assign(forest, X) -> Tuple[np.ndarray, int]:
+    """Terminal node of every row of X in every tree (Methodology, "Threshold-based Splits":
+    x <= tau goes left, x > tau goes right; every sample, in-bag or not, is dropped down every tree).
+
+    Returns (leaf uint32 [B][N], summed path length over all (tree, row) pairs).
+    """
+    X = _c(X, np.float32)
+    N, M = X.shape
+    assert M == forest.n_features
+    B = forest.n_trees
+    leaf = np.empty((B, N), np.uint32)
+    plen = ctypes.c_int64(0)
+    rc = _core().orc_leaf_assign(B, _c(forest.node_offset, np.int64).ctypes.data,
+                                 _c(forest.feature, np.int32).ctypes.data,
+                                 _c(forest.threshold, np.float32).ctypes.data,
+                                 _c(forest.left, np.int32).ctypes.data, _c(forest.right, np.int32).ctypes.data,
+                                 _c(forest.leaf_id, np.int32).ctypes.data, X.ctypes.data, N, M, leaf.ctypes.data,
+                                 ctypes.addressof(plen))
+    if rc != 0:
+        raise ValueError("malformed forest: a walk left its tree")
+    return leaf, int(plen.value)
+
+
+# --------------------------------------------------------------------------- a2-a4: counts and proximities
+def counts_rows(leaf, i0: int, i1: int) -> np.ndarray:
+    """Rows i0..i1-1 of cnt(i,j) = #{b : node_b(i) = node_b(j)} (proximity equation, numerator)."""
+    leaf = _c(leaf, np.uint32)
+    B, N = leaf.shape
+    out = np.empty((i1 - i0, N), np.uint32)
+    _core().orc_counts_rows(leaf.ctypes.data, N, B, i0, i1, out.ctypes.data)
+    return out
+
+
+def counts_full(leaf) -> np.ndarray:
+    return counts_rows(leaf, 0, leaf.shape[1])
+
+
+def oob_rows(leaf, inbag, i0: int, i1: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Rows i0..i1-1 of the out-of-bag-only numerator and denominator ("Case-wise Bootstrap Tracking":
+    OOB_i is the set of trees whose bootstrap sample misses i; both samples must be out-of-bag)."""
+    leaf = _c(leaf, np.uint32)
+    inbag = _c(inbag, np.uint16)
+    B, N = leaf.shape
+    assert inbag.shape == (B, N)
+    num = np.empty((i1 - i0, N), np.uint32)
+    den = np.empty((i1 - i0, N), np.uint32)
+    _core().orc_oob_rows(leaf.ctypes.data, inbag.ctypes.data, N, B, i0, i1, num.ctypes.data, den.ctypes.data)
+    return num, den
+
+
+def normalise(cnt, B: int) -> np.ndarray:
+    """p = cnt / B in float32 IEEE division (proximity equation)."""
+    return (cnt.astype(np.float32) / np.float32(B)).astype(np.float32)
+
+
+def prox_oob_rows(num, den, i0: int) -> np.ndarray:
+    """Out-of-bag proximity rows: num/den in float32, 0 where no tree has both samples out-of-bag,
+    and 1 on the diagonal (row r of the block is sample i0 + r)."""
+    p = np.zeros(num.shape, np.float32)
+    m = den > 0
+    p[m] = num[m].astype(np.float32) / den[m].astype(np.float32)
+    r = np.arange(num.shape[0])
+    p[r, i0 + r] = np.float32(1.0)
+    return p
+
+
+def pack_upper(full) -> np.ndarray:
+    """Strict upper triangle, row-major: idx(i,j) = i*N - i(i+1)/2 + (j-i-1) for i < j
+    (n(n-1)/2 elements, "Packed Upper Triangle Storage")."""
+    N = full.shape[0]
+    iu = np.triu_indices(N, 1)
+    return np.ascontiguousarray(full[iu])
+
+
+# --------------------------------------------------------------------------- a5: products
+def pv_implicit(leaf, V) -> np.ndarray:
+    """Y = P V = (1/B) sum_b Z_b (Z_b^T V) in float64 without forming P."""
+    leaf = _c(leaf, np.uint32)
+    V = _c(V, np.float64)
+    B, N = leaf.shape
+    assert V.shape[0] == N
+    Y = np.empty_like(V)
+    rc = _core().orc_pv_implicit(leaf.ctypes.data, N, B, int(leaf.max()) + 1, V.ctypes.data, V.shape[1],
+                                 Y.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"orc_pv_implicit failed ({rc})")
+    return Y
+
+
+def pv_rows(leaf, V, i0: int, i1: int) -> np.ndarray:
+    """Rows i0..i1-1 of the dense product (1/B) sum_j cnt(i,j) V[j,:] in float64."""
+    leaf = _c(leaf, np.uint32)
+    V = _c(V, np.float64)
+    B, N = leaf.shape
+    Y = np.empty((i1 - i0, V.shape[1]), np.float64)
+    _core().orc_pv_rows(leaf.ctypes.data, N, B, i0, i1, V.ctypes.data, V.shape[1], Y.ctypes.data)
+    return Y
+
+
+# --------------------------------------------------------------------------- a6: block power iteration
+def fix_signs(V) -> np.ndarray:
+    """Makes the largest-magnitude entry of every column positive."""
+    V = np.array(V, copy=True)
+    idx = np.argmax(np.abs(V), axis=0)
+    s = np.sign(V[idx, np.arange(V.shape[1])])
+    s[s == 0] = 1.0
+    return V * s
+
+
+def block_iteration(leaf, V0, T: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Top-k eigenpairs of P by block power iteration with exactly T applications of P, float64.
+
+    V <- orth(V0); T-1 times V <- orth(P V); then Y = P V, H = sym(V^T Y), H = W diag(theta) W^T
+    (descending), V <- V W.  orth is Householder QR.  P is symmetric positive semi-definite (a sum of
+    Gram matrices Z_b Z_b^T), so P ~ V diag(theta) V^T is the symmetric form of the paper's
+    low-rank factorisation P ~ Q U^T with Q = U = V diag(sqrt(theta)).
+    Returns (theta [k] descending, V [N][k]) with the sign convention of fix_signs.
+    """
+    V, _ = np.linalg.qr(np.asarray(V0, np.float64))
+    for _ in range(T - 1):
+        V, _ = np.linalg.qr(pv_implicit(leaf, V))
+    Y = pv_implicit(leaf, V)
+    H = V.T @ Y
+    H = 0.5 * (H + H.T)
+    theta, W = np.linalg.eigh(H)
+    order = np.argsort(theta)[::-1]
+    return theta[order], fix_signs(V @ W[:, order])
+
+
+def dense_eig(P, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Top-k eigenpairs of a materialised symmetric P by LAPACK (descending)."""
+    import scipy.linalg as sla
+    P = np.asarray(P, np.float64)
+    n = P.shape[0]
+    lam, U = sla.eigh(P, subset_by_index=[n - k, n - 1])
+    return lam[::-1].copy(), fix_signs(U[:, ::-1])
+
+
+def principal_angle(U, V) -> float:
+    """Largest principal angle (rad) between the column spans of U and V."""
+    Qu, _ = np.linalg.qr(np.asarray(U, np.float64))
+    Qv, _ = np.linalg.qr(np.asarray(V, np.float64))
+    # sin of the largest angle = norm of the part of Qu outside span(Qv); accurate for small angles
+    R = Qu - Qv @ (Qv.T @ Qu)
+    s = np.linalg.svd(R, compute_uv=False)
+    return float(np.arcsin(min(1.0, s[0])))
+
+
+# --------------------------------------------------------------------------- a7: INT8 factors
+def quantise_int8(V, lam) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-column symmetric INT8 codes of A = V diag(sqrt(lam)), all arithmetic in float32.
+
+    s_c = max_i |A_ic| / 127 (1 for an all-zero column); q = clamp(round-half-even(A / s_c), -127, 127).
+    The paper only names the encoding "INT8 (8-bit)" ("Low-Rank Factorization and Quantization
+    Trade-offs"); the per-column absmax scheme is this build's reading.
+    """
+    V = np.asarray(V, np.float32)
+    lam = np.asarray(lam, np.float32)
+    A = (V * np.sqrt(np.maximum(lam, np.float32(0.0)))[None, :]).astype(np.float32)
+    amax = np.max(np.abs(A), axis=0).astype(np.float32)
+    s = np.where(amax > 0, amax / np.float32(127.0), np.float32(1.0)).astype(np.float32)
+    q = np.rint((A / s[None, :]).astype(np.float32))
+    return np.clip(q, -127, 127).astype(np.int8), s
+
+
+def dequantise(Q, s) -> np.ndarray:
+    return Q.astype(np.float64) * np.asarray(s, np.float64)[None, :]
+
+
+# --------------------------------------------------------------------------- a8: 3-D MDS from the factors
+def double_centre(D2) -> np.ndarray:
+    """G = -1/2 H D2 H with H = I - 11^T/n (paper, MDS Step 2)."""
+    D2 = np.asarray(D2, np.float64)
+    n = D2.shape[0]
+    H = np.eye(n) - np.full((n, n), 1.0 / n)
+    return -0.5 * (H @ D2 @ H)
+
+
+def mds_gram_dense(A, mode: int = SQUARED) -> np.ndarray:
+    """Gram matrix of the scaling from P^ = A A^T (paper, MDS Steps 1-2).
+
+    D = max P - P with max P read as 1 (an exact proximity matrix has unit diagonal); SQUARED takes
+    D2 = D o D as the paper does, LINEAR takes D2 = D.
+    """
+    A = np.asarray(A, np.float64)
+    D = 1.0 - A @ A.T
+    return double_centre(D * D if mode == SQUARED else D)
+
+
+def mds_operator(A, mode: int = SQUARED):
+    """v -> G v in float64 using only the factor A (paper, MDS Step 3: u = H v, z = D2 u, w = H z,
+    G v = -w/2).  With p_ij = a_i . a_j and sum(u) = 0:
+    SQUARED: (1 - p)^2 = 1 - 2p + p^2, so z = -2 A (A^T u) + rowquad(A, A^T diag(u) A);
+    LINEAR:  z = -A (A^T u)."""
+    A = np.asarray(A, np.float64)
+
+    def apply(v):
+        v = np.asarray(v, np.float64)
+        u = v - v.mean(axis=0)
+        if mode == SQUARED:
+            if u.ndim == 1:
+                Mq = A.T @ (u[:, None] * A)
+                z = -2.0 * (A @ (A.T @ u)) + np.einsum("ik,kl,il->i", A, Mq, A)
+            else:
+                z = np.stack([-2.0 * (A @ (A.T @ u[:, c])) +
+                              np.einsum("ik,kl,il->i", A, A.T @ (u[:, c, None] * A), A)
+                              for c in range(u.shape[1])], axis=1)
+        else:
+            z = -(A @ (A.T @ u))
+        w = z - z.mean(axis=0)
+        return -0.5 * w
+
+    return apply
+
+
+def mds3d_dense(Q, s, mode: int = SQUARED, dims: int = 3) -> Tuple[np.ndarray, np.ndarray]:
+    """Classical (Torgerson) scaling from the INT8 factors: top `dims` eigenpairs of G by algebraic
+    value via LAPACK, coordinates x_i = sqrt(max(lam,0)) v_i (paper, MDS Step 4).  Small N only."""
+    G = mds_gram_dense(dequantise(Q, s), mode)
+    lam, U = np.linalg.eigh(0.5 * (G + G.T))
+    lam = lam[::-1][:dims].copy()
+    U = fix_signs(U[:, ::-1][:, :dims])
+    return U * np.sqrt(np.maximum(lam, 0.0))[None, :], lam
+
+
+def mds3d_implicit(Q, s, mode: int = SQUARED, dims: int = 3, tol: float = 1e-12) -> Tuple[np.ndarray, np.ndarray]:
+    """Same eigenpairs from the float64 implicit operator with ARPACK; for N too large to form G."""
+    import scipy.sparse.linalg as spla
+    A = dequantise(Q, s)
+    n = A.shape[0]
+    op = mds_operator(A, mode)
+    L = spla.LinearOperator((n, n), matvec=op, matmat=op, dtype=np.float64)
+    rng = np.random.default_rng(4242)
+    lam, U = spla.eigsh(L, k=dims, which="LA", tol=tol, v0=rng.standard_normal(n))
+    order = np.argsort(lam)[::-1]
+    lam = lam[order]
+    U = fix_signs(U[:, order])
+    return U * np.sqrt(np.maximum(lam, 0.0))[None, :], lam

@@ -1,0 +1,163 @@
+"""Pins for the oracle's products, block iteration, INT8 factors and 3-D scaling."""
+import numpy as np
+import pytest
+
+import oracle
+import rfx_inputs as ri
+
+
+def test_implicit_product_equals_dense_product(cfg1, small2):
+    for d, k in ((cfg1, 5), (small2, 8)):
+        leaf = d["leaf"]
+        B, N = leaf.shape
+        V = ri.start_block(N, k).astype(np.float64)
+        P = oracle.counts_full(leaf).astype(np.float64) / B
+        ref = P @ V                                            # library product on the materialised matrix
+        Y = oracle.pv_implicit(leaf, V)
+        np.testing.assert_allclose(Y, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+        rows = oracle.pv_rows(leaf, V, 10, 25)
+        np.testing.assert_allclose(rows, ref[10:25], rtol=0, atol=1e-12 * np.abs(ref).max())
+
+
+def test_product_with_ones_is_the_leaf_size_sum(small2):
+    """B * (P 1)_i = sum_b |leaf_b(i)|, an exact integer."""
+    leaf = small2["leaf"]
+    B, N = leaf.shape
+    Y = oracle.pv_implicit(leaf, np.ones((N, 1)))
+    sizes = np.zeros(N, np.int64)
+    for b in range(B):
+        sizes += np.bincount(leaf[b])[leaf[b]]
+    np.testing.assert_array_equal(np.rint(Y[:, 0] * B).astype(np.int64), sizes)
+    assert np.abs(Y[:, 0] * B - sizes).max() < 1e-7
+
+
+def test_product_is_linear_symmetric_psd(cfg1):
+    leaf = cfg1["leaf"]
+    N = leaf.shape[1]
+    rng = np.random.default_rng(5)
+    u, v = rng.standard_normal((N, 1)), rng.standard_normal((N, 1))
+    Pu, Pv = oracle.pv_implicit(leaf, u), oracle.pv_implicit(leaf, v)
+    np.testing.assert_allclose(oracle.pv_implicit(leaf, 2 * u - 3 * v), 2 * Pu - 3 * Pv, atol=1e-12)
+    assert float((u * Pv).sum()) == pytest.approx(float((Pu * v).sum()), rel=1e-12)
+    assert float((v * Pv).sum()) >= 0.0
+
+
+def test_block_iteration_converges_to_lapack(cfg1):
+    leaf = cfg1["leaf"]
+    B, N = leaf.shape
+    P = oracle.counts_full(leaf).astype(np.float64) / B
+    lam_all = np.linalg.eigvalsh(P)[::-1]
+    assert lam_all.sum() == pytest.approx(N, rel=1e-12)            # trace P = N
+    assert lam_all.min() > -1e-10                                   # P is positive semi-definite
+    assert lam_all[0] <= P.sum(axis=1).max() + 1e-9
+    assert (lam_all ** 2).sum() == pytest.approx((P ** 2).sum(), rel=1e-12)
+
+    k = 8
+    lam_d, U_d = oracle.dense_eig(P, k)
+    np.testing.assert_allclose(lam_d, lam_all[:k], rtol=1e-12)
+    # enough applications of P that the leading three pairs have converged
+    lam, V = oracle.block_iteration(leaf, ri.start_block(N, k), T=60)
+    np.testing.assert_allclose(V.T @ V, np.eye(k), atol=1e-12)
+    np.testing.assert_allclose(lam[:3], lam_d[:3], rtol=1e-9)
+    assert oracle.principal_angle(V[:, :3], U_d[:, :3]) < 1e-4
+    assert (lam <= lam_d + 1e-10).all()                              # Ritz values never exceed eigenvalues
+    # a full-width block spans everything: Ritz values are the spectrum after one application
+    lam_f, _ = oracle.block_iteration(leaf, ri.start_block(N, N), T=1)
+    np.testing.assert_allclose(lam_f, lam_all, atol=1e-10)
+
+
+def test_block_iteration_counts_applications(monkeypatch, cfg1):
+    calls = []
+    real = oracle.pv_implicit
+    monkeypatch.setattr(oracle, "pv_implicit", lambda l, v: calls.append(1) or real(l, v))
+    oracle.block_iteration(cfg1["leaf"], ri.start_block(178, 4), T=5)
+    assert len(calls) == 5
+
+
+def test_principal_angle():
+    e = np.eye(4)
+    assert oracle.principal_angle(e[:, :2], e[:, :2] @ np.array([[0, 1], [1, 0.0]])) < 1e-12
+    t = 1e-4
+    U = np.stack([e[:, 0], np.cos(t) * e[:, 1] + np.sin(t) * e[:, 2]], axis=1)
+    assert oracle.principal_angle(e[:, :2], U) == pytest.approx(t, rel=1e-6)
+    assert oracle.principal_angle(e[:, :1], e[:, 1:2]) == pytest.approx(np.pi / 2)
+
+
+def test_int8_quantisation():
+    # ties go to the even code; the column maximum maps to +-127
+    V = np.array([[127.0, -2.0], [0.5, 1.0], [1.5, 0.25], [2.5, 0.0], [-0.5, 0.5], [-3.5, 2.0]], np.float32)
+    Q, s = oracle.quantise_int8(V, np.ones(2, np.float32))
+    assert s[0] == np.float32(1.0) and s[1] == np.float32(2.0) / np.float32(127.0)
+    np.testing.assert_array_equal(Q[:, 0], [127, 0, 2, 2, 0, -4])
+    assert Q[0, 1] == -127 and Q[5, 1] == 127
+    # eigenvalue scaling: A = V sqrt(lam)
+    Q2, s2 = oracle.quantise_int8(V, np.array([4.0, 0.0], np.float32))
+    assert s2[0] == np.float32(2.0) and s2[1] == np.float32(1.0) and (Q2[:, 1] == 0).all()
+    np.testing.assert_array_equal(Q2[:, 0], Q[:, 0])
+
+    rng = np.random.default_rng(9)
+    V = rng.standard_normal((1000, 6)).astype(np.float32)
+    lam = rng.uniform(0.1, 50, 6).astype(np.float32)
+    Q, s = oracle.quantise_int8(V, lam)
+    A = V.astype(np.float64) * np.sqrt(lam.astype(np.float64))
+    assert Q.dtype == np.int8 and (np.abs(Q).max(axis=0) == 127).all()
+    assert (np.abs(oracle.dequantise(Q, s) - A) <= 0.5 * s * (1 + 1e-5)).all()
+
+
+def test_double_centring_recovers_a_euclidean_configuration():
+    """Torgerson scaling: for squared Euclidean distances, -1/2 H D2 H is the Gram matrix of the
+    centred points, and the embedding reproduces every pairwise distance."""
+    rng = np.random.default_rng(2)
+    Xp = rng.standard_normal((40, 3)) * [3.0, 2.0, 0.5]
+    D2 = ((Xp[:, None] - Xp[None]) ** 2).sum(-1)
+    G = oracle.double_centre(D2)
+    Xc = Xp - Xp.mean(0)
+    np.testing.assert_allclose(G, Xc @ Xc.T, atol=1e-10)
+
+
+def test_mds_linear_mode_embeds_factor_rows():
+    # LINEAR: G = 1/2 H A A^T H = 1/2 (HA)(HA)^T, so with k = 3 the 3-D embedding is exact:
+    # |x_i - x_j|^2 = |a_i - a_j|^2 / 2
+    rng = np.random.default_rng(1)
+    A = rng.standard_normal((60, 3))
+    s = np.abs(A).max(axis=0) / 127
+    Q = np.rint(A / s).astype(np.int8)
+    Ah = oracle.dequantise(Q, s)
+    coords, lam = oracle.mds3d_dense(Q, s, oracle.LINEAR)
+    d_true = np.linalg.norm(Ah[:, None] - Ah[None], axis=-1) / np.sqrt(2.0)
+    d_emb = np.linalg.norm(coords[:, None] - coords[None], axis=-1)
+    np.testing.assert_allclose(d_emb, d_true, atol=1e-8)
+    Ac = Ah - Ah.mean(0)
+    np.testing.assert_allclose(lam, np.linalg.eigvalsh(0.5 * Ac.T @ Ac)[::-1], rtol=1e-10)
+
+
+@pytest.mark.parametrize("mode", [oracle.SQUARED, oracle.LINEAR])
+def test_mds_operator_and_invariants(cfg1, mode):
+    leaf = cfg1["leaf"]
+    N = leaf.shape[1]
+    lam, V = oracle.block_iteration(leaf, ri.start_block(N, 12), T=20)
+    Q, s = oracle.quantise_int8(V, lam)
+    A = oracle.dequantise(Q, s)
+    G = oracle.mds_gram_dense(A, mode)
+    # brute-force entries of G from the definition
+    D2 = (1 - A @ A.T) ** (2 if mode == oracle.SQUARED else 1)
+    i, j = 3, 77
+    g = -0.5 * (D2[i, j] - D2[i].mean() - D2[:, j].mean() + D2.mean())
+    assert G[i, j] == pytest.approx(g, abs=1e-12)
+    # the implicit operator is the dense matrix
+    op = oracle.mds_operator(A, mode)
+    Vt = np.random.default_rng(0).standard_normal((N, 4))
+    np.testing.assert_allclose(op(Vt), G @ Vt, atol=1e-10)
+    np.testing.assert_allclose(op(Vt[:, 0]), G @ Vt[:, 0], atol=1e-10)
+    coords, ev = oracle.mds3d_dense(Q, s, mode)
+    assert coords.shape == (N, 3)
+    np.testing.assert_allclose(coords.sum(axis=0), 0, atol=1e-9)           # centred
+    gram = coords.T @ coords
+    np.testing.assert_allclose(gram, np.diag(ev), atol=1e-9)               # orthogonal, |col|^2 = lambda
+    np.testing.assert_allclose(ev, np.linalg.eigvalsh(G)[::-1][:3], rtol=1e-12)
+    c2, ev2 = oracle.mds3d_implicit(Q, s, mode)
+    np.testing.assert_allclose(ev2, ev, rtol=1e-9)
+    if min(ev[0] - ev[1], ev[1] - ev[2]) > 1e-3 * ev[0]:
+        np.testing.assert_allclose(c2, coords, atol=1e-6 * np.abs(coords).max())
+    if mode == oracle.LINEAR:
+        assert np.linalg.eigvalsh(G).min() > -1e-10                         # 1/2 H P^ H is PSD
