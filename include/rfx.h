@@ -1,0 +1,188 @@
+/* rfx.h -- C ABI of librfx: the random-forest proximity path on one MI355X (gfx950).
+ *
+ * The library computes, for a grown Breiman-Cutler classification forest,
+ *   1. the terminal node of every sample in every tree,
+ *   2. the dense proximity matrix p(i,j) = (1/B) #{b : node_b(i) = node_b(j)} and its
+ *      out-of-bag-only variant,
+ *   3. a rank-k factorisation of P obtained without forming P, quantised to INT8, and
+ *      3-D scaling coordinates computed from those factors.
+ * Citations name sections / equations of the RFX paper (arXiv 2511.19493).
+ *
+ * Conventions
+ *   - Every function returns an int status: RFX_OK (0) or a negative RFX_ERR_* code.  No
+ *     exception or abort crosses this boundary.  rfx_last_error() returns a thread-local
+ *     message for the last failing call on the calling thread.
+ *   - Pointers marked [device] are device (HBM) addresses owned by the caller; the library
+ *     neither frees nor keeps them after the call returns.  Pointers marked [host] are host
+ *     addresses.  All arrays are dense, row-major, with the index order written in brackets.
+ *   - `stream` is a hipStream_t passed as void* (null = the default stream).  Work is
+ *     enqueued on that stream in order.  Calls documented as "asynchronous" return before
+ *     the work has finished and their outputs are valid once the caller has synchronised
+ *     the stream; the others synchronise the stream before returning.
+ *   - Scratch memory is allocated and freed by the library inside the call (hipMalloc /
+ *     hipFree), except for plans and forests, which own theirs until destroyed.
+ *   - Arguments are validated on the host before anything is launched; a call that
+ *     returns an error has launched nothing that writes caller memory.
+ */
+#ifndef RFX_H
+#define RFX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RFX_OK 0
+#define RFX_ERR_INVALID_ARG (-1) /* a size, enum or combination of arguments is out of range */
+#define RFX_ERR_NULL (-2)        /* a required pointer is null */
+#define RFX_ERR_OVERFLOW (-3)    /* a count does not fit the requested output type */
+#define RFX_ERR_OOM (-4)         /* device or host allocation failed */
+#define RFX_ERR_HIP (-5)         /* a HIP runtime call failed (message has the HIP error) */
+#define RFX_ERR_UNSUPPORTED (-6) /* valid request outside what this build implements */
+#define RFX_ERR_FOREST (-7)      /* the forest description is malformed */
+
+/* count_dtype */
+#define RFX_U16 0
+#define RFX_U32 1
+/* layout of an N x N symmetric output */
+#define RFX_FULL 0         /* [N][N]: both triangles and the diagonal */
+#define RFX_UPPER_PACKED 1 /* strict upper triangle, row-major, N(N-1)/2 entries:
+                              idx(i,j) = i*N - i(i+1)/2 + (j-i-1) for i < j
+                              ("Packed Upper Triangle Storage") */
+/* dissim_mode of rfx_mds3d */
+#define RFX_MDS_SQUARED 0 /* D = 1 - P squared element-wise before double-centring (MDS Steps 1-2) */
+#define RFX_MDS_LINEAR 1  /* 1 - P itself taken as the squared distance */
+
+const char* rfx_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Forest: flattened trees ("Flattened arrays": per-node split variable, split value, child
+ * pointers and node status, concatenated over trees).  All pointers [host].
+ * Tree b owns nodes [node_offset[b], node_offset[b+1]); its root is local node 0; child
+ * indices are tree-local.  A node is a leaf iff feature < 0; then leaf_id is its dense index
+ * in 0..n_leaves[b]-1.  Internal nodes send a sample left iff x[feature] <= threshold, right
+ * otherwise ("Threshold-based Splits"); a NaN feature value therefore goes right.
+ */
+typedef struct {
+    int32_t n_trees;            /* B >= 1 */
+    int32_t n_features;         /* M >= 1 */
+    const int64_t* node_offset; /* [B+1] */
+    const int32_t* feature;     /* [nodes] */
+    const float* threshold;     /* [nodes] */
+    const int32_t* left;        /* [nodes] */
+    const int32_t* right;       /* [nodes] */
+    const int32_t* leaf_id;     /* [nodes] */
+    const int32_t* n_leaves;    /* [B] */
+} rfx_forest_desc;
+
+typedef struct rfx_forest rfx_forest;
+
+/* Validates the description (every tree is a proper binary tree reachable from its root,
+ * indices in range, leaf ids dense), re-lays each tree breadth-first with sibling pairs
+ * adjacent, and uploads it to the current device.  Synchronous.  The handle owns its device
+ * copy; the description's arrays may be freed after the call.
+ * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_FOREST, RFX_ERR_UNSUPPORTED (feature
+ * index and child index of some tree do not fit one 32-bit word together), RFX_ERR_OOM. */
+int rfx_forest_create(const rfx_forest_desc* desc, rfx_forest** out);
+int rfx_forest_destroy(rfx_forest* forest);
+/* Largest n_leaves over the trees: an exclusive upper bound on every leaf id the forest can
+ * emit, to be passed as `leaf_bound` below. */
+int32_t rfx_forest_leaf_bound(const rfx_forest* forest);
+
+/* Leaf assignment: leaf[b*N + i] = dense leaf index of sample i in tree b, for every tree and
+ * every sample, in-bag or not ("for each tree, terminal node assignments are computed for all
+ * samples", CPU Proximity Computation; traversal rule: "Threshold-based Splits").
+ *   X    [device] float32 [N][M] row-major samples, M == forest n_features
+ *   leaf [device] uint32 [B][N] out
+ * Asynchronous.  Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG (N < 1, M mismatch). */
+int rfx_leaf_assign(const rfx_forest* forest, const float* X, int64_t N, int32_t M, uint32_t* leaf,
+                    void* stream);
+
+/* Dense proximity (equation p(i,j) = (1/B) sum_b I(node_b(i) = node_b(j)), "Proximity
+ * Matrices").
+ *   leaf        [device] uint32 [B][N], every entry < leaf_bound
+ *   leaf_bound  exclusive upper bound on the leaf ids, 1..2^24; ids >= leaf_bound give wrong
+ *               counts (never a memory fault)
+ *   count_dtype RFX_U16 (requires B <= 65535) or RFX_U32
+ *   layout      RFX_FULL or RFX_UPPER_PACKED, applies to both outputs
+ *   counts      [device] nullable; cnt(i,j) = #{b : leaf_b(i) = leaf_b(j)}; diagonal = B
+ *   prox        [device] nullable float32; cnt / B in IEEE float32 division; diagonal = 1
+ * At least one of counts / prox must be given.  Asynchronous apart from scratch management
+ * (the call returns after its kernels have finished).
+ * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_OVERFLOW, RFX_ERR_OOM. */
+int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
+                   void* counts, float* prox, void* stream);
+
+/* Out-of-bag-only proximity.  With c_b(i) the bootstrap in-bag count of sample i in tree b
+ * and OOB_i = {b : c_b(i) = 0} ("Case-wise Bootstrap Tracking"):
+ *   num(i,j) = #{b in OOB_i and OOB_j : leaf_b(i) = leaf_b(j)},  den(i,j) = |OOB_i and OOB_j|,
+ *   prox(i,j) = num/den in IEEE float32 division, 0 where den = 0, 1 on the diagonal.
+ *   inbag [device] uint16 [B][N];  num, den, prox [device] nullable (at least one given);
+ *   other arguments as rfx_prox_dense.  Diagonal of num and den in RFX_FULL = |OOB_i|. */
+int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
+                 int count_dtype, int layout, void* num, void* den, float* prox, void* stream);
+
+/* Implicit product Y = P V = (1/B) sum_b Z_b (Z_b^T V), Z_b the N x L_b one-hot leaf
+ * membership of tree b, i.e. Y[i,:] = (1/B) sum_b sum_{j : leaf_b(j) = leaf_b(i)} V[j,:];
+ * P is never formed.  A plan holds the per-tree grouping of samples by leaf (built once per
+ * forest) and the scratch for the per-leaf sums.
+ *   rfx_pv_plan_create: leaf [device] uint32 [B][N] (read during the call only), ids < leaf_bound.
+ *   rfx_pv_apply:       V [device] float32 [N][k] in, Y [device] float32 [N][k] out, 1 <= k <= 256,
+ *                       V and Y must not overlap.  Asynchronous once the plan's scratch has
+ *                       been sized for k (first call with a larger k allocates).
+ *   rfx_prox_matvec:    one-shot convenience: create plan, apply, destroy.  Synchronous. */
+typedef struct rfx_pv_plan rfx_pv_plan;
+int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, rfx_pv_plan** out,
+                       void* stream);
+int rfx_pv_plan_destroy(rfx_pv_plan* plan);
+int rfx_pv_apply(rfx_pv_plan* plan, const float* V, int32_t k, float* Y, void* stream);
+int rfx_prox_matvec(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const float* V, int32_t k,
+                    float* Y, void* stream);
+
+/* Rank-k factorisation of P by block power iteration, then INT8 factors.
+ * P is symmetric positive semi-definite, so the paper's P ~ Q U^T ("QLORA", "Low-Rank
+ * Factorization and Quantization Trade-offs") is taken in its symmetric form P ~ A A^T with
+ * A = V diag(sqrt(lambda)).  Steps: V <- orth(V0); iters-1 times V <- orth(P V); then
+ * Y = P V, H = sym(V^T Y), H = W diag(theta) W^T (theta descending), V <- V W: exactly
+ * `iters` applications of P.  Each column of V is then signed so that its largest-magnitude
+ * entry is positive, and quantised: s_c = max_i |A_ic| / 127 (1 if the column is zero),
+ * Q_ic = clamp(round-half-even(A_ic / s_c), -127, 127), all in float32.
+ *   V0      [device] float32 [N][k] start block (full column rank)
+ *   eigvals [device] float32 [k] out, descending Ritz values
+ *   V       [device] float32 [N][k] out, orthonormal Ritz vectors (before quantisation)
+ *   Q       [device] int8 [N][k] out, nullable together with scales
+ *   scales  [device] float32 [k] out
+ * 1 <= k <= 128, k <= N, iters >= 1.  Synchronous. */
+int rfx_prox_lowrank(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t k, int32_t iters,
+                     const float* V0, float* eigvals, float* V, int8_t* Q, float* scales, void* stream);
+
+/* The quantisation step of rfx_prox_lowrank on its own (same arithmetic).  Asynchronous. */
+int rfx_quantise_int8(const float* V, const float* eigvals, int64_t N, int32_t k, int8_t* Q, float* scales,
+                      void* stream);
+
+/* 3-D scaling coordinates from the INT8 factors ("GPU-Accelerated 3D MDS from Low-Rank
+ * Proximity Matrices", Steps 1-4).  With A^ = Q diag(scales), P^ = A^ A^^T and D = 1 - P^ (the
+ * paper's max P - P with max P = 1): G = -1/2 H D2 H, H = I - 11^T/N, D2 = D o D
+ * (RFX_MDS_SQUARED) or D (RFX_MDS_LINEAR).  G is applied through the factors only
+ * (u = H v, z = D2 u, w = H z, G v = -w/2).  The three algebraically largest eigenpairs are
+ * found by simultaneous power iteration on a block of m vectors with a Rayleigh-Ritz step
+ * (the power method with deflation of Step 3, done for all vectors at once); coordinates are
+ * x_i = (sqrt(l1) v1_i, sqrt(l2) v2_i, sqrt(l3) v3_i), a non-positive eigenvalue giving a zero
+ * column; each column is signed so that its largest-magnitude entry is positive.
+ *   Q [device] int8 [N][k], scales [device] float32 [k], 1 <= k <= 128
+ *   m          block width, 3..16 (extra vectors speed up convergence)
+ *   x0         [device] float32 [N][m] start block
+ *   max_iters  >= 1; tol: stop when the three leading Ritz values change by less than
+ *              tol * |value| between two checks
+ *   coords     [device] float32 [N][3] out;  eigvals [device] float32 [3] out
+ *   iters_done [host] nullable out: applications of G performed
+ * Synchronous. */
+int rfx_mds3d(const int8_t* Q, const float* scales, int64_t N, int32_t k, int dissim_mode, int32_t m,
+              int32_t max_iters, float tol, const float* x0, float* coords, float* eigvals,
+              int32_t* iters_done, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RFX_H */

@@ -1,0 +1,265 @@
+"""Thin Python binding of librfx (random-forest proximity path, HIP kernels for gfx950).
+
+Argument marshalling only: every computation runs in the library's kernels.  Tensors are
+torch CUDA tensors used as device buffers; work is enqueued on torch's current stream.
+Function names and arguments mirror include/rfx.h.  Importing the package does not load the
+library; the first call does, and raises if it has not been built
+(`python -m paper_2511_19493_amd.build`).
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional, Tuple
+
+import numpy as np
+
+_LIB_PATH = Path(__file__).resolve().parent / "lib" / "librfx.so"
+_lib = None
+
+U16, U32 = 0, 1
+FULL, UPPER_PACKED = 0, 1
+MDS_SQUARED, MDS_LINEAR = 0, 1
+
+EXPORTS = (
+    "rfx_last_error", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
+    "rfx_prox_dense", "rfx_prox_oob", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
+    "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d",
+)
+
+
+class RfxError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"librfx error {code}: {msg}")
+        self.code = code
+
+
+class _ForestDesc(ctypes.Structure):
+    _fields_ = [("n_trees", ctypes.c_int32), ("n_features", ctypes.c_int32), ("node_offset", ctypes.c_void_p),
+                ("feature", ctypes.c_void_p), ("threshold", ctypes.c_void_p), ("left", ctypes.c_void_p),
+                ("right", ctypes.c_void_p), ("leaf_id", ctypes.c_void_p), ("n_leaves", ctypes.c_void_p)]
+
+
+def lib_path() -> Path:
+    return _LIB_PATH
+
+
+def load():
+    """Loads librfx.so; raises if it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise RuntimeError(f"{_LIB_PATH} not built: run `python -m paper_2511_19493_amd.build`")
+        lib = ctypes.CDLL(str(_LIB_PATH))
+        vp, i64, i32, ci, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int, ctypes.c_float
+        lib.rfx_last_error.restype = ctypes.c_char_p
+        lib.rfx_last_error.argtypes = []
+        sigs = {
+            "rfx_forest_create": [ctypes.POINTER(_ForestDesc), ctypes.POINTER(vp)],
+            "rfx_forest_destroy": [vp],
+            "rfx_leaf_assign": [vp, vp, i64, i32, vp, vp],
+            "rfx_prox_dense": [vp, i64, i32, i32, ci, ci, vp, vp, vp],
+            "rfx_prox_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp],
+            "rfx_pv_plan_create": [vp, i64, i32, i32, ctypes.POINTER(vp), vp],
+            "rfx_pv_plan_destroy": [vp],
+            "rfx_pv_apply": [vp, vp, i32, vp, vp],
+            "rfx_prox_matvec": [vp, i64, i32, i32, vp, i32, vp, vp],
+            "rfx_prox_lowrank": [vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp],
+            "rfx_quantise_int8": [vp, vp, i64, i32, vp, vp, vp],
+            "rfx_mds3d": [vp, vp, i64, i32, ci, i32, i32, f32, vp, vp, vp, ctypes.POINTER(i32), vp],
+        }
+        for name, args in sigs.items():
+            fn = getattr(lib, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = args
+        lib.rfx_forest_leaf_bound.restype = ctypes.c_int32
+        lib.rfx_forest_leaf_bound.argtypes = [vp]
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise RfxError(rc, load().rfx_last_error().decode())
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t, dtype, shape=None) -> int:
+    """Device address of a contiguous CUDA tensor of the given dtype (and shape)."""
+    if t is None:
+        return 0
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype:
+        raise TypeError(f"expected a contiguous CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+class Forest:
+    """Device-resident forest (rfx_forest_create / rfx_forest_destroy)."""
+
+    def __init__(self, n_features: int, node_offset, feature, threshold, left, right, leaf_id, n_leaves):
+        arrs = [np.ascontiguousarray(node_offset, np.int64), np.ascontiguousarray(feature, np.int32),
+                np.ascontiguousarray(threshold, np.float32), np.ascontiguousarray(left, np.int32),
+                np.ascontiguousarray(right, np.int32), np.ascontiguousarray(leaf_id, np.int32),
+                np.ascontiguousarray(n_leaves, np.int32)]
+        self.n_trees = len(arrs[6])
+        self.n_features = int(n_features)
+        d = _ForestDesc(self.n_trees, self.n_features, *(a.ctypes.data for a in arrs))
+        h = ctypes.c_void_p()
+        _check(load().rfx_forest_create(ctypes.byref(d), ctypes.byref(h)))
+        self._h = h
+
+    @property
+    def leaf_bound(self) -> int:
+        return int(load().rfx_forest_leaf_bound(self._h))
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load().rfx_forest_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def leaf_assign(forest: Forest, X, leaf=None):
+    """rfx_leaf_assign: X float32 [N][M] -> leaf uint32 [B][N] (stored in an int32 tensor)."""
+    import torch
+    N, M = X.shape
+    if leaf is None:
+        leaf = torch.empty((forest.n_trees, N), dtype=torch.int32, device=X.device)
+    _check(load().rfx_leaf_assign(forest._h, _dev(X, torch.float32), N, M,
+                                  _dev(leaf, torch.int32, (forest.n_trees, N)), _stream()))
+    return leaf
+
+
+def _count_dtype(count_dtype):
+    import torch
+    return torch.int16 if count_dtype == U16 else torch.int32
+
+
+def _sym_shape(N: int, layout: int):
+    return (N, N) if layout == FULL else (N * (N - 1) // 2,)
+
+
+def prox_dense(leaf, leaf_bound: int, count_dtype: int = U32, layout: int = FULL, counts=None, prox=None,
+               want_counts: bool = True, want_prox: bool = True):
+    """rfx_prox_dense.  Counts come back in int16 / int32 tensors holding the uint16 / uint32 bits."""
+    import torch
+    B, N = leaf.shape
+    shp = _sym_shape(N, layout)
+    if counts is None and want_counts:
+        counts = torch.empty(shp, dtype=_count_dtype(count_dtype), device=leaf.device)
+    if prox is None and want_prox:
+        prox = torch.empty(shp, dtype=torch.float32, device=leaf.device)
+    _check(load().rfx_prox_dense(_dev(leaf, torch.int32), N, B, leaf_bound, count_dtype, layout,
+                                 _dev(counts, _count_dtype(count_dtype), shp) if counts is not None else 0,
+                                 _dev(prox, torch.float32, shp) if prox is not None else 0, _stream()))
+    return counts, prox
+
+
+def prox_oob(leaf, inbag, leaf_bound: int, count_dtype: int = U32, layout: int = FULL, want_prox: bool = True):
+    """rfx_prox_oob: returns (num, den, prox)."""
+    import torch
+    B, N = leaf.shape
+    shp = _sym_shape(N, layout)
+    num = torch.empty(shp, dtype=_count_dtype(count_dtype), device=leaf.device)
+    den = torch.empty(shp, dtype=_count_dtype(count_dtype), device=leaf.device)
+    prox = torch.empty(shp, dtype=torch.float32, device=leaf.device) if want_prox else None
+    _check(load().rfx_prox_oob(_dev(leaf, torch.int32), _dev(inbag, torch.int16, (B, N)), N, B, leaf_bound,
+                               count_dtype, layout, num.data_ptr(), den.data_ptr(),
+                               prox.data_ptr() if prox is not None else 0, _stream()))
+    return num, den, prox
+
+
+class PvPlan:
+    """rfx_pv_plan_create / rfx_pv_apply / rfx_pv_plan_destroy."""
+
+    def __init__(self, leaf, leaf_bound: int):
+        import torch
+        B, N = leaf.shape
+        self.N, self.B = N, B
+        h = ctypes.c_void_p()
+        _check(load().rfx_pv_plan_create(_dev(leaf, torch.int32), N, B, leaf_bound, ctypes.byref(h), _stream()))
+        self._h = h
+
+    def apply(self, V, Y=None):
+        import torch
+        N, k = V.shape
+        if N != self.N:
+            raise ValueError("V has the wrong number of rows")
+        if Y is None:
+            Y = torch.empty_like(V)
+        _check(load().rfx_pv_apply(self._h, _dev(V, torch.float32), k, _dev(Y, torch.float32, (N, k)), _stream()))
+        return Y
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load().rfx_pv_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def prox_matvec(leaf, leaf_bound: int, V):
+    """rfx_prox_matvec: one P.V without a persistent plan."""
+    import torch
+    B, N = leaf.shape
+    k = V.shape[1]
+    Y = torch.empty_like(V)
+    _check(load().rfx_prox_matvec(_dev(leaf, torch.int32), N, B, leaf_bound, _dev(V, torch.float32, (N, k)), k,
+                                  Y.data_ptr(), _stream()))
+    return Y
+
+
+def prox_lowrank(leaf, leaf_bound: int, V0, iters: int, quantise: bool = True):
+    """rfx_prox_lowrank: returns (eigvals [k], V [N][k], Q int8 [N][k] or None, scales [k] or None)."""
+    import torch
+    B, N = leaf.shape
+    k = V0.shape[1]
+    dev = leaf.device
+    eig = torch.empty(k, dtype=torch.float32, device=dev)
+    V = torch.empty((N, k), dtype=torch.float32, device=dev)
+    Q = torch.empty((N, k), dtype=torch.int8, device=dev) if quantise else None
+    s = torch.empty(k, dtype=torch.float32, device=dev) if quantise else None
+    _check(load().rfx_prox_lowrank(_dev(leaf, torch.int32), N, B, leaf_bound, k, iters,
+                                   _dev(V0, torch.float32, (N, k)), eig.data_ptr(), V.data_ptr(),
+                                   Q.data_ptr() if quantise else 0, s.data_ptr() if quantise else 0, _stream()))
+    return eig, V, Q, s
+
+
+def quantise_int8(V, eigvals):
+    """rfx_quantise_int8: returns (Q int8 [N][k], scales float32 [k])."""
+    import torch
+    N, k = V.shape
+    Q = torch.empty((N, k), dtype=torch.int8, device=V.device)
+    s = torch.empty(k, dtype=torch.float32, device=V.device)
+    _check(load().rfx_quantise_int8(_dev(V, torch.float32), _dev(eigvals, torch.float32, (k,)), N, k, Q.data_ptr(),
+                                    s.data_ptr(), _stream()))
+    return Q, s
+
+
+def mds3d(Q, scales, x0, mode: int = MDS_SQUARED, max_iters: int = 300, tol: float = 1e-6) -> Tuple:
+    """rfx_mds3d: returns (coords float32 [N][3], eigvals float32 [3], iterations done)."""
+    import torch
+    N, k = Q.shape
+    m = x0.shape[1]
+    coords = torch.empty((N, 3), dtype=torch.float32, device=Q.device)
+    ev = torch.empty(3, dtype=torch.float32, device=Q.device)
+    it = ctypes.c_int32(0)
+    _check(load().rfx_mds3d(_dev(Q, torch.int8), _dev(scales, torch.float32, (k,)), N, k, mode, m, max_iters, tol,
+                            _dev(x0, torch.float32, (N, m)), coords.data_ptr(), ev.data_ptr(), ctypes.byref(it),
+                            _stream()))
+    return coords, ev, int(it.value)

@@ -1,0 +1,39 @@
+// Small dense linear algebra on device used by the block iterations: k x k Gram matrices of
+// tall N x k blocks, Cholesky factor and its inverse, symmetric eigen-decomposition (cyclic
+// Jacobi), and tall-times-small products.  All reductions and k x k work are float64; tall
+// blocks are float32 in memory.  Host-side launch wrappers; every call is asynchronous on `st`.
+#pragma once
+
+#include "common.h"
+
+namespace rfx {
+
+constexpr int kMaxRank = 128;  // largest block width the small-matrix kernels are built for
+
+// Scratch shared by the wrappers below, sized for N rows and width k.
+struct SmallWs {
+    double* partial = nullptr;  // [gram_blocks][k][k]
+    double* G = nullptr;        // [k][k]
+    double* T = nullptr;        // [k][k]
+    double* theta = nullptr;    // [k]
+    double* W = nullptr;        // [k][k]
+    int* flag = nullptr;        // device status word (non-positive Cholesky pivot)
+    int gram_blocks = 0;
+    DevBuf buf;
+    hipError_t alloc(int64_t N, int k);
+};
+
+// G = A^T Bm (k x k, float64), A and Bm float32 [N][k]; symmetrised (G + G^T)/2 if sym.
+int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& ws, double* G, hipStream_t st);
+// T = inverse of the upper Cholesky factor R of G (G = R^T R); sets *ws.flag on a bad pivot.
+int chol_inverse(const double* G, int k, SmallWs& ws, double* T, hipStream_t st);
+// Eigen-decomposition of the symmetric k x k matrix H: theta descending, W columns = vectors.
+int jacobi_eigh(const double* H, int k, SmallWs& ws, double* theta, double* W, hipStream_t st);
+// Out = A T with A float32 [N][k], T float64 [k][kout] (row stride k), Out float32 [N][kout].
+int apply_small(const float* A, int64_t N, int k, const double* T, int kout, float* Out, hipStream_t st);
+// Two passes of Cholesky QR: V = orthonormal basis of span(Y); Z is an [N][k] temporary.
+int orthonormalise(const float* Y, int64_t N, int k, SmallWs& ws, float* Z, float* V, hipStream_t st);
+// Flips every column of V [N][kc] so that its largest-magnitude entry (first one on ties) is positive.
+int fix_signs(float* V, int64_t N, int kc, hipStream_t st);
+
+}  // namespace rfx

@@ -1,0 +1,355 @@
+// Small dense linear algebra for the block iterations (see dense_small.h).
+#include "dense_small.h"
+
+#include <algorithm>
+
+namespace rfx {
+namespace {
+
+constexpr int kGramRows = 32;   // rows staged per step by the Gram kernel
+constexpr int kApplyRows = 32;  // rows per workgroup step of the tall-times-small product
+
+// partial[block][p][q] = sum over the block's rows of A[i][p] * Bm[i][q], float64 accumulation.
+// Thread (ty, tx) of a 16 x 16 workgroup owns entries p = ty + 16u, q = tx + 16v.
+template <int NB>
+__global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restrict__ A, const float* __restrict__ Bm,
+                                                          int64_t N, int k, int64_t rows_per_block,
+                                                          double* __restrict__ partial) {
+    extern __shared__ float gram_sm[];
+    float* As = gram_sm;
+    float* Bs = gram_sm + kGramRows * k;
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    double acc[NB][NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u)
+#pragma unroll
+        for (int v = 0; v < NB; ++v) acc[u][v] = 0.0;
+    const int64_t i_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t i_end = min(N, i_begin + rows_per_block);
+    for (int64_t i0 = i_begin; i0 < i_end; i0 += kGramRows) {
+        const int rows = (int)min((int64_t)kGramRows, i_end - i0);
+        for (int idx = threadIdx.x; idx < rows * k; idx += 256) {
+            As[idx] = A[i0 * k + idx];
+            Bs[idx] = Bm[i0 * k + idx];
+        }
+        __syncthreads();
+        for (int r = 0; r < rows; ++r) {
+            double a[NB], b[NB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int p = ty + 16 * u, q = tx + 16 * u;
+                a[u] = p < k ? (double)As[r * k + p] : 0.0;
+                b[u] = q < k ? (double)Bs[r * k + q] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < NB; ++u)
+#pragma unroll
+                for (int v = 0; v < NB; ++v) acc[u][v] = fma(a[u], b[v], acc[u][v]);
+        }
+        __syncthreads();
+    }
+    double* out = partial + (int64_t)blockIdx.x * k * k;
+#pragma unroll
+    for (int u = 0; u < NB; ++u)
+#pragma unroll
+        for (int v = 0; v < NB; ++v) {
+            const int p = ty + 16 * u, q = tx + 16 * v;
+            if (p < k && q < k) out[p * k + q] = acc[u][v];
+        }
+}
+
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ partial, int blocks, int k, int sym,
+                                                         double* __restrict__ G) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= k * k) return;
+    const int p = e / k, q = e - p * k;
+    double s = 0.0, st = 0.0;
+    for (int b = 0; b < blocks; ++b) {
+        s += partial[(int64_t)b * k * k + p * k + q];
+        if (sym) st += partial[(int64_t)b * k * k + q * k + p];
+    }
+    G[e] = sym ? 0.5 * (s + st) : s;
+}
+
+// One workgroup.  R (upper, G = R^T R) is formed in LDS by the right-looking Cholesky algorithm,
+// then thread c solves R x = e_c by back substitution and writes column c of T = R^-1.
+__global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restrict__ G, int k, double* __restrict__ T,
+                                                          int* __restrict__ flag) {
+    extern __shared__ double chol_sm[];
+    double* R = chol_sm;  // [k][k]
+    for (int e = threadIdx.x; e < k * k; e += 256) R[e] = G[e];
+    __syncthreads();
+    double scale = 0.0;
+    for (int j = 0; j < k; ++j) scale = fmax(scale, R[j * k + j]);
+    for (int j = 0; j < k; ++j) {
+        if (threadIdx.x == 0) {
+            double d = R[j * k + j];
+            if (!(d > scale * 1e-28)) {
+                *flag = 1;  // numerically rank-deficient block
+                d = scale > 0.0 ? scale * 1e-28 : 1.0;
+            }
+            R[j * k + j] = sqrt(d);
+        }
+        __syncthreads();
+        const double piv = R[j * k + j];
+        for (int c = j + 1 + threadIdx.x; c < k; c += 256) R[j * k + c] /= piv;
+        __syncthreads();
+        const int m = k - 1 - j;  // trailing block (j+1..k-1)^2, upper part
+        for (int e = threadIdx.x; e < m * m; e += 256) {
+            const int r = j + 1 + e / m, c = j + 1 + e % m;
+            if (c >= r) R[r * k + c] -= R[j * k + r] * R[j * k + c];
+        }
+        __syncthreads();
+    }
+    for (int c = threadIdx.x; c < k; c += 256) {
+        for (int r = k - 1; r > c; --r) T[r * k + c] = 0.0;
+        T[c * k + c] = 1.0 / R[c * k + c];
+        for (int r = c - 1; r >= 0; --r) {
+            double s = 0.0;
+            for (int p = r + 1; p <= c; ++p) s += R[r * k + p] * T[p * k + c];
+            T[r * k + c] = -s / R[r * k + r];
+        }
+    }
+}
+
+// One workgroup: cyclic Jacobi on a symmetric k x k matrix held in LDS; rotations of one
+// round-robin step act on disjoint index pairs and are applied together (rows, then columns).
+// The accumulated rotations Wk live in global memory.  theta is sorted descending and the
+// columns of W follow.
+__global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ H, int k, int sweeps,
+                                                    double* __restrict__ Wk, double* __restrict__ theta,
+                                                    double* __restrict__ W) {
+    extern __shared__ double jac_sm[];
+    const int K = (k + 1) & ~1;  // even number of players; index k (if any) is a dummy
+    double* A = jac_sm;          // [k][k]
+    double* cs = A + k * k;      // [K/2] cos, [K/2] sin
+    double* sn = cs + K / 2;
+    int* pp = (int*)(sn + K / 2);  // [K/2] p, [K/2] q
+    int* qq = pp + K / 2;
+    for (int e = threadIdx.x; e < k * k; e += 256) {
+        A[e] = H[e];
+        Wk[e] = (e / k == e % k) ? 1.0 : 0.0;
+    }
+    __syncthreads();
+    for (int sw = 0; sw < sweeps; ++sw) {
+        for (int step = 0; step < K - 1; ++step) {
+            for (int pr = threadIdx.x; pr < K / 2; pr += 256) {
+                int p = (step + pr) % (K - 1);
+                int q = (pr == 0) ? K - 1 : (step + K - 1 - pr) % (K - 1);
+                if (p > q) {
+                    int t = p;
+                    p = q;
+                    q = t;
+                }
+                double c = 1.0, s = 0.0;
+                if (q < k) {
+                    const double apq = A[p * k + q];
+                    if (apq != 0.0) {
+                        const double tau = (A[q * k + q] - A[p * k + p]) / (2.0 * apq);
+                        const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+                        c = 1.0 / sqrt(1.0 + t * t);
+                        s = t * c;
+                    }
+                } else {
+                    q = -1;  // pair with the dummy: nothing to rotate
+                }
+                cs[pr] = c;
+                sn[pr] = s;
+                pp[pr] = p;
+                qq[pr] = q;
+            }
+            __syncthreads();
+            for (int e = threadIdx.x; e < (K / 2) * k; e += 256) {  // rows p, q of A
+                const int pr = e / k, col = e - pr * k;
+                const int p = pp[pr], q = qq[pr];
+                if (q >= 0) {
+                    const double c = cs[pr], s = sn[pr];
+                    const double ap = A[p * k + col], aq = A[q * k + col];
+                    A[p * k + col] = c * ap - s * aq;
+                    A[q * k + col] = s * ap + c * aq;
+                }
+            }
+            __syncthreads();
+            for (int e = threadIdx.x; e < (K / 2) * k; e += 256) {  // columns p, q of A and of Wk
+                const int pr = e / k, row = e - pr * k;
+                const int p = pp[pr], q = qq[pr];
+                if (q >= 0) {
+                    const double c = cs[pr], s = sn[pr];
+                    const double ap = A[row * k + p], aq = A[row * k + q];
+                    A[row * k + p] = c * ap - s * aq;
+                    A[row * k + q] = s * ap + c * aq;
+                    const double wp = Wk[row * k + p], wq = Wk[row * k + q];
+                    Wk[row * k + p] = c * wp - s * wq;
+                    Wk[row * k + q] = s * wp + c * wq;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    // descending order; equal values keep their index order
+    for (int i = threadIdx.x; i < k; i += 256) {
+        const double ti = A[i * k + i];
+        int rank = 0;
+        for (int j = 0; j < k; ++j) {
+            const double tj = A[j * k + j];
+            rank += (tj > ti) || (tj == ti && j < i);
+        }
+        theta[rank] = ti;
+        for (int r = 0; r < k; ++r) W[r * k + rank] = Wk[r * k + i];
+    }
+}
+
+// Out[i][c] = sum_p A[i][p] T[p][c]; T (float64, [k][kout], row stride k) is staged in LDS.
+__global__ __launch_bounds__(256) void apply_small_kernel(const float* __restrict__ A, int64_t N, int k,
+                                                         const double* __restrict__ T, int kout,
+                                                         float* __restrict__ Out) {
+    extern __shared__ double app_sm[];
+    double* Ts = app_sm;                     // [k][kout]
+    float* As = (float*)(Ts + k * kout);     // [kApplyRows][k]
+    for (int e = threadIdx.x; e < k * kout; e += 256) Ts[e] = T[(e / kout) * k + (e % kout)];
+    for (int64_t i0 = (int64_t)blockIdx.x * kApplyRows; i0 < N; i0 += (int64_t)gridDim.x * kApplyRows) {
+        const int rows = (int)min((int64_t)kApplyRows, N - i0);
+        __syncthreads();
+        for (int e = threadIdx.x; e < rows * k; e += 256) As[e] = A[i0 * k + e];
+        __syncthreads();
+        for (int e = threadIdx.x; e < rows * kout; e += 256) {
+            const int r = e / kout, c = e - r * kout;
+            double s = 0.0;
+            for (int p = 0; p < k; ++p) s = fma((double)As[r * k + p], Ts[p * kout + c], s);
+            Out[(i0 + r) * kout + c] = (float)s;
+        }
+    }
+}
+
+// One workgroup per column: find the largest-magnitude entry (first on ties), flip if negative.
+__global__ __launch_bounds__(256) void fix_signs_kernel(float* __restrict__ V, int64_t N, int kc) {
+    __shared__ float s_abs[256];
+    __shared__ long long s_idx[256];
+    __shared__ float s_sign;
+    const int c = blockIdx.x;
+    float best = -1.0f;
+    long long bi = 0;
+    for (int64_t i = threadIdx.x; i < N; i += 256) {
+        const float a = fabsf(V[i * kc + c]);
+        if (a > best) {
+            best = a;
+            bi = i;
+        }
+    }
+    s_abs[threadIdx.x] = best;
+    s_idx[threadIdx.x] = bi;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (threadIdx.x < off) {
+            const float oa = s_abs[threadIdx.x + off];
+            const long long oi = s_idx[threadIdx.x + off];
+            if (oa > s_abs[threadIdx.x] || (oa == s_abs[threadIdx.x] && oi < s_idx[threadIdx.x])) {
+                s_abs[threadIdx.x] = oa;
+                s_idx[threadIdx.x] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) s_sign = V[s_idx[0] * kc + c] < 0.0f ? -1.0f : 1.0f;
+    __syncthreads();
+    if (s_sign < 0.0f)
+        for (int64_t i = threadIdx.x; i < N; i += 256) V[i * kc + c] = -V[i * kc + c];
+}
+
+template <class K>
+hipError_t allow_lds(K kern, size_t bytes) {
+    if (bytes <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+}  // namespace
+
+hipError_t SmallWs::alloc(int64_t N, int k) {
+    gram_blocks = (int)std::min<int64_t>(512, ceil_div(N, kGramRows));
+    const size_t kk = (size_t)k * k;
+    const size_t doubles = (size_t)gram_blocks * kk + 3 * kk + (size_t)k + kk /*jacobi work*/;
+    hipError_t e = buf.alloc(doubles * sizeof(double) + 64);
+    if (e != hipSuccess) return e;
+    double* p = buf.as<double>();
+    partial = p;
+    p += (size_t)gram_blocks * kk;
+    G = p;
+    p += kk;
+    T = p;
+    p += kk;
+    W = p;
+    p += kk;
+    theta = p;
+    p += k;
+    p += kk;  // jacobi work matrix sits at theta + k
+    flag = (int*)p;
+    return hipMemset(flag, 0, sizeof(int));
+}
+
+int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& ws, double* G, hipStream_t st) {
+    const int64_t rpb = ceil_div(ceil_div(N, ws.gram_blocks), kGramRows) * kGramRows;
+    const int blocks = (int)ceil_div(N, rpb);
+    const size_t lds = sizeof(float) * 2 * kGramRows * (size_t)k;
+    const int NB = (k + 15) / 16;
+#define RFX_GRAM(nb)                                                                                              \
+    case nb:                                                                                                      \
+        hipLaunchKernelGGL(gram_partial_kernel<nb>, dim3(blocks), dim3(256), lds, st, A, Bm, N, k, rpb, ws.partial); \
+        break;
+    switch (NB) {
+        RFX_GRAM(1) RFX_GRAM(2) RFX_GRAM(3) RFX_GRAM(4) RFX_GRAM(5) RFX_GRAM(6) RFX_GRAM(7) RFX_GRAM(8)
+        default:
+            return fail(RFX_ERR_INVALID_ARG, "gram: k=%d > %d", k, kMaxRank);
+    }
+#undef RFX_GRAM
+    RFX_LAUNCH_CHECK("gram_partial_kernel");
+    hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)ceil_div(k * k, 256)), dim3(256), 0, st, ws.partial, blocks, k,
+                       sym ? 1 : 0, G);
+    RFX_LAUNCH_CHECK("gram_reduce_kernel");
+    return RFX_OK;
+}
+
+int chol_inverse(const double* G, int k, SmallWs& ws, double* T, hipStream_t st) {
+    const size_t lds = sizeof(double) * (size_t)k * k;
+    RFX_HIP(allow_lds(chol_inverse_kernel, lds));
+    hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(256), lds, st, G, k, T, ws.flag);
+    RFX_LAUNCH_CHECK("chol_inverse_kernel");
+    return RFX_OK;
+}
+
+int jacobi_eigh(const double* H, int k, SmallWs& ws, double* theta, double* W, hipStream_t st) {
+    const int K = (k + 1) & ~1;
+    const size_t lds = sizeof(double) * ((size_t)k * k + K) + sizeof(int) * K;
+    RFX_HIP(allow_lds(jacobi_kernel, lds));
+    double* work = ws.theta + k;  // [k][k] accumulated rotations
+    const int sweeps = 12;
+    hipLaunchKernelGGL(jacobi_kernel, dim3(1), dim3(256), lds, st, H, k, sweeps, work, theta, W);
+    RFX_LAUNCH_CHECK("jacobi_kernel");
+    return RFX_OK;
+}
+
+int apply_small(const float* A, int64_t N, int k, const double* T, int kout, float* Out, hipStream_t st) {
+    const size_t lds = sizeof(double) * (size_t)k * kout + sizeof(float) * kApplyRows * (size_t)k;
+    RFX_HIP(allow_lds(apply_small_kernel, lds));
+    const unsigned blocks = (unsigned)std::min<int64_t>(ceil_div(N, kApplyRows), 2048);
+    hipLaunchKernelGGL(apply_small_kernel, dim3(blocks), dim3(256), lds, st, A, N, k, T, kout, Out);
+    RFX_LAUNCH_CHECK("apply_small_kernel");
+    return RFX_OK;
+}
+
+int orthonormalise(const float* Y, int64_t N, int k, SmallWs& ws, float* Z, float* V, hipStream_t st) {
+    int rc;
+    if ((rc = gram(Y, Y, N, k, true, ws, ws.G, st)) != RFX_OK) return rc;
+    if ((rc = chol_inverse(ws.G, k, ws, ws.T, st)) != RFX_OK) return rc;
+    if ((rc = apply_small(Y, N, k, ws.T, k, Z, st)) != RFX_OK) return rc;
+    if ((rc = gram(Z, Z, N, k, true, ws, ws.G, st)) != RFX_OK) return rc;
+    if ((rc = chol_inverse(ws.G, k, ws, ws.T, st)) != RFX_OK) return rc;
+    return apply_small(Z, N, k, ws.T, k, V, st);
+}
+
+int fix_signs(float* V, int64_t N, int kc, hipStream_t st) {
+    hipLaunchKernelGGL(fix_signs_kernel, dim3(kc), dim3(256), 0, st, V, N, kc);
+    RFX_LAUNCH_CHECK("fix_signs_kernel");
+    return RFX_OK;
+}
+
+}  // namespace rfx

@@ -1,0 +1,291 @@
+// Dense proximity: cnt(i,j) = #{b : leaf_b(i) = leaf_b(j)} and its out-of-bag-only variant
+// (paper, "Proximity Matrices", p(i,j) = (1/B) sum_b I(node_b(i) = node_b(j)); out-of-bag sets
+// from "Case-wise Bootstrap Tracking").
+//
+// The N^2 B / 2 equality tests are integer-ALU bound, so the leaf ids are first transposed
+// into bit planes: for a group of 32 trees and a sample, word p holds bit p of the sample's
+// 32 leaf ids (one tree per bit lane).  Two samples differ in tree t iff some plane differs in
+// bit t, so one 3-input boolean op per plane (t | (a ^ b)) followed by one population count
+// tests 32 trees at once: (P + 1) / 32 vector ops per test for P-bit leaf ids, against 2 ops per
+// test for a compare-and-add on 32-bit ids.  Matches = B - mismatches; padding trees and
+// padding samples have all planes zero and never mismatch.
+//
+// Work decomposition: a wave owns 256 "a" samples (4 consecutive per lane, their planes in
+// vector registers, reloaded per tree group) and J "b" samples whose planes are wave-uniform
+// and therefore come in through the scalar data path as SGPR operands; the R x J mismatch
+// counters live in vector registers for the whole tree loop and are written once.  Four waves
+// of a workgroup share the a samples (L1 hits) and take consecutive b ranges.  Only tile pairs
+// on or below the diagonal are launched.
+#include "common.h"
+
+namespace {
+
+constexpr int kR = 4;           // a samples per lane
+constexpr int kATile = 64 * kR; // a samples per wave / workgroup
+constexpr int kWaves = 4;
+
+__host__ __device__ constexpr int plane_stride(int P) { return (P + 1 + 3) & ~3; }  // words per (group, sample)
+
+// ---------------------------------------------------------------------------------------------
+// leaf[B][N] (+ inbag[B][N]) -> planes[G][Npad][PS]; word P of a sample is its out-of-bag mask.
+__global__ __launch_bounds__(256) void pack_planes_kernel(const uint32_t* __restrict__ leaf,
+                                                         const uint16_t* __restrict__ inbag, int64_t N, int32_t B,
+                                                         int64_t Npad, int32_t P, int32_t PS,
+                                                         uint32_t* __restrict__ planes) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int g = blockIdx.y;
+    if (i >= Npad) return;
+    uint32_t w[25];
+#pragma unroll
+    for (int p = 0; p < 25; ++p) w[p] = 0;
+    uint32_t oob = 0;
+    if (i < N) {
+        const int nb = min(32, B - g * 32);
+        for (int t = 0; t < nb; ++t) {
+            const int64_t at = (int64_t)(g * 32 + t) * N + i;
+            const uint32_t id = leaf[at];
+#pragma unroll
+            for (int p = 0; p < 25; ++p) w[p] |= ((id >> p) & 1u) << t;
+            if (inbag) oob |= (inbag[at] == 0 ? 1u : 0u) << t;
+        }
+    }
+    uint32_t* dst = planes + ((int64_t)g * Npad + i) * PS;
+#pragma unroll
+    for (int p = 0; p < 25; ++p)
+        if (p < P) dst[p] = w[p];
+    dst[P] = oob;
+    for (int p = P + 1; p < PS; ++p) dst[p] = 0;
+}
+
+struct TileOut {
+    void* counts;  // plain: counts; out-of-bag: num
+    void* den;     // out-of-bag only
+    float* prox;
+    int64_t N;
+    int32_t B;
+    int32_t u16;     // counts / num / den are uint16
+    int32_t packed;  // strict-upper packed layout
+};
+
+__device__ __forceinline__ int64_t packed_index(int64_t i, int64_t j, int64_t N) {
+    return i * N - i * (i + 1) / 2 + (j - i - 1);
+}
+
+template <class T>
+__device__ __forceinline__ void store_one(void* base, int64_t at, uint32_t v) {
+    static_cast<T*>(base)[at] = (T)v;
+}
+
+__device__ __forceinline__ void store_count(void* base, int32_t u16, int64_t at, uint32_t v) {
+    if (u16)
+        store_one<uint16_t>(base, at, v);
+    else
+        store_one<uint32_t>(base, at, v);
+}
+
+// P = number of leaf-id bit planes, J = b samples per wave, kOob = out-of-bag variant.
+template <int P, int J, bool kOob>
+__global__ __launch_bounds__(64 * kWaves, 2) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
+                                                                 int32_t G, TileOut out) {
+    constexpr int PS = plane_stride(P);
+    constexpr int PL = kOob ? P + 1 : P;     // words of a sample actually used
+    constexpr int PV = (PL + 3) / 4;         // 16-byte loads per a sample
+    constexpr int kBTile = J * kWaves;
+    constexpr int kRatio = kATile / kBTile;  // b tiles per a tile
+
+    // triangular tile index: a tile `ta` pairs with b tiles 0 .. (ta+1)*kRatio - 1
+    const int64_t id = blockIdx.x;
+    int64_t ta = (int64_t)((sqrt(8.0 * (double)id / kRatio + 1.0) - 1.0) * 0.5);
+    while (kRatio * (ta + 1) * (ta + 2) / 2 <= id) ++ta;
+    while (kRatio * ta * (ta + 1) / 2 > id) --ta;
+    const int64_t tb = id - kRatio * ta * (ta + 1) / 2;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t a0 = ta * kATile + lane * kR;
+    const int64_t b0 = __builtin_amdgcn_readfirstlane((int)(tb * kBTile + wave * J));
+
+    uint32_t mis[kR][J];
+    uint32_t den[kOob ? kR : 1][kOob ? J : 1];
+#pragma unroll
+    for (int r = 0; r < kR; ++r)
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            mis[r][j] = 0;
+            if (kOob) den[r][j] = 0;
+        }
+
+    for (int g = 0; g < G; ++g) {
+        const uint4* pa = reinterpret_cast<const uint4*>(planes + ((int64_t)g * Npad + a0) * PS);
+        uint32_t xa[kR][PV * 4];
+#pragma unroll
+        for (int r = 0; r < kR; ++r)
+#pragma unroll
+            for (int v = 0; v < PV; ++v) {
+                uint4 q = pa[r * (PS / 4) + v];
+                xa[r][v * 4 + 0] = q.x;
+                xa[r][v * 4 + 1] = q.y;
+                xa[r][v * 4 + 2] = q.z;
+                xa[r][v * 4 + 3] = q.w;
+            }
+        const uint32_t* __restrict__ pb = planes + ((int64_t)g * Npad + b0) * PS;  // wave-uniform
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            uint32_t xb[PL];
+#pragma unroll
+            for (int p = 0; p < PL; ++p) xb[p] = pb[j * PS + p];
+#pragma unroll
+            for (int r = 0; r < kR; ++r) {
+                uint32_t t = xa[r][0] ^ xb[0];
+#pragma unroll
+                for (int p = 1; p < P; ++p) t = __builtin_amdgcn_bitop3_b32(t, xa[r][p], xb[p], 0xf6);  // t | (a ^ b)
+                if (kOob) {
+                    // trees where both are out-of-bag and the leaves agree: ~t & oa & ob
+                    uint32_t both_same = __builtin_amdgcn_bitop3_b32(t, xa[r][P], xb[P], 0x08);
+                    mis[r][j] += __builtin_popcount(both_same);
+                    den[r][j] += __builtin_popcount(xa[r][P] & xb[P]);
+                } else {
+                    mis[r][j] += __builtin_popcount(t);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue: one write per pair -------------------------------------------------------
+    const int64_t N = out.N;
+    const float Bf = (float)out.B;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int64_t b = b0 + j;
+        if (b >= N) break;
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            const int64_t a = a0 + r;
+            if (a >= N) continue;
+            uint32_t c = kOob ? mis[r][j] : (uint32_t)out.B - mis[r][j];
+            uint32_t d = kOob ? den[r][j] : (uint32_t)out.B;
+            float p;
+            if (a == b)
+                p = 1.0f;
+            else if (kOob)
+                p = d ? (float)c / (float)d : 0.0f;
+            else
+                p = (float)c / Bf;
+            if (out.packed) {
+                if (b < a) {
+                    const int64_t at = packed_index(b, a, N);
+                    if (out.counts) store_count(out.counts, out.u16, at, c);
+                    if (kOob && out.den) store_count(out.den, out.u16, at, d);
+                    if (out.prox) out.prox[at] = p;
+                }
+            } else {
+                const int64_t at = b * N + a, mt = a * N + b;
+                if (out.counts) {
+                    store_count(out.counts, out.u16, at, c);
+                    store_count(out.counts, out.u16, mt, c);
+                }
+                if (kOob && out.den) {
+                    store_count(out.den, out.u16, at, d);
+                    store_count(out.den, out.u16, mt, d);
+                }
+                if (out.prox) {
+                    out.prox[at] = p;
+                    out.prox[mt] = p;
+                }
+            }
+        }
+    }
+}
+
+template <int P, int J, bool kOob>
+int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, hipStream_t st) {
+    constexpr int kRatio = kATile / (J * kWaves);
+    const int64_t ta = Npad / kATile;
+    const int64_t blocks = kRatio * ta * (ta + 1) / 2;
+    if (blocks > 0x7fffffffLL) return rfx::fail(RFX_ERR_INVALID_ARG, "proximity: N too large for one launch");
+    hipLaunchKernelGGL((prox_tile_kernel<P, J, kOob>), dim3((unsigned)blocks), dim3(64 * kWaves), 0, st, planes, Npad, G,
+                       out);
+    RFX_LAUNCH_CHECK("prox_tile_kernel");
+    return RFX_OK;
+}
+
+template <bool kOob>
+int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, hipStream_t st) {
+    constexpr int J = kOob ? 16 : 32;
+    switch (P) {
+#define RFX_CASE(p) \
+    case p:         \
+        return launch_tiles<p, J, kOob>(planes, Npad, G, out, st);
+        RFX_CASE(1) RFX_CASE(2) RFX_CASE(3) RFX_CASE(4) RFX_CASE(5) RFX_CASE(6) RFX_CASE(7) RFX_CASE(8)
+        RFX_CASE(9) RFX_CASE(10) RFX_CASE(11) RFX_CASE(12) RFX_CASE(13) RFX_CASE(14) RFX_CASE(15) RFX_CASE(16)
+        RFX_CASE(17) RFX_CASE(18) RFX_CASE(19) RFX_CASE(20) RFX_CASE(21) RFX_CASE(22) RFX_CASE(23) RFX_CASE(24)
+#undef RFX_CASE
+    }
+    return rfx::fail(RFX_ERR_INVALID_ARG, "proximity: %d bit planes", P);
+}
+
+int check_common(const char* who, const void* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype,
+                 int layout) {
+    if (!leaf) return rfx::fail(RFX_ERR_NULL, "%s: leaf is null", who);
+    if (N < 1 || N > 3000000) return rfx::fail(RFX_ERR_INVALID_ARG, "%s: N=%lld outside 1..3000000", who, (long long)N);
+    if (B < 1) return rfx::fail(RFX_ERR_INVALID_ARG, "%s: B=%d", who, B);
+    if (leaf_bound < 1 || leaf_bound > (1 << 24))
+        return rfx::fail(RFX_ERR_INVALID_ARG, "%s: leaf_bound=%d outside 1..2^24", who, leaf_bound);
+    if (count_dtype != RFX_U16 && count_dtype != RFX_U32)
+        return rfx::fail(RFX_ERR_INVALID_ARG, "%s: count_dtype=%d", who, count_dtype);
+    if (layout != RFX_FULL && layout != RFX_UPPER_PACKED) return rfx::fail(RFX_ERR_INVALID_ARG, "%s: layout=%d", who, layout);
+    if (count_dtype == RFX_U16 && B > 65535)
+        return rfx::fail(RFX_ERR_OVERFLOW, "%s: %d trees do not fit uint16 counts", who, B);
+    return RFX_OK;
+}
+
+int bits_for(int32_t leaf_bound) {
+    int P = 1;
+    while ((1 << P) < leaf_bound) ++P;
+    return P;
+}
+
+template <bool kOob>
+int run(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound, const TileOut& out,
+        hipStream_t st) {
+    const int P = bits_for(leaf_bound);
+    const int PS = plane_stride(P);
+    const int32_t G = (B + 31) / 32;
+    const int64_t Npad = rfx::ceil_div(N, kATile) * kATile;
+    rfx::DevBuf planes;
+    RFX_HIP(planes.alloc(sizeof(uint32_t) * (size_t)G * (size_t)Npad * (size_t)PS));
+    hipLaunchKernelGGL(pack_planes_kernel, dim3((unsigned)rfx::ceil_div(Npad, 256), (unsigned)G), dim3(256), 0, st, leaf,
+                       inbag, N, B, Npad, P, PS, planes.as<uint32_t>());
+    RFX_LAUNCH_CHECK("pack_planes_kernel");
+    int rc = dispatch_planes<kOob>(P, planes.as<uint32_t>(), Npad, G, out, st);
+    // the scratch is freed on return, so wait for the kernels that read it
+    hipError_t e = hipStreamSynchronize(st);
+    if (rc != RFX_OK) return rc;
+    if (e != hipSuccess) return rfx::fail(RFX_ERR_HIP, "proximity kernels failed: %s", hipGetErrorString(e));
+    return RFX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
+                   void* counts, float* prox, void* stream) {
+    int rc = check_common("rfx_prox_dense", leaf, N, B, leaf_bound, count_dtype, layout);
+    if (rc != RFX_OK) return rc;
+    if (!counts && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_dense: neither counts nor prox given");
+    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED};
+    return run<false>(leaf, nullptr, N, B, leaf_bound, out, rfx::as_stream(stream));
+}
+
+int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
+                 int count_dtype, int layout, void* num, void* den, float* prox, void* stream) {
+    int rc = check_common("rfx_prox_oob", leaf, N, B, leaf_bound, count_dtype, layout);
+    if (rc != RFX_OK) return rc;
+    if (!inbag) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: inbag is null");
+    if (!num && !den && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: no output given");
+    TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED};
+    return run<true>(leaf, inbag, N, B, leaf_bound, out, rfx::as_stream(stream));
+}
+
+}  // extern "C"

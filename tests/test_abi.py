@@ -1,0 +1,45 @@
+"""The C-ABI library loads and exports every symbol include/rfx.h declares (no GPU needed)."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+import paper_2511_19493_amd as rfx
+
+ROOT = Path(__file__).resolve().parents[1]
+
+
+def _declared():
+    text = (ROOT / "include" / "rfx.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rfx_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert _declared() == sorted(rfx.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    if not rfx.lib_path().exists():
+        pytest.fail("librfx.so is not built: run `python -m paper_2511_19493_amd.build`")
+    lib = ctypes.CDLL(str(rfx.lib_path()))
+    for name in _declared():
+        assert hasattr(lib, name), name
+    rfx.load()
+
+
+def test_host_side_argument_checks():
+    """Validation happens before any device work, so these run without a GPU."""
+    lib = rfx.load()
+    assert lib.rfx_prox_dense(None, 10, 4, 8, rfx.U32, rfx.FULL, None, None, None) == -2
+    assert b"leaf is null" in lib.rfx_last_error()
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.rfx_prox_dense(fake, 10, 70000, 8, rfx.U16, rfx.FULL, fake, None, None) == -3   # overflow of u16
+    assert lib.rfx_prox_dense(fake, 10, 4, 8, 7, rfx.FULL, fake, None, None) == -1
+    assert lib.rfx_prox_dense(fake, 10, 4, 8, rfx.U32, rfx.FULL, None, None, None) == -2
+    assert lib.rfx_prox_oob(fake, None, 10, 4, 8, rfx.U32, rfx.FULL, fake, fake, None, None) == -2
+    assert lib.rfx_pv_apply(None, fake, 4, fake, None) == -2
+    assert lib.rfx_prox_lowrank(fake, 10, 4, 8, 300, 5, fake, fake, fake, None, None, None) == -1
+    assert lib.rfx_prox_lowrank(fake, 10, 4, 8, 4, 0, fake, fake, fake, None, None, None) == -1
+    assert lib.rfx_forest_create(None, None) == -2

@@ -1,0 +1,191 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def _forest(F):
+    import paper_2511_19493_amd as rfx
+    return rfx.Forest(F.n_features, F.node_offset, F.feature, F.threshold, F.left, F.right, F.leaf_id, F.n_leaves)
+
+
+def _u(t):
+    """Counts come back as int16/int32 tensors holding unsigned bits."""
+    a = t.cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.int16 else a.view(np.uint32)
+
+
+def _dev_leaf(torch, leaf):
+    return torch.from_numpy(leaf.view(np.int32)).cuda()
+
+
+@pytest.mark.parametrize("which", ["cfg1", "small2"])
+def test_leaf_assign_bit_exact(torch_cuda, request, which):
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    d = request.getfixturevalue(which)
+    print(f"leaf_assign {which} N={d['X'].shape[0]} B={d['F'].n_trees}", flush=True)
+    gf = _forest(d["F"])
+    assert gf.leaf_bound == int(d["F"].n_leaves.max())
+    leaf = rfx.leaf_assign(gf, torch.from_numpy(d["X"]).cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(_u(leaf), d["leaf"])
+
+
+def test_leaf_assign_nan_goes_right_and_bad_forest_is_rejected(torch_cuda, cfg1):
+    import paper_2511_19493_amd as rfx
+    import oracle
+    torch = torch_cuda
+    X = cfg1["X"].copy()
+    X[::5, ::3] = np.nan
+    ref, _ = oracle.leaf_assign(cfg1["F"], X)
+    leaf = rfx.leaf_assign(_forest(cfg1["F"]), torch.from_numpy(X).cuda())
+    np.testing.assert_array_equal(_u(leaf), ref)
+    F = cfg1["F"]
+    bad_left = F.left.copy()
+    bad_left[0] = 10_000
+    with pytest.raises(rfx.RfxError) as ei:
+        rfx.Forest(F.n_features, F.node_offset, F.feature, F.threshold, bad_left, F.right, F.leaf_id, F.n_leaves)
+    assert ei.value.code == -7
+
+
+def test_prox_dense_full_u32_cfg1(torch_cuda, cfg1):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    leaf = cfg1["leaf"]
+    B, N = leaf.shape
+    print(f"prox_dense full u32 N={N} B={B}", flush=True)
+    cnt, prox = rfx.prox_dense(_dev_leaf(torch, leaf), int(leaf.max()) + 1, rfx.U32, rfx.FULL)
+    torch.cuda.synchronize()
+    ref = oracle.counts_full(leaf)
+    np.testing.assert_array_equal(_u(cnt), ref)
+    np.testing.assert_array_equal(prox.cpu().numpy(), oracle.normalise(ref, B))   # same IEEE division
+
+
+def test_prox_dense_packed_u16_ragged(torch_cuda, small2):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    leaf = small2["leaf"]
+    B, N = leaf.shape                      # N = 1500: several tiles and a ragged tail
+    print(f"prox_dense packed u16 N={N} B={B}", flush=True)
+    cnt, prox = rfx.prox_dense(_dev_leaf(torch, leaf), int(leaf.max()) + 1, rfx.U16, rfx.UPPER_PACKED)
+    torch.cuda.synchronize()
+    ref = oracle.counts_full(leaf)
+    np.testing.assert_array_equal(_u(cnt), oracle.pack_upper(ref).astype(np.uint16))
+    np.testing.assert_allclose(prox.cpu().numpy(), oracle.pack_upper(oracle.normalise(ref, B)), rtol=1e-6)
+    # full layout on the same input, counts only
+    cnt2, none = rfx.prox_dense(_dev_leaf(torch, leaf), int(leaf.max()) + 1, rfx.U32, rfx.FULL, want_prox=False)
+    assert none is None
+    np.testing.assert_array_equal(_u(cnt2), ref)
+
+
+@pytest.mark.parametrize("bound", [1, 2, 3, 17, 300, 70000])
+def test_prox_dense_any_leaf_id_width(torch_cuda, bound):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    rng = np.random.default_rng(bound)
+    # ids drawn from a small pool inside [0, bound) so that matches occur at every width
+    pool = rng.integers(0, bound, size=min(bound, 6))
+    leaf = pool[rng.integers(0, len(pool), size=(37, 300))].astype(np.uint32)
+    cnt, _ = rfx.prox_dense(_dev_leaf(torch, leaf), bound, rfx.U32, rfx.FULL, want_prox=False)
+    np.testing.assert_array_equal(_u(cnt), oracle.counts_full(leaf))
+
+
+@pytest.mark.parametrize("which,layout", [("cfg1", "full"), ("small2", "packed")])
+def test_prox_oob(torch_cuda, request, which, layout):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    d = request.getfixturevalue(which)
+    leaf, inbag = d["leaf"], d["F"].inbag
+    B, N = leaf.shape
+    print(f"prox_oob {which} {layout} N={N} B={B}", flush=True)
+    lay = rfx.FULL if layout == "full" else rfx.UPPER_PACKED
+    num, den, prox = rfx.prox_oob(_dev_leaf(torch, leaf), torch.from_numpy(inbag.view(np.int16)).cuda(),
+                                  int(leaf.max()) + 1, rfx.U32, lay)
+    torch.cuda.synchronize()
+    rn, rd = oracle.oob_rows(leaf, inbag, 0, N)
+    rp = oracle.prox_oob_rows(rn, rd, 0)
+    if layout == "packed":
+        rn, rd, rp = oracle.pack_upper(rn), oracle.pack_upper(rd), oracle.pack_upper(rp)
+    np.testing.assert_array_equal(_u(num), rn)
+    np.testing.assert_array_equal(_u(den), rd)
+    np.testing.assert_array_equal(prox.cpu().numpy(), rp)
+
+
+@pytest.mark.parametrize("which,k", [("cfg1", 16), ("small2", 32), ("small2", 64), ("cfg1", 5), ("small2", 100)])
+def test_matvec(torch_cuda, request, which, k):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    torch = torch_cuda
+    d = request.getfixturevalue(which)
+    leaf = d["leaf"]
+    B, N = leaf.shape
+    print(f"matvec {which} N={N} B={B} k={k}", flush=True)
+    V = ri.start_block(N, k)
+    ref = oracle.pv_implicit(leaf, V.astype(np.float64))
+    Y = rfx.prox_matvec(_dev_leaf(torch, leaf), int(leaf.max()) + 1, torch.from_numpy(V).cuda())
+    torch.cuda.synchronize()
+    err = np.linalg.norm(Y.cpu().numpy().astype(np.float64) - ref) / np.linalg.norm(ref)
+    assert err <= 1e-5, err
+    # plan reuse and run-to-run reproducibility
+    plan = rfx.PvPlan(_dev_leaf(torch, leaf), int(leaf.max()) + 1)
+    Y1 = plan.apply(torch.from_numpy(V).cuda())
+    Y2 = plan.apply(torch.from_numpy(V).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2) and torch.equal(Y1, Y)
+    plan.close()
+
+
+def test_matvec_rejects_leaf_ids_beyond_the_bound(torch_cuda, cfg1):
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    leaf = cfg1["leaf"]
+    with pytest.raises(rfx.RfxError):
+        rfx.PvPlan(_dev_leaf(torch, leaf), int(leaf.max()))     # bound one too small
+
+
+@pytest.mark.parametrize("which,k,T", [("cfg1", 16, 20), ("small2", 32, 20)])
+def test_lowrank_against_the_same_iteration_in_float64(torch_cuda, request, which, k, T):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    torch = torch_cuda
+    d = request.getfixturevalue(which)
+    leaf = d["leaf"]
+    B, N = leaf.shape
+    print(f"lowrank {which} N={N} B={B} k={k} T={T}", flush=True)
+    V0 = ri.start_block(N, k)
+    lam_ref, V_ref = oracle.block_iteration(leaf, V0, T)
+    lam, V, Q, s = rfx.prox_lowrank(_dev_leaf(torch, leaf), int(leaf.max()) + 1, torch.from_numpy(V0).cuda(), T)
+    torch.cuda.synchronize()
+    lam, V = lam.cpu().numpy(), V.cpu().numpy()
+    np.testing.assert_allclose(lam, lam_ref, rtol=1e-4)
+    assert oracle.principal_angle(V, V_ref) < 1e-3
+    np.testing.assert_allclose(V.astype(np.float64).T @ V.astype(np.float64), np.eye(k), atol=5e-6)
+    # sign convention: largest-magnitude entry of each column is positive
+    assert (V[np.argmax(np.abs(V), axis=0), np.arange(k)] > 0).all()
+    # the quantiser takes its rounding decisions in float32 on both sides: codes are bit-exact
+    Qr, sr = oracle.quantise_int8(V, lam)
+    np.testing.assert_array_equal(s.cpu().numpy(), sr)
+    np.testing.assert_array_equal(Q.cpu().numpy(), Qr)
+    Q2, s2 = rfx.quantise_int8(torch.from_numpy(V).cuda(), torch.from_numpy(lam).cuda())
+    assert torch.equal(Q2, Q) and torch.equal(s2, s)
+    # INT8-dequantised P.V on the converged block against the float64 product
+    A = oracle.dequantise(Q.cpu().numpy(), s.cpu().numpy())
+    Xb = V_ref
+    PX = oracle.pv_implicit(leaf, Xb)
+    err = np.linalg.norm(A @ (A.T @ Xb) - PX) / np.linalg.norm(PX)
+    assert err <= 2e-2, err
