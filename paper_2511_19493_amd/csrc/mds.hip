@@ -1,7 +1,365 @@
-// 3-D scaling coordinates from the INT8 factors (placeholder until the kernels land).
-#include "common.h"
+// 3-D scaling coordinates from the INT8 proximity factors (paper, "GPU-Accelerated 3D MDS from
+// Low-Rank Proximity Matrices", Steps 1-4).
+//
+// With A^ = Q diag(scales) (N x k), P^ = A^ A^^T and D = 1 - P^, the Gram matrix of the scaling is
+// G = -1/2 H D2 H, H = I - 11^T/N, D2 = D o D (SQUARED) or D (LINEAR).  G is never formed.  For a
+// vector v: u = H v (so sum u = 0), z = D2 u, w = H z, G v = -w/2 (Step 3), and with
+// p_ij = a_i . a_j
+//     SQUARED: (1 - p)^2 = 1 - 2p + p^2  =>  z_i = -2 a_i . t + a_i^T M a_i
+//     LINEAR :                               z_i = -a_i . t
+// where t = A^^T u (k) and M = A^^T diag(u) A^ (k x k); the constant term vanishes because sum u = 0.
+// A block of m vectors is iterated at once with a Rayleigh-Ritz step per iteration.
+#include <cmath>
+#include <vector>
 
-extern "C" int rfx_mds3d(const int8_t*, const float*, int64_t, int32_t, int, int32_t, int32_t, float, const float*,
-                         float*, float*, int32_t*, void*) {
-    return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_mds3d: not implemented yet");
+#include "common.h"
+#include "dense_small.h"
+
+namespace {
+
+constexpr int kRowsStage = 32;
+
+// partial[block][c] = sum of column c over the block's rows (float64)
+__global__ __launch_bounds__(256) void col_sums_partial_kernel(const float* __restrict__ X, int64_t N, int m,
+                                                              int64_t rows_per_block, double* __restrict__ partial) {
+    __shared__ double red[256];
+    const int64_t i_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t i_end = min(N, i_begin + rows_per_block);
+    // thread t handles column t % m of rows t / m, t / m + 256 / m, ...
+    const int per = 256 / m;  // rows in flight (m <= 32)
+    const int c = threadIdx.x % m, r0 = threadIdx.x / m;
+    double s = 0.0;
+    if (r0 < per)
+        for (int64_t i = i_begin + r0; i < i_end; i += per) s += (double)X[i * m + c];
+    red[threadIdx.x] = (r0 < per) ? s : 0.0;
+    __syncthreads();
+    if (threadIdx.x < m) {
+        double tot = 0.0;
+        for (int r = 0; r < per; ++r) tot += red[r * m + threadIdx.x];
+        partial[(int64_t)blockIdx.x * m + threadIdx.x] = tot;
+    }
+}
+
+__global__ void col_sums_reduce_kernel(const double* __restrict__ partial, int blocks, int m, double* __restrict__ sums) {
+    const int c = threadIdx.x;
+    if (c >= m) return;
+    double s = 0.0;
+    for (int b = 0; b < blocks; ++b) s += partial[(int64_t)b * m + c];
+    sums[c] = s;
+}
+
+// For column c = blockIdx.y, over the block's rows, with u_i = X[i][c] - mean_c:
+//   partialT[block][c][q]    = sum_i u_i a_iq
+//   partialM[block][c][p][q] = sum_i u_i a_ip a_iq        (SQUARED only)
+template <int NB>
+__global__ __launch_bounds__(256) void mds_moments_kernel(const int8_t* __restrict__ Q, const float* __restrict__ scales,
+                                                         const float* __restrict__ X, const double* __restrict__ colsum,
+                                                         int64_t N, int k, int m, int64_t rows_per_block, int squared,
+                                                         double* __restrict__ partialM, double* __restrict__ partialT) {
+    extern __shared__ float mom_sm[];
+    float* As = mom_sm;                                   // [kRowsStage][k]
+    double* us = (double*)(mom_sm + kRowsStage * k);      // [kRowsStage]
+    const int c = blockIdx.y;
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    const double mean = colsum[c] / (double)N;
+    double acc[NB][NB], tacc[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+        tacc[u] = 0.0;
+#pragma unroll
+        for (int v = 0; v < NB; ++v) acc[u][v] = 0.0;
+    }
+    const int64_t i_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t i_end = min(N, i_begin + rows_per_block);
+    for (int64_t i0 = i_begin; i0 < i_end; i0 += kRowsStage) {
+        const int rows = (int)min((int64_t)kRowsStage, i_end - i0);
+        for (int e = threadIdx.x; e < rows * k; e += 256) As[e] = (float)Q[i0 * k + e] * scales[e % k];
+        if (threadIdx.x < rows) us[threadIdx.x] = (double)X[(i0 + threadIdx.x) * m + c] - mean;
+        __syncthreads();
+        for (int r = 0; r < rows; ++r) {
+            const double ur = us[r];
+            double a[NB], b[NB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int p = ty + 16 * u, q = tx + 16 * u;
+                a[u] = p < k ? (double)As[r * k + p] : 0.0;
+                b[u] = q < k ? ur * (double)As[r * k + q] : 0.0;
+            }
+            if (ty == 0) {
+#pragma unroll
+                for (int v = 0; v < NB; ++v) tacc[v] += b[v];
+            }
+            if (squared) {
+#pragma unroll
+                for (int u = 0; u < NB; ++u)
+#pragma unroll
+                    for (int v = 0; v < NB; ++v) acc[u][v] = fma(a[u], b[v], acc[u][v]);
+            }
+        }
+        __syncthreads();
+    }
+    const int64_t slot = (int64_t)blockIdx.x * m + c;
+    if (ty == 0) {
+#pragma unroll
+        for (int v = 0; v < NB; ++v) {
+            const int q = tx + 16 * v;
+            if (q < k) partialT[slot * k + q] = tacc[v];
+        }
+    }
+    if (squared) {
+        double* out = partialM + slot * k * k;
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
+#pragma unroll
+            for (int v = 0; v < NB; ++v) {
+                const int p = ty + 16 * u, q = tx + 16 * v;
+                if (p < k && q < k) out[p * k + q] = acc[u][v];
+            }
+    }
+}
+
+// M[c][e] = sum_block partialM[block][c][e];  T[c][q] likewise.  len = k*k or k.
+__global__ __launch_bounds__(256) void moments_reduce_kernel(const double* __restrict__ partial, int blocks, int m,
+                                                            int len, double* __restrict__ out) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    const int c = blockIdx.y;
+    if (e >= len) return;
+    double s = 0.0;
+    for (int b = 0; b < blocks; ++b) s += partial[((int64_t)b * m + c) * len + e];
+    out[(int64_t)c * len + e] = s;
+}
+
+// Z[i][c] for a tile of RT rows and column c = blockIdx.y:
+//   SQUARED: a_i^T (M_c a_i) - 2 t_c . a_i      LINEAR: -t_c . a_i
+// (RT/16) x NB register tile per thread of the product A^ M_c, then a row reduction over the
+// 16 threads that share a row.
+template <int NB, int RT>
+__global__ __launch_bounds__(256) void mds_quad_kernel(const int8_t* __restrict__ Q, const float* __restrict__ scales,
+                                                      const double* __restrict__ M, const double* __restrict__ T,
+                                                      int64_t N, int k, int m, int squared, float* __restrict__ Z) {
+    extern __shared__ double quad_sm[];
+    double* Ms = quad_sm;                     // [k][k]   (SQUARED only)
+    double* ts = Ms + (squared ? k * k : 0);  // [k]
+    float* As = (float*)(ts + k);             // [RT][k]
+    const int c = blockIdx.y;
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    const int64_t i0 = (int64_t)blockIdx.x * RT;
+    const int rows = (int)min((int64_t)RT, N - i0);
+    if (squared)
+        for (int e = threadIdx.x; e < k * k; e += 256) Ms[e] = M[(int64_t)c * k * k + e];
+    for (int e = threadIdx.x; e < k; e += 256) ts[e] = T[(int64_t)c * k + e];
+    for (int e = threadIdx.x; e < RT * k; e += 256)
+        As[e] = e < rows * k ? (float)Q[i0 * k + e] * scales[e % k] : 0.0f;
+    __syncthreads();
+    constexpr int RU = RT / 16;
+    double acc[RU][NB];
+#pragma unroll
+    for (int u = 0; u < RU; ++u)
+#pragma unroll
+        for (int v = 0; v < NB; ++v) acc[u][v] = 0.0;
+    if (squared) {
+        for (int q = 0; q < k; ++q) {
+            double a[RU], mq[NB];
+#pragma unroll
+            for (int u = 0; u < RU; ++u) a[u] = (double)As[(ty + 16 * u) * k + q];
+#pragma unroll
+            for (int v = 0; v < NB; ++v) {
+                const int p = tx + 16 * v;
+                mq[v] = p < k ? Ms[q * k + p] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < RU; ++u)
+#pragma unroll
+                for (int v = 0; v < NB; ++v) acc[u][v] = fma(a[u], mq[v], acc[u][v]);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < RU; ++u) {
+        const int r = ty + 16 * u;
+        double z = 0.0;
+#pragma unroll
+        for (int v = 0; v < NB; ++v) {
+            const int p = tx + 16 * v;
+            if (p < k) {
+                const double ap = (double)As[r * k + p];
+                z += squared ? (acc[u][v] - 2.0 * ts[p]) * ap : -ts[p] * ap;
+            }
+        }
+        // sum over the 16 consecutive lanes that hold this row
+        for (int off = 8; off > 0; off >>= 1) z += __shfl_xor(z, off, 16);
+        if (tx == 0 && r < rows) Z[(i0 + r) * m + c] = (float)z;
+    }
+}
+
+// Y[i][c] = -1/2 (Z[i][c] - mean_c(Z))
+__global__ __launch_bounds__(256) void mds_center_kernel(const float* __restrict__ Z, const double* __restrict__ colsum,
+                                                        int64_t N, int m, float* __restrict__ Y) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= N * m) return;
+    const int c = (int)(e % m);
+    Y[e] = (float)(-0.5 * ((double)Z[e] - colsum[c] / (double)N));
+}
+
+// coords[i][d] = sqrt(max(theta_d, 0)) * V[i][d] for d < 3 (V has row stride 3); eigvals[d] = theta_d
+__global__ __launch_bounds__(256) void mds_coords_kernel(float* __restrict__ V, const double* __restrict__ theta, int64_t N,
+                                                        float* __restrict__ eigvals) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < 3) eigvals[e] = (float)theta[e];
+    if (e >= N * 3) return;
+    const double th = theta[e % 3];
+    V[e] = (float)((double)V[e] * sqrt(th > 0.0 ? th : 0.0));
+}
+
+struct MdsWs {
+    int blocks = 0;
+    int64_t rows_per_block = 0;
+    double* colsum_partial = nullptr;  // [blocks][m]
+    double* colsum = nullptr;          // [m]
+    double* partialM = nullptr;        // [blocks][m][k][k]
+    double* partialT = nullptr;        // [blocks][m][k]
+    double* M = nullptr;               // [m][k][k]
+    double* T = nullptr;               // [m][k]
+    rfx::DevBuf buf;
+};
+
+int col_sums(const float* X, int64_t N, int m, MdsWs& w, hipStream_t st) {
+    hipLaunchKernelGGL(col_sums_partial_kernel, dim3(w.blocks), dim3(256), 0, st, X, N, m, w.rows_per_block,
+                       w.colsum_partial);
+    hipLaunchKernelGGL(col_sums_reduce_kernel, dim3(1), dim3(64), 0, st, w.colsum_partial, w.blocks, m, w.colsum);
+    RFX_LAUNCH_CHECK("col_sums");
+    return RFX_OK;
+}
+
+template <int NB>
+int apply_gram_nb(const int8_t* Q, const float* scales, int64_t N, int k, int m, int squared, const float* X, float* Z,
+                  float* Y, MdsWs& w, hipStream_t st) {
+    int rc;
+    if ((rc = col_sums(X, N, m, w, st)) != RFX_OK) return rc;
+    {
+        const size_t lds = sizeof(float) * kRowsStage * (size_t)k + sizeof(double) * kRowsStage;
+        hipLaunchKernelGGL(mds_moments_kernel<NB>, dim3(w.blocks, m), dim3(256), lds, st, Q, scales, X, w.colsum, N, k, m,
+                           w.rows_per_block, squared, w.partialM, w.partialT);
+        RFX_LAUNCH_CHECK("mds_moments_kernel");
+        if (squared)
+            hipLaunchKernelGGL(moments_reduce_kernel, dim3((unsigned)rfx::ceil_div(k * k, 256), m), dim3(256), 0, st,
+                               w.partialM, w.blocks, m, k * k, w.M);
+        hipLaunchKernelGGL(moments_reduce_kernel, dim3((unsigned)rfx::ceil_div(k, 256), m), dim3(256), 0, st, w.partialT,
+                           w.blocks, m, k, w.T);
+        RFX_LAUNCH_CHECK("moments_reduce_kernel");
+    }
+    {
+        const bool small_tile = k > 96;
+        const int RT = small_tile ? 32 : 64;
+        const size_t lds = sizeof(double) * ((squared ? (size_t)k * k : 0) + k) + sizeof(float) * (size_t)RT * k;
+        dim3 grid((unsigned)rfx::ceil_div(N, RT), m);
+        if (small_tile) {
+            auto kern = mds_quad_kernel<NB, 32>;
+            if (lds > 64 * 1024)
+                RFX_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, Q, scales, w.M, w.T, N, k, m, squared, Z);
+        } else {
+            auto kern = mds_quad_kernel<NB, 64>;
+            if (lds > 64 * 1024)
+                RFX_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, Q, scales, w.M, w.T, N, k, m, squared, Z);
+        }
+        RFX_LAUNCH_CHECK("mds_quad_kernel");
+    }
+    if ((rc = col_sums(Z, N, m, w, st)) != RFX_OK) return rc;
+    hipLaunchKernelGGL(mds_center_kernel, dim3((unsigned)rfx::ceil_div(N * m, 256)), dim3(256), 0, st, Z, w.colsum, N, m, Y);
+    RFX_LAUNCH_CHECK("mds_center_kernel");
+    return RFX_OK;
+}
+
+// Y = G X for a block X [N][m]; Z is an [N][m] temporary.
+int apply_gram(const int8_t* Q, const float* scales, int64_t N, int k, int m, int squared, const float* X, float* Z,
+               float* Y, MdsWs& w, hipStream_t st) {
+    switch ((k + 15) / 16) {
+#define RFX_CASE(nb) \
+    case nb:         \
+        return apply_gram_nb<nb>(Q, scales, N, k, m, squared, X, Z, Y, w, st);
+        RFX_CASE(1) RFX_CASE(2) RFX_CASE(3) RFX_CASE(4) RFX_CASE(5) RFX_CASE(6) RFX_CASE(7) RFX_CASE(8)
+#undef RFX_CASE
+    }
+    return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: k=%d", k);
+}
+
+}  // namespace
+
+extern "C" int rfx_mds3d(const int8_t* Q, const float* scales, int64_t N, int32_t k, int dissim_mode, int32_t m,
+                         int32_t max_iters, float tol, const float* x0, float* coords, float* eigvals,
+                         int32_t* iters_done, void* stream) {
+    if (!Q || !scales || !x0 || !coords || !eigvals) return rfx::fail(RFX_ERR_NULL, "rfx_mds3d: null argument");
+    if (N < 3 || N * 32 / 256 > 0x7fffffffLL) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: N=%lld", (long long)N);
+    if (k < 1 || k > rfx::kMaxRank) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: k=%d outside 1..%d", k, rfx::kMaxRank);
+    if (m < 3 || m > 32 || m > N) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: m=%d outside 3..min(32, N)", m);
+    if (dissim_mode != RFX_MDS_SQUARED && dissim_mode != RFX_MDS_LINEAR)
+        return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: dissim_mode=%d", dissim_mode);
+    if (max_iters < 1 || !(tol >= 0.0f)) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: max_iters=%d tol=%g", max_iters, tol);
+    hipStream_t st = rfx::as_stream(stream);
+    const int squared = dissim_mode == RFX_MDS_SQUARED;
+
+    MdsWs w;
+    w.blocks = (int)std::min<int64_t>(256, rfx::ceil_div(N, kRowsStage));
+    w.rows_per_block = rfx::ceil_div(rfx::ceil_div(N, w.blocks), kRowsStage) * kRowsStage;
+    w.blocks = (int)rfx::ceil_div(N, w.rows_per_block);
+    const size_t kk = (size_t)k * k;
+    const size_t doubles = (size_t)w.blocks * m + m + (size_t)w.blocks * m * (squared ? kk : 0) + (size_t)w.blocks * m * k +
+                           (size_t)m * kk + (size_t)m * k;
+    RFX_HIP(w.buf.alloc(doubles * sizeof(double)));
+    double* p = w.buf.as<double>();
+    w.colsum_partial = p;
+    p += (size_t)w.blocks * m;
+    w.colsum = p;
+    p += m;
+    w.partialM = p;
+    p += (size_t)w.blocks * m * (squared ? kk : 0);
+    w.partialT = p;
+    p += (size_t)w.blocks * m * k;
+    w.M = p;
+    p += (size_t)m * kk;
+    w.T = p;
+
+    rfx::SmallWs ws;
+    RFX_HIP(ws.alloc(N, m));
+    rfx::DevBuf blocks;
+    RFX_HIP(blocks.alloc(sizeof(float) * 3 * (size_t)N * m));
+    float* X = blocks.as<float>();
+    float* Y = X + (size_t)N * m;
+    float* Z = Y + (size_t)N * m;
+
+    int rc;
+    if ((rc = rfx::orthonormalise(x0, N, m, ws, Z, X, st)) != RFX_OK) return rc;
+    std::vector<double> theta(m), prev(3, 0.0);
+    int it = 0;
+    bool converged = false;
+    while (true) {
+        // Y = G X, H = sym(X^T Y) = W diag(theta) W^T (theta descending by algebraic value)
+        if ((rc = apply_gram(Q, scales, N, k, m, squared, X, Z, Y, w, st)) != RFX_OK) return rc;
+        ++it;
+        if ((rc = rfx::gram(X, Y, N, m, true, ws, ws.G, st)) != RFX_OK) return rc;
+        if ((rc = rfx::jacobi_eigh(ws.G, m, ws, ws.theta, ws.W, st)) != RFX_OK) return rc;
+        RFX_HIP(hipMemcpyAsync(theta.data(), ws.theta, sizeof(double) * m, hipMemcpyDeviceToHost, st));
+        RFX_HIP(hipStreamSynchronize(st));
+        if (it > 1) {
+            converged = true;
+            for (int d = 0; d < 3; ++d)
+                if (std::fabs(theta[d] - prev[d]) > (double)tol * std::fabs(theta[d])) converged = false;
+        }
+        for (int d = 0; d < 3; ++d) prev[d] = theta[d];
+        if (converged || it >= max_iters) break;
+        if ((rc = rfx::orthonormalise(Y, N, m, ws, Z, X, st)) != RFX_OK) return rc;
+    }
+    // Ritz vectors of the three largest values: coords = X W[:, 0:3] scaled by sqrt(theta)
+    if ((rc = rfx::apply_small(X, N, m, ws.W, 3, coords, st)) != RFX_OK) return rc;
+    if ((rc = rfx::fix_signs(coords, N, 3, st)) != RFX_OK) return rc;
+    hipLaunchKernelGGL(mds_coords_kernel, dim3((unsigned)rfx::ceil_div(N * 3, 256)), dim3(256), 0, st, coords, ws.theta, N,
+                       eigvals);
+    RFX_LAUNCH_CHECK("mds_coords_kernel");
+    int h_flag = 0;
+    RFX_HIP(hipMemcpyAsync(&h_flag, ws.flag, sizeof(int), hipMemcpyDeviceToHost, st));
+    RFX_HIP(hipStreamSynchronize(st));
+    if (iters_done) *iters_done = it;
+    if (h_flag) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: iteration block lost rank (G has rank < m=%d?)", m);
+    return RFX_OK;
 }

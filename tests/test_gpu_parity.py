@@ -189,3 +189,46 @@ def test_lowrank_against_the_same_iteration_in_float64(torch_cuda, request, whic
     PX = oracle.pv_implicit(leaf, Xb)
     err = np.linalg.norm(A @ (A.T @ Xb) - PX) / np.linalg.norm(PX)
     assert err <= 2e-2, err
+
+
+def _align(coords, ref, lam):
+    """Ritz vectors of (nearly) equal eigenvalues are defined up to a rotation inside their
+    eigenspace; align with orthogonal Procrustes in that case, otherwise compare as is."""
+    gaps = np.abs(np.diff(lam)) / np.abs(lam[0])
+    if gaps.min() > 1e-2:
+        return coords
+    U, _, Vt = np.linalg.svd(coords.T @ ref)
+    return coords @ (U @ Vt)
+
+
+@pytest.mark.parametrize("which,k,mode", [("cfg1", 16, "squared"), ("cfg1", 16, "linear"), ("small2", 32, "squared"),
+                                          ("small2", 100, "squared")])
+def test_mds3d_against_dense_torgerson_scaling(torch_cuda, request, which, k, mode):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    torch = torch_cuda
+    d = request.getfixturevalue(which)
+    leaf = d["leaf"]
+    B, N = leaf.shape
+    print(f"mds3d {which} N={N} k={k} {mode}", flush=True)
+    # factors from the oracle so that this test isolates the scaling step
+    lam, V = oracle.block_iteration(leaf, ri.start_block(N, k), 8)
+    Qh, sh = oracle.quantise_int8(V, lam)
+    omode = oracle.SQUARED if mode == "squared" else oracle.LINEAR
+    gmode = rfx.MDS_SQUARED if mode == "squared" else rfx.MDS_LINEAR
+    ref, ev_ref = oracle.mds3d_dense(Qh, sh, omode)
+    m = 12
+    x0 = ri.start_block(N, m, seed=778)
+    coords, ev, iters = rfx.mds3d(torch.from_numpy(Qh).cuda(), torch.from_numpy(sh).cuda(), torch.from_numpy(x0).cuda(),
+                                  gmode, max_iters=500, tol=1e-7)
+    torch.cuda.synchronize()
+    coords, ev = coords.cpu().numpy().astype(np.float64), ev.cpu().numpy().astype(np.float64)
+    print(f"  iterations={iters} eig={ev} ref={ev_ref}", flush=True)
+    assert iters < 500
+    np.testing.assert_allclose(ev, ev_ref, rtol=1e-4)
+    err = np.linalg.norm(_align(coords, ref, ev_ref) - ref) / np.linalg.norm(ref)
+    assert err <= 1e-3, err
+    # invariants of classical scaling: centred, mutually orthogonal columns with |col|^2 = lambda
+    assert np.abs(coords.sum(axis=0)).max() <= 1e-3 * np.abs(coords).max() * np.sqrt(N)
+    np.testing.assert_allclose(coords.T @ coords, np.diag(ev), atol=2e-4 * ev[0])
