@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the random-forest proximity hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--cfg 4]
+
+One step = one pass of the whole path over one synthetic workload, inputs resident in HBM:
+leaf assignment -> dense proximity (full float32) -> out-of-bag proximity (packed upper float32)
+-> rank-k block iteration with INT8 factors -> 3-D scaling from the factors.
+Prints ONE JSON line (metric: leaf co-occurrence tests per second, N^2*B/2 per step), with the
+roofline of the dominant kernel and the CPU oracle timed on a bounded sample of the same work.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+PEAK_VALU_LANE_OPS = 256 * 64 * 2.4e9   # 256 CUs x 64 lanes/clk x 2.4 GHz: plain 32-bit vector ops per second
+PEAK_HBM_BYTES = 8.0e12
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--cfg", type=int, default=4, help="workload 1..5 (default: N=100,000, B=1,000)")
+    ap.add_argument("--trees", type=int, default=0, help="override the tree count (debugging only)")
+    ap.add_argument("--rows", type=int, default=0, help="override the row count (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mds-block", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    rfx.load()          # fails loudly if librfx.so is missing: there is no fallback path
+    dev = torch.device("cuda:0")
+    c = ri.CONFIGS[args.cfg]
+    N = args.rows or c.N
+    B = args.trees or c.B
+    k, T = c.k, c.T
+    reduced = bool(args.rows or args.trees)
+
+    t0 = time.time()
+    X, y, F = ri.load_or_grow(c, N=N if args.rows else None, B=B if args.trees else None)
+    log(f"workload cfg{c.cfg}: N={N} M={c.M} B={B} k={k} T={T}; inputs ready in {time.time() - t0:.1f}s "
+        f"(nodes={F.total_nodes}, max leaves/tree={int(F.n_leaves.max())})")
+    gf = rfx.Forest(F.n_features, F.node_offset, F.feature, F.threshold, F.left, F.right, F.leaf_id, F.n_leaves)
+    Lb = gf.leaf_bound
+    dX = torch.from_numpy(X).to(dev)
+    d_inbag = torch.from_numpy(F.inbag.view(np.int16)).to(dev)
+    dV0 = torch.from_numpy(ri.start_block(N, k)).to(dev)
+    m = args.mds_block
+    dx0 = torch.from_numpy(ri.start_block(N, m, seed=ri.mixture.START_SEED + 1)).to(dev)
+    leaf = torch.empty((B, N), dtype=torch.int32, device=dev)
+    prox = torch.empty((N, N), dtype=torch.float32, device=dev)
+    n_ut = N * (N - 1) // 2
+    prox_oob = torch.empty((n_ut,), dtype=torch.float32, device=dev)
+
+    lib = rfx.load()
+    st = torch.cuda.current_stream().cuda_stream
+    phase_ms = {}
+
+    def timed(name, fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        out = fn()
+        e1.record()
+        phase_ms.setdefault(name, []).append((e0, e1))
+        return out
+
+    def step():
+        timed("leaf_assign", lambda: rfx.leaf_assign(gf, dX, leaf))
+        timed("prox_dense", lambda: rfx.prox_dense(leaf, Lb, rfx.U32, rfx.FULL, prox=prox, want_counts=False))
+        timed("prox_oob", lambda: rfx._check(lib.rfx_prox_oob(leaf.data_ptr(), d_inbag.data_ptr(), N, B, Lb, rfx.U32,
+                                                               rfx.UPPER_PACKED, 0, 0, prox_oob.data_ptr(), st)))
+        lam, V, Q, s = timed("prox_lowrank", lambda: rfx.prox_lowrank(leaf, Lb, dV0, T))
+        res = timed("mds3d", lambda: rfx.mds3d(Q, s, dx0, rfx.MDS_SQUARED, max_iters=200, tol=1e-5))
+        return lam, res
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    phase_ms.clear()
+    rfx.timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        lam, (coords, ev, mds_iters) = step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    phases = {n: float(np.mean([a.elapsed_time(b) for a, b in evs])) for n, evs in phase_ms.items()}
+    kern = {}
+    for name in ("leaf_assign_kernel", "prox_tile_kernel", "prox_tile_kernel_oob", "pv_leaf_sum_kernel", "pv_gather_kernel"):
+        ms, n = rfx.timing_get(name)
+        kern[name] = {"avg_ms": ms / max(n, 1), "launches": n}
+    rfx.timing_enable(False)
+
+    tests = N * N * B / 2.0
+    P = max(1, int(np.ceil(np.log2(max(Lb, 2)))))
+    # dominant kernel: bit-plane compare-and-count.  One launch covers the tile pairs on and below the
+    # diagonal of the (padded) N x N grid, 32 trees per (P+1) vector ops: algorithmic lane-ops per launch
+    ops_per_launch = tests * (P + 1) / 32.0
+    tile_ms = kern["prox_tile_kernel"]["avg_ms"]
+    achieved = ops_per_launch / (tile_ms * 1e-3) if tile_ms > 0 else 0.0
+    roofline = {"kernel": "prox_tile_kernel", "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_VALU_LANE_OPS / 1e12,
+                "unit": "T lane-ops/s", "frac": achieved / PEAK_VALU_LANE_OPS, "traffic": None,
+                "ops_per_test": (P + 1) / 32.0, "avg_launch_ms": tile_ms,
+                "tests_per_s": tests / (tile_ms * 1e-3) if tile_ms > 0 else 0.0}
+    # implicit product: algorithmic bytes per application = B*N*(2*4k + 4) + 2*4*N*k
+    w_pv = B * N * (2 * 4 * k + 4) + 2 * 4 * N * k
+    pv_ms = kern["pv_leaf_sum_kernel"]["avg_ms"] + kern["pv_gather_kernel"]["avg_ms"]
+    pv = {"bytes_per_application": w_pv, "avg_ms": pv_ms, "GBps": w_pv / (pv_ms * 1e-3) / 1e9 if pv_ms > 0 else 0.0,
+          "frac_of_hbm_peak": (w_pv / (pv_ms * 1e-3)) / PEAK_HBM_BYTES if pv_ms > 0 else 0.0,
+          "leaf_sum_ms": kern["pv_leaf_sum_kernel"]["avg_ms"], "gather_ms": kern["pv_gather_kernel"]["avg_ms"]}
+
+    out = {
+        "metric": "leaf co-occurrence tests/s (N^2*B/2 per pass of the whole proximity path)",
+        "value": tests / (ms_per_step * 1e-3),
+        "unit": "tests/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{c.cfg}: N={N} M={c.M} B={B} trees to purity, mtry={c.mtry}, k={k}, T={T}"
+                               + (" (REDUCED, debugging)" if reduced else ""),
+                   "leaf_bound": Lb, "bit_planes": P, "mds_block": m, "mds_iters": mds_iters},
+        "phases_ms": phases,
+        "dense_tests_per_s": tests / (phases["prox_dense"] * 1e-3),
+        "pv": pv,
+        "kernels": kern,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(leaf, N, B)
+    print(json.dumps(out))
+
+
+def cpu_baseline(leaf_dev, N, B):
+    """The oracle's naive pair counting, as it stands, on a bounded block of rows of the same leaf ids."""
+    import oracle
+    leaf = leaf_dev.cpu().numpy().view(np.uint32)
+    cores = len(os.sched_getaffinity(0))
+    try:
+        cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    except ValueError:
+        pass
+    rows = min(N, 8)
+    t0 = time.perf_counter()
+    oracle.counts_rows(leaf, 0, rows)
+    dt = time.perf_counter() - t0
+    # size the sample for roughly 10 s of work
+    rows2 = int(min(N, max(rows, rows * 10.0 / max(dt, 1e-3))))
+    t0 = time.perf_counter()
+    oracle.counts_rows(leaf, 0, rows2)
+    dt = time.perf_counter() - t0
+    tests = rows2 * N * B
+    return {"value": tests / dt, "unit": "tests/s", "cores": cores, "kind": "oracle",
+            "sample": f"orc_counts_rows on rows 0..{rows2 - 1} x all {N} columns x {B} trees ({tests:.3g} tests, {dt:.1f}s)"}
+
+
+if __name__ == "__main__":
+    main()

@@ -56,6 +56,15 @@ extern "C" {
 
 const char* rfx_last_error(void);
 
+/* Measurement aid.  While enabled, the library brackets each launch of its main kernels
+ * ("leaf_assign_kernel", "prox_tile_kernel", "prox_tile_kernel_oob", "pv_leaf_sum_kernel",
+ * "pv_gather_kernel") with HIP events on the launch stream.  rfx_timing_enable(on) switches it
+ * and clears the totals; rfx_timing_get waits for the recorded events and returns the summed
+ * kernel time in milliseconds and the number of launches of one kernel since the last enable.
+ *   total_ms, launches [host] out. */
+int rfx_timing_enable(int on);
+int rfx_timing_get(const char* kernel, double* total_ms, int64_t* launches);
+
 /* ------------------------------------------------------------------------------------------
  * Forest: flattened trees ("Flattened arrays": per-node split variable, split value, child
  * pointers and node status, concatenated over trees).  All pointers [host].

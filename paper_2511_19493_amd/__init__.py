@@ -22,7 +22,7 @@ FULL, UPPER_PACKED = 0, 1
 MDS_SQUARED, MDS_LINEAR = 0, 1
 
 EXPORTS = (
-    "rfx_last_error", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
+    "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
     "rfx_prox_dense", "rfx_prox_oob", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d",
 )
@@ -57,6 +57,8 @@ def load():
         sigs = {
             "rfx_forest_create": [ctypes.POINTER(_ForestDesc), ctypes.POINTER(vp)],
             "rfx_forest_destroy": [vp],
+            "rfx_timing_enable": [ci],
+            "rfx_timing_get": [ctypes.c_char_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)],
             "rfx_leaf_assign": [vp, vp, i64, i32, vp, vp],
             "rfx_prox_dense": [vp, i64, i32, i32, ci, ci, vp, vp, vp],
             "rfx_prox_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp],
@@ -97,6 +99,18 @@ def _dev(t, dtype, shape=None) -> int:
     if shape is not None and tuple(t.shape) != tuple(shape):
         raise ValueError(f"expected shape {tuple(shape)}, got {tuple(t.shape)}")
     return t.data_ptr()
+
+
+def timing_enable(on: bool = True):
+    """rfx_timing_enable: per-kernel HIP-event timing inside the library (clears the totals)."""
+    _check(load().rfx_timing_enable(1 if on else 0))
+
+
+def timing_get(kernel: str):
+    """rfx_timing_get: (total milliseconds, launches) of one kernel since timing was enabled."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(load().rfx_timing_get(kernel.encode(), ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
 
 
 class Forest:

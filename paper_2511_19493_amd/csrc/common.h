@@ -39,6 +39,16 @@ struct DevBuf {
     }
 };
 
+// Optional per-kernel timing (rfx_timing_enable): brackets one kernel launch with HIP events on
+// the launch stream; rfx_timing_get waits for the events and accumulates the elapsed times.
+struct TimedLaunch {
+    TimedLaunch(const char* name, hipStream_t st);
+    ~TimedLaunch();
+    const char* name_;
+    hipStream_t st_;
+    hipEvent_t start_ = nullptr;
+};
+
 }  // namespace rfx
 
 #define RFX_HIP(call)                                                                                    \

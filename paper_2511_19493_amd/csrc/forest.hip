@@ -14,6 +14,8 @@
 // everything the step needs.
 #include <algorithm>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -31,6 +33,47 @@ int fail(int code, const char* fmt, ...) {
     va_end(ap);
     g_last_error = buf;
     return code;
+}
+
+namespace {
+struct TimingState {
+    std::mutex mu;
+    bool enabled = false;
+    struct Pending {
+        std::string name;
+        hipEvent_t a, b;
+    };
+    std::vector<Pending> pending;
+    std::map<std::string, std::pair<double, int64_t>> totals;  // name -> (ms, launches)
+};
+TimingState& timing() {
+    static TimingState s;
+    return s;
+}
+}  // namespace
+
+TimedLaunch::TimedLaunch(const char* name, hipStream_t st) : name_(name), st_(st) {
+    TimingState& t = timing();
+    std::lock_guard<std::mutex> lk(t.mu);
+    if (!t.enabled) return;
+    if (hipEventCreate(&start_) != hipSuccess) {
+        start_ = nullptr;
+        return;
+    }
+    (void)hipEventRecord(start_, st_);
+}
+
+TimedLaunch::~TimedLaunch() {
+    if (!start_) return;
+    hipEvent_t stop = nullptr;
+    if (hipEventCreate(&stop) != hipSuccess) {
+        (void)hipEventDestroy(start_);
+        return;
+    }
+    (void)hipEventRecord(stop, st_);
+    TimingState& t = timing();
+    std::lock_guard<std::mutex> lk(t.mu);
+    t.pending.push_back({name_, start_, stop});
 }
 
 }  // namespace rfx
@@ -104,6 +147,41 @@ int bit_width(uint64_t v) {
 extern "C" {
 
 const char* rfx_last_error(void) { return rfx::g_last_error.c_str(); }
+
+int rfx_timing_enable(int on) {
+    rfx::TimingState& t = rfx::timing();
+    std::lock_guard<std::mutex> lk(t.mu);
+    t.enabled = on != 0;
+    for (auto& p : t.pending) {
+        (void)hipEventSynchronize(p.b);
+        (void)hipEventDestroy(p.a);
+        (void)hipEventDestroy(p.b);
+    }
+    t.pending.clear();
+    t.totals.clear();
+    return RFX_OK;
+}
+
+int rfx_timing_get(const char* kernel, double* total_ms, int64_t* launches) {
+    if (!kernel || !total_ms || !launches) return rfx::fail(RFX_ERR_NULL, "rfx_timing_get: null argument");
+    rfx::TimingState& t = rfx::timing();
+    std::lock_guard<std::mutex> lk(t.mu);
+    for (auto& p : t.pending) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(p.b) == hipSuccess && hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+            auto& tot = t.totals[p.name];
+            tot.first += ms;
+            tot.second += 1;
+        }
+        (void)hipEventDestroy(p.a);
+        (void)hipEventDestroy(p.b);
+    }
+    t.pending.clear();
+    auto it = t.totals.find(kernel);
+    *total_ms = it == t.totals.end() ? 0.0 : it->second.first;
+    *launches = it == t.totals.end() ? 0 : it->second.second;
+    return RFX_OK;
+}
 
 int rfx_forest_create(const rfx_forest_desc* d, rfx_forest** out) {
     if (!d || !out) return rfx::fail(RFX_ERR_NULL, "rfx_forest_create: null argument");
@@ -229,6 +307,7 @@ int rfx_leaf_assign(const rfx_forest* F, const float* X, int64_t N, int32_t M, u
     const int32_t stride = (M & 1) ? M : M + 1;
     const size_t lds = sizeof(float) * (size_t)kTileSamples * (size_t)stride;
     hipStream_t st = rfx::as_stream(stream);
+    rfx::TimedLaunch timed("leaf_assign_kernel", st);
     if (lds <= 128 * 1024) {
         auto kern = leaf_assign_kernel<true>;
         RFX_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));

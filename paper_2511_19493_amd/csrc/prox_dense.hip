@@ -203,6 +203,7 @@ int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut&
     const int64_t ta = Npad / kATile;
     const int64_t blocks = kRatio * ta * (ta + 1) / 2;
     if (blocks > 0x7fffffffLL) return rfx::fail(RFX_ERR_INVALID_ARG, "proximity: N too large for one launch");
+    rfx::TimedLaunch timed(kOob ? "prox_tile_kernel_oob" : "prox_tile_kernel", st);
     hipLaunchKernelGGL((prox_tile_kernel<P, J, kOob>), dim3((unsigned)blocks), dim3(64 * kWaves), 0, st, planes, Npad, G,
                        out);
     RFX_LAUNCH_CHECK("prox_tile_kernel");

@@ -200,10 +200,14 @@ __global__ __launch_bounds__(256) void pv_gather_kernel(const uint32_t* __restri
 template <int KCH>
 int launch_apply(const rfx_pv_plan* p, const float* V, int32_t k, float* Y, hipStream_t st) {
     const int64_t n_slots = (int64_t)p->B * p->Lb;
-    hipLaunchKernelGGL(pv_leaf_sum_kernel<KCH>, dim3((unsigned)rfx::ceil_div(n_slots, 4)), dim3(256), 0, st,
-                       p->d_seg_start, p->d_perm, n_slots, V, k, p->d_S);
+    {
+        rfx::TimedLaunch timed("pv_leaf_sum_kernel", st);
+        hipLaunchKernelGGL(pv_leaf_sum_kernel<KCH>, dim3((unsigned)rfx::ceil_div(n_slots, 4)), dim3(256), 0, st,
+                           p->d_seg_start, p->d_perm, n_slots, V, k, p->d_S);
+    }
     RFX_LAUNCH_CHECK("pv_leaf_sum_kernel");
     const int64_t tiles = rfx::ceil_div(p->N, kGatherTile);
+    rfx::TimedLaunch timed("pv_gather_kernel", st);
     hipLaunchKernelGGL(pv_gather_kernel<KCH>, dim3((unsigned)rfx::ceil_div(tiles, 4)), dim3(256), 0, st, p->d_slot, p->N,
                        p->B, p->d_S, k, Y);
     RFX_LAUNCH_CHECK("pv_gather_kernel");
