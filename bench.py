@@ -114,7 +114,8 @@ def main():
     rfx.timing_enable(False)
 
     tests = N * N * B / 2.0
-    P = max(1, int(np.ceil(np.log2(max(Lb, 2)))))
+    P = int(np.ceil(np.log2(max(Lb, 2))))
+    P = 8 if P < 8 else (P if P <= 16 else (P + 1) & ~1)   # plane count the library uses for this bound
     # dominant kernel: bit-plane compare-and-count.  One launch covers the tile pairs on and below the
     # diagonal of the (padded) N x N grid, 32 trees per (P+1) vector ops: algorithmic lane-ops per launch
     ops_per_launch = tests * (P + 1) / 32.0

@@ -20,7 +20,10 @@
 
 namespace {
 
-constexpr int kR = 4;           // a samples per lane
+#ifndef RFX_R
+#define RFX_R 4
+#endif
+constexpr int kR = RFX_R;       // a samples per lane
 constexpr int kATile = 64 * kR; // a samples per wave / workgroup
 constexpr int kWaves = 4;
 
@@ -65,6 +68,7 @@ struct TileOut {
     int32_t B;
     int32_t u16;     // counts / num / den are uint16
     int32_t packed;  // strict-upper packed layout
+    int32_t use_tab; // quotient table in LDS (set by the launcher)
 };
 
 __device__ __forceinline__ int64_t packed_index(int64_t i, int64_t j, int64_t N) {
@@ -81,6 +85,116 @@ __device__ __forceinline__ void store_count(void* base, int32_t u16, int64_t at,
         store_one<uint16_t>(base, at, v);
     else
         store_one<uint32_t>(base, at, v);
+}
+
+// 4 consecutive counts at base[at .. at+3]; `at` is a multiple of 4 and the row start is 16-byte aligned
+__device__ __forceinline__ void store4_count(void* base, int32_t u16, int64_t at, const uint32_t (&v)[4]) {
+    if (u16)
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(base) + at) = make_uint2(v[0] | (v[1] << 16), v[2] | (v[3] << 16));
+    else
+        *reinterpret_cast<uint4*>(static_cast<uint32_t*>(base) + at) = make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// Writes one wave tile: mis / den hold, per (r, j), the mismatch count (plain) or the out-of-bag
+// numerator and denominator for the pair (a0 + r, b0 + j).
+template <int J, bool kOob, bool kTab>
+__device__ __forceinline__ void write_tile(const TileOut& out, const float* tab, int64_t a0, int64_t b0,
+                                           const uint32_t (&mis)[kR][J], const uint32_t (&den)[kOob ? kR : 1][kOob ? J : 1]) {
+    const int64_t N = out.N;
+    const float Bf = (float)out.B;
+    if (a0 >= N) return;
+    // proximity value of a plain count: exact IEEE quotient, from the LDS table when there is one
+    auto quotient = [&](uint32_t c) -> float { return kTab ? tab[c] : (float)c / Bf; };
+
+    if (!out.packed && (N & 3) == 0 && b0 + J <= N) {
+        // Full layout, interior tile.  Row b of the output takes this lane's 4 consecutive a values
+        // as one 16-byte (8-byte for uint16) store, contiguous across lanes; the mirrored entries
+        // of row a are J consecutive values per lane, stored 4 at a time.
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            const int64_t at = (b0 + j) * N + a0;
+            uint32_t c[kR], d[kR];
+            float p[kR];
+#pragma unroll
+            for (int r = 0; r < kR; ++r) {
+                c[r] = kOob ? mis[r][j] : (uint32_t)out.B - mis[r][j];
+                d[r] = kOob ? den[r][j] : 0u;
+                if (kOob)
+                    p[r] = (a0 + r == b0 + j) ? 1.0f : (d[r] ? (float)c[r] / (float)d[r] : 0.0f);
+                else
+                    p[r] = quotient(c[r]);
+            }
+            if (out.counts) store4_count(out.counts, out.u16, at, c);
+            if (kOob && out.den) store4_count(out.den, out.u16, at, d);
+            if (out.prox) *reinterpret_cast<float4*>(out.prox + at) = make_float4(p[0], p[1], p[2], p[3]);
+        }
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            const int64_t mt = (a0 + r) * N + b0;
+#pragma unroll
+            for (int q = 0; q < J / 4; ++q) {
+                uint32_t c[4], d[4];
+                float p[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int j = 4 * q + e;
+                    c[e] = kOob ? mis[r][j] : (uint32_t)out.B - mis[r][j];
+                    d[e] = kOob ? den[r][j] : 0u;
+                    if (kOob)
+                        p[e] = (a0 + r == b0 + j) ? 1.0f : (d[e] ? (float)c[e] / (float)d[e] : 0.0f);
+                    else
+                        p[e] = quotient(c[e]);
+                }
+                if (out.counts) store4_count(out.counts, out.u16, mt + 4 * q, c);
+                if (kOob && out.den) store4_count(out.den, out.u16, mt + 4 * q, d);
+                if (out.prox) *reinterpret_cast<float4*>(out.prox + mt + 4 * q) = make_float4(p[0], p[1], p[2], p[3]);
+            }
+        }
+        return;
+    }
+
+    // Packed layout, ragged edge tiles, or N not a multiple of 4: element-wise stores.
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int64_t b = b0 + j;
+        if (b >= N) break;
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            const int64_t a = a0 + r;
+            if (a >= N) continue;
+            uint32_t c = kOob ? mis[r][j] : (uint32_t)out.B - mis[r][j];
+            uint32_t d = kOob ? den[r][j] : (uint32_t)out.B;
+            float p;
+            if (a == b)
+                p = 1.0f;
+            else if (kOob)
+                p = d ? (float)c / (float)d : 0.0f;
+            else
+                p = quotient(c);
+            if (out.packed) {
+                if (b < a) {
+                    const int64_t at = packed_index(b, a, N);
+                    if (out.counts) store_count(out.counts, out.u16, at, c);
+                    if (kOob && out.den) store_count(out.den, out.u16, at, d);
+                    if (out.prox) out.prox[at] = p;
+                }
+            } else {
+                const int64_t at = b * N + a, mt = a * N + b;
+                if (out.counts) {
+                    store_count(out.counts, out.u16, at, c);
+                    store_count(out.counts, out.u16, mt, c);
+                }
+                if (kOob && out.den) {
+                    store_count(out.den, out.u16, at, d);
+                    store_count(out.den, out.u16, mt, d);
+                }
+                if (out.prox) {
+                    out.prox[at] = p;
+                    out.prox[mt] = p;
+                }
+            }
+        }
+    }
 }
 
 // P = number of leaf-id bit planes, J = b samples per wave, kOob = out-of-bag variant.
@@ -104,6 +218,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void prox_tile_kernel(const uint32_
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t a0 = ta * kATile + lane * kR;
     const int64_t b0 = __builtin_amdgcn_readfirstlane((int)(tb * kBTile + wave * J));
+
+    // table of the quotients c / B, c = 0..B (plain variant with a float32 output only)
+    extern __shared__ float tab[];
+    if (out.use_tab) {
+        for (int c = threadIdx.x; c <= out.B; c += 64 * kWaves) tab[c] = (float)c / (float)out.B;
+        __syncthreads();
+    }
 
     uint32_t mis[kR][J];
     uint32_t den[kOob ? kR : 1][kOob ? J : 1];
@@ -151,50 +272,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void prox_tile_kernel(const uint32_
         }
     }
 
-    // ---- epilogue: one write per pair -------------------------------------------------------
-    const int64_t N = out.N;
-    const float Bf = (float)out.B;
-#pragma unroll
-    for (int j = 0; j < J; ++j) {
-        const int64_t b = b0 + j;
-        if (b >= N) break;
-#pragma unroll
-        for (int r = 0; r < kR; ++r) {
-            const int64_t a = a0 + r;
-            if (a >= N) continue;
-            uint32_t c = kOob ? mis[r][j] : (uint32_t)out.B - mis[r][j];
-            uint32_t d = kOob ? den[r][j] : (uint32_t)out.B;
-            float p;
-            if (a == b)
-                p = 1.0f;
-            else if (kOob)
-                p = d ? (float)c / (float)d : 0.0f;
-            else
-                p = (float)c / Bf;
-            if (out.packed) {
-                if (b < a) {
-                    const int64_t at = packed_index(b, a, N);
-                    if (out.counts) store_count(out.counts, out.u16, at, c);
-                    if (kOob && out.den) store_count(out.den, out.u16, at, d);
-                    if (out.prox) out.prox[at] = p;
-                }
-            } else {
-                const int64_t at = b * N + a, mt = a * N + b;
-                if (out.counts) {
-                    store_count(out.counts, out.u16, at, c);
-                    store_count(out.counts, out.u16, mt, c);
-                }
-                if (kOob && out.den) {
-                    store_count(out.den, out.u16, at, d);
-                    store_count(out.den, out.u16, mt, d);
-                }
-                if (out.prox) {
-                    out.prox[at] = p;
-                    out.prox[mt] = p;
-                }
-            }
-        }
-    }
+    if (out.use_tab)
+        write_tile<J, kOob, true>(out, tab, a0, b0, mis, den);
+    else
+        write_tile<J, kOob, false>(out, tab, a0, b0, mis, den);
 }
 
 template <int P, int J, bool kOob>
@@ -203,23 +284,32 @@ int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut&
     const int64_t ta = Npad / kATile;
     const int64_t blocks = kRatio * ta * (ta + 1) / 2;
     if (blocks > 0x7fffffffLL) return rfx::fail(RFX_ERR_INVALID_ARG, "proximity: N too large for one launch");
+    TileOut o = out;
+    o.use_tab = (!kOob && out.prox && out.B < 8192) ? 1 : 0;
+    const size_t lds = o.use_tab ? sizeof(float) * (size_t)(out.B + 1) : 0;
     rfx::TimedLaunch timed(kOob ? "prox_tile_kernel_oob" : "prox_tile_kernel", st);
-    hipLaunchKernelGGL((prox_tile_kernel<P, J, kOob>), dim3((unsigned)blocks), dim3(64 * kWaves), 0, st, planes, Npad, G,
-                       out);
+    hipLaunchKernelGGL((prox_tile_kernel<P, J, kOob>), dim3((unsigned)blocks), dim3(64 * kWaves), lds, st, planes, Npad, G,
+                       o);
     RFX_LAUNCH_CHECK("prox_tile_kernel");
     return RFX_OK;
 }
 
 template <bool kOob>
 int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, hipStream_t st) {
-    constexpr int J = kOob ? 16 : 32;
+#ifndef RFX_J_PLAIN
+#define RFX_J_PLAIN 16
+#endif
+    constexpr int J = kOob ? 16 : RFX_J_PLAIN;
     switch (P) {
 #define RFX_CASE(p) \
     case p:         \
         return launch_tiles<p, J, kOob>(planes, Npad, G, out, st);
-        RFX_CASE(1) RFX_CASE(2) RFX_CASE(3) RFX_CASE(4) RFX_CASE(5) RFX_CASE(6) RFX_CASE(7) RFX_CASE(8)
-        RFX_CASE(9) RFX_CASE(10) RFX_CASE(11) RFX_CASE(12) RFX_CASE(13) RFX_CASE(14) RFX_CASE(15) RFX_CASE(16)
-        RFX_CASE(17) RFX_CASE(18) RFX_CASE(19) RFX_CASE(20) RFX_CASE(21) RFX_CASE(22) RFX_CASE(23) RFX_CASE(24)
+#ifdef RFX_ONLY_P  // development builds: a single plane count compiles in seconds
+        RFX_CASE(RFX_ONLY_P)
+#else
+        RFX_CASE(8) RFX_CASE(9) RFX_CASE(10) RFX_CASE(11) RFX_CASE(12) RFX_CASE(13) RFX_CASE(14) RFX_CASE(15)
+        RFX_CASE(16) RFX_CASE(18) RFX_CASE(20) RFX_CASE(22) RFX_CASE(24)
+#endif
 #undef RFX_CASE
     }
     return rfx::fail(RFX_ERR_INVALID_ARG, "proximity: %d bit planes", P);
@@ -240,16 +330,20 @@ int check_common(const char* who, const void* leaf, int64_t N, int32_t B, int32_
     return RFX_OK;
 }
 
-int bits_for(int32_t leaf_bound) {
+// Number of bit planes used for ids below leaf_bound: the exact width from 9 to 16 bits, at least 8
+// (narrower ids are rare and extra zero planes never mismatch), even above 16.  One kernel
+// instantiation exists per value returned here.
+int planes_for(int32_t leaf_bound) {
     int P = 1;
     while ((1 << P) < leaf_bound) ++P;
-    return P;
+    if (P < 8) return 8;
+    return P <= 16 ? P : (P + 1) & ~1;
 }
 
 template <bool kOob>
 int run(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound, const TileOut& out,
         hipStream_t st) {
-    const int P = bits_for(leaf_bound);
+    const int P = planes_for(leaf_bound);
     const int PS = plane_stride(P);
     const int32_t G = (B + 31) / 32;
     const int64_t Npad = rfx::ceil_div(N, kATile) * kATile;
@@ -275,7 +369,7 @@ int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_boun
     int rc = check_common("rfx_prox_dense", leaf, N, B, leaf_bound, count_dtype, layout);
     if (rc != RFX_OK) return rc;
     if (!counts && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_dense: neither counts nor prox given");
-    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED};
+    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0};
     return run<false>(leaf, nullptr, N, B, leaf_bound, out, rfx::as_stream(stream));
 }
 
@@ -285,7 +379,7 @@ int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t
     if (rc != RFX_OK) return rc;
     if (!inbag) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: inbag is null");
     if (!num && !den && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: no output given");
-    TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED};
+    TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0};
     return run<true>(leaf, inbag, N, B, leaf_bound, out, rfx::as_stream(stream));
 }
 

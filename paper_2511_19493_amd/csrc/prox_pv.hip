@@ -115,8 +115,20 @@ __global__ __launch_bounds__(64) void pv_scatter_kernel(const uint32_t* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
-// Leaf sums.  One wave per slot; lanes are columns (KCH columns per lane, stride 64).
-template <int KCH>
+// Column handled by a lane.  RPW = rows (samples) a wave touches with one load instruction:
+// 1 for k > 32 (lanes are columns lane, lane+64, ...), 2 for 16 < k <= 32, 4 for k <= 16 (each
+// group of 64/RPW lanes is one row).  Lanes beyond k read a clamped column and are never stored,
+// which keeps every load unconditional so that the loads of a batch are all in flight together.
+template <int RPW>
+__device__ __forceinline__ int lane_col(int lane) {
+    return lane & (64 / RPW - 1);
+}
+
+// Leaf sums.  One wave per slot; the RPW lane groups take members t, t+RPW, ... of the slot in
+// batches of kSumBatch loads, and their partial sums are added in group order at the end.
+constexpr int kSumBatch = 8;
+
+template <int KCH, int RPW>
 __global__ __launch_bounds__(256) void pv_leaf_sum_kernel(const uint32_t* __restrict__ seg_start,
                                                          const uint32_t* __restrict__ perm, int64_t n_slots,
                                                          const float* __restrict__ V, int32_t k, float* __restrict__ S) {
@@ -125,91 +137,124 @@ __global__ __launch_bounds__(256) void pv_leaf_sum_kernel(const uint32_t* __rest
     if (slot >= n_slots) return;
     const uint32_t lo = seg_start[slot], hi = seg_start[slot + 1];
     if (lo == hi) return;  // empty leaf: its row of S is never read
+    const int grp = lane / (64 / RPW);
+    int col[KCH];
+#pragma unroll
+    for (int c = 0; c < KCH; ++c) col[c] = min(lane_col<RPW>(lane) + 64 * c, k - 1);
     float acc[KCH];
 #pragma unroll
     for (int c = 0; c < KCH; ++c) acc[c] = 0.0f;
-    uint32_t t = lo;
-    for (; t + 4 <= hi; t += 4) {
-        const uint32_t j0 = perm[t], j1 = perm[t + 1], j2 = perm[t + 2], j3 = perm[t + 3];
+    for (uint32_t t0 = lo; t0 < hi; t0 += kSumBatch * RPW) {
+        float v[kSumBatch][KCH];
 #pragma unroll
-        for (int c = 0; c < KCH; ++c) {
-            const int col = lane + 64 * c;
-            if (col < k) {
-                const float v0 = V[(int64_t)j0 * k + col], v1 = V[(int64_t)j1 * k + col];
-                const float v2 = V[(int64_t)j2 * k + col], v3 = V[(int64_t)j3 * k + col];
-                acc[c] = (((acc[c] + v0) + v1) + v2) + v3;
-            }
+        for (int u = 0; u < kSumBatch; ++u) {
+            const uint32_t t = t0 + u * RPW + grp;
+            const uint32_t j = perm[min(t, hi - 1)];   // clamped: always a valid member
+#pragma unroll
+            for (int c = 0; c < KCH; ++c) v[u][c] = V[(int64_t)j * k + col[c]];
+        }
+#pragma unroll
+        for (int u = 0; u < kSumBatch; ++u) {
+            const bool live = t0 + u * RPW + grp < hi;
+#pragma unroll
+            for (int c = 0; c < KCH; ++c) acc[c] += live ? v[u][c] : 0.0f;
         }
     }
-    for (; t < hi; ++t) {
-        const uint32_t j = perm[t];
+    if (RPW > 1) {
 #pragma unroll
         for (int c = 0; c < KCH; ++c) {
-            const int col = lane + 64 * c;
-            if (col < k) acc[c] += V[(int64_t)j * k + col];
+            float tot = acc[c];
+#pragma unroll
+            for (int g = 1; g < RPW; ++g) tot += __shfl(acc[c], lane_col<RPW>(lane) + g * (64 / RPW));
+            acc[c] = tot;
         }
     }
+    if (grp == 0) {
 #pragma unroll
-    for (int c = 0; c < KCH; ++c) {
-        const int col = lane + 64 * c;
-        if (col < k) S[slot * k + col] = acc[c];
+        for (int c = 0; c < KCH; ++c) {
+            const int cc = lane_col<RPW>(lane) + 64 * c;
+            if (cc < k) S[slot * k + cc] = acc[c];
+        }
     }
 }
 
-// Gather.  A wave owns kGatherTile consecutive samples and sweeps all trees in order.
-template <int KCH>
+// Gather.  A wave owns kGatherTile consecutive samples and sweeps all trees in order, two trees
+// per step; all row loads of a step are issued before any is consumed.
+constexpr int kGatherTrees = 2;
+
+template <int KCH, int RPW>
 __global__ __launch_bounds__(256) void pv_gather_kernel(const uint32_t* __restrict__ slot, int64_t N, int32_t B,
                                                        const float* __restrict__ S, int32_t k, float* __restrict__ Y) {
+    constexpr int kSteps = kGatherTile / RPW;  // load instructions per tree
     const int lane = threadIdx.x & 63;
     const int64_t tile = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t i0 = tile * kGatherTile;
     if (i0 >= N) return;
     const int rows = (int)min((int64_t)kGatherTile, N - i0);
-    float acc[kGatherTile][KCH];
+    const int grp = lane / (64 / RPW);
+    int col[KCH];
 #pragma unroll
-    for (int s = 0; s < kGatherTile; ++s)
+    for (int c = 0; c < KCH; ++c) col[c] = min(lane_col<RPW>(lane) + 64 * c, k - 1);
+    float acc[kSteps][KCH];
+#pragma unroll
+    for (int s = 0; s < kSteps; ++s)
 #pragma unroll
         for (int c = 0; c < KCH; ++c) acc[s][c] = 0.0f;
-    for (int b = 0; b < B; ++b) {
-        const uint32_t mine = (lane < rows) ? slot[(int64_t)b * N + i0 + lane] : 0u;
+    // lane l < 32 carries the slot of sample i0 + l (clamped to the tile's last valid row)
+    const int64_t my_row = i0 + min(lane & (kGatherTile - 1), rows - 1);
+    for (int b = 0; b < B; b += kGatherTrees) {
+        uint32_t mine[kGatherTrees];
 #pragma unroll
-        for (int s = 0; s < kGatherTile; ++s) {
-            const uint32_t row = __builtin_amdgcn_readlane(mine, s);
-            if (s < rows) {
+        for (int t = 0; t < kGatherTrees; ++t) mine[t] = slot[(int64_t)min(b + t, B - 1) * N + my_row];
+        float v[kGatherTrees][kSteps][KCH];
 #pragma unroll
-                for (int c = 0; c < KCH; ++c) {
-                    const int col = lane + 64 * c;
-                    if (col < k) acc[s][c] += S[(int64_t)row * k + col];
-                }
+        for (int t = 0; t < kGatherTrees; ++t)
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s) {
+                uint32_t row;
+                if (RPW == 1)
+                    row = __builtin_amdgcn_readlane(mine[t], s);
+                else
+                    row = __shfl(mine[t], s * RPW + grp);
+#pragma unroll
+                for (int c = 0; c < KCH; ++c) v[t][s][c] = S[(int64_t)row * k + col[c]];
             }
+#pragma unroll
+        for (int t = 0; t < kGatherTrees; ++t) {
+            const bool live = b + t < B;
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s)
+#pragma unroll
+                for (int c = 0; c < KCH; ++c) acc[s][c] += live ? v[t][s][c] : 0.0f;
         }
     }
     const float Bf = (float)B;
 #pragma unroll
-    for (int s = 0; s < kGatherTile; ++s) {
-        if (s < rows) {
+    for (int s = 0; s < kSteps; ++s) {
+        const int r = s * RPW + grp;
+        if (r < rows) {
 #pragma unroll
             for (int c = 0; c < KCH; ++c) {
-                const int col = lane + 64 * c;
-                if (col < k) Y[(i0 + s) * k + col] = acc[s][c] / Bf;
+                const int cc = lane_col<RPW>(lane) + 64 * c;
+                if (cc < k) Y[(i0 + r) * k + cc] = acc[s][c] / Bf;
             }
         }
     }
 }
 
-template <int KCH>
+template <int KCH, int RPW>
 int launch_apply(const rfx_pv_plan* p, const float* V, int32_t k, float* Y, hipStream_t st) {
     const int64_t n_slots = (int64_t)p->B * p->Lb;
     {
         rfx::TimedLaunch timed("pv_leaf_sum_kernel", st);
-        hipLaunchKernelGGL(pv_leaf_sum_kernel<KCH>, dim3((unsigned)rfx::ceil_div(n_slots, 4)), dim3(256), 0, st,
+        hipLaunchKernelGGL((pv_leaf_sum_kernel<KCH, RPW>), dim3((unsigned)rfx::ceil_div(n_slots, 4)), dim3(256), 0, st,
                            p->d_seg_start, p->d_perm, n_slots, V, k, p->d_S);
     }
     RFX_LAUNCH_CHECK("pv_leaf_sum_kernel");
     const int64_t tiles = rfx::ceil_div(p->N, kGatherTile);
     rfx::TimedLaunch timed("pv_gather_kernel", st);
-    hipLaunchKernelGGL(pv_gather_kernel<KCH>, dim3((unsigned)rfx::ceil_div(tiles, 4)), dim3(256), 0, st, p->d_slot, p->N,
-                       p->B, p->d_S, k, Y);
+    hipLaunchKernelGGL((pv_gather_kernel<KCH, RPW>), dim3((unsigned)rfx::ceil_div(tiles, 4)), dim3(256), 0, st, p->d_slot,
+                       p->N, p->B, p->d_S, k, Y);
     RFX_LAUNCH_CHECK("pv_gather_kernel");
     return RFX_OK;
 }
@@ -287,11 +332,13 @@ int rfx_pv_apply(rfx_pv_plan* p, const float* V, int32_t k, float* Y, void* stre
         RFX_HIP(hipMalloc((void**)&p->d_S, sizeof(float) * (size_t)p->B * (size_t)p->Lb * (size_t)k));
         p->k_cap = k;
     }
+    if (k <= 16) return launch_apply<1, 4>(p, V, k, Y, st);
+    if (k <= 32) return launch_apply<1, 2>(p, V, k, Y, st);
     switch ((k + 63) / 64) {
-        case 1: return launch_apply<1>(p, V, k, Y, st);
-        case 2: return launch_apply<2>(p, V, k, Y, st);
-        case 3: return launch_apply<3>(p, V, k, Y, st);
-        default: return launch_apply<4>(p, V, k, Y, st);
+        case 1: return launch_apply<1, 1>(p, V, k, Y, st);
+        case 2: return launch_apply<2, 1>(p, V, k, Y, st);
+        case 3: return launch_apply<3, 1>(p, V, k, Y, st);
+        default: return launch_apply<4, 1>(p, V, k, Y, st);
     }
 }
 

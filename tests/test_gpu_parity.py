@@ -87,6 +87,18 @@ def test_prox_dense_packed_u16_ragged(torch_cuda, small2):
     cnt2, none = rfx.prox_dense(_dev_leaf(torch, leaf), int(leaf.max()) + 1, rfx.U32, rfx.FULL, want_prox=False)
     assert none is None
     np.testing.assert_array_equal(_u(cnt2), ref)
+    # full layout with N a multiple of 4 takes the vector-store path: uint16 counts and float32 quotients
+    cnt3, prox3 = rfx.prox_dense(_dev_leaf(torch, leaf), int(leaf.max()) + 1, rfx.U16, rfx.FULL)
+    np.testing.assert_array_equal(_u(cnt3), ref.astype(np.uint16))
+    np.testing.assert_array_equal(prox3.cpu().numpy(), oracle.normalise(ref, B))
+    # out-of-bag variant, full layout, same path
+    inbag = small2["F"].inbag
+    num, den, poob = rfx.prox_oob(_dev_leaf(torch, leaf), torch.from_numpy(inbag.view(np.int16)).cuda(),
+                                  int(leaf.max()) + 1, rfx.U16, rfx.FULL)
+    rn, rd = oracle.oob_rows(leaf, inbag, 0, N)
+    np.testing.assert_array_equal(_u(num), rn.astype(np.uint16))
+    np.testing.assert_array_equal(_u(den), rd.astype(np.uint16))
+    np.testing.assert_array_equal(poob.cpu().numpy(), oracle.prox_oob_rows(rn, rd, 0))
 
 
 @pytest.mark.parametrize("bound", [1, 2, 3, 17, 300, 70000])
