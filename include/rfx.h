@@ -117,8 +117,8 @@ int rfx_leaf_assign(const rfx_forest* forest, const float* X, int64_t N, int32_t
  *   layout      RFX_FULL or RFX_UPPER_PACKED, applies to both outputs
  *   counts      [device] nullable; cnt(i,j) = #{b : leaf_b(i) = leaf_b(j)}; diagonal = B
  *   prox        [device] nullable float32; cnt / B in IEEE float32 division; diagonal = 1
- * At least one of counts / prox must be given.  Asynchronous apart from scratch management
- * (the call returns after its kernels have finished).
+ * At least one of counts / prox must be given.  Synchronous (the bit-plane scratch is freed
+ * before returning).
  * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_OVERFLOW, RFX_ERR_OOM. */
 int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
                    void* counts, float* prox, void* stream);
@@ -128,7 +128,8 @@ int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_boun
  *   num(i,j) = #{b in OOB_i and OOB_j : leaf_b(i) = leaf_b(j)},  den(i,j) = |OOB_i and OOB_j|,
  *   prox(i,j) = num/den in IEEE float32 division, 0 where den = 0, 1 on the diagonal.
  *   inbag [device] uint16 [B][N];  num, den, prox [device] nullable (at least one given);
- *   other arguments as rfx_prox_dense.  Diagonal of num and den in RFX_FULL = |OOB_i|. */
+ *   other arguments as rfx_prox_dense.  Diagonal of num and den in RFX_FULL = |OOB_i|.
+ * B <= 65535 (numerator and denominator share one 32-bit counter), else RFX_ERR_UNSUPPORTED. */
 int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
                  int count_dtype, int layout, void* num, void* den, float* prox, void* stream);
 

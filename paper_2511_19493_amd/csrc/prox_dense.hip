@@ -16,6 +16,8 @@
 // counters live in vector registers for the whole tree loop and are written once.  Four waves
 // of a workgroup share the a samples (L1 hits) and take consecutive b ranges.  Only tile pairs
 // on or below the diagonal are launched.
+#include <algorithm>
+
 #include "common.h"
 
 namespace {
@@ -95,59 +97,83 @@ __device__ __forceinline__ void store4_count(void* base, int32_t u16, int64_t at
         *reinterpret_cast<uint4*>(static_cast<uint32_t*>(base) + at) = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-// Writes one wave tile: mis / den hold, per (r, j), the mismatch count (plain) or the out-of-bag
-// numerator and denominator for the pair (a0 + r, b0 + j).
+// Writes one wave tile.  acc[r][j] belongs to the pair (a_tile + 4*lane + r, b0 + j): the mismatch
+// count (plain), or the out-of-bag numerator in bits 0..15 and denominator in bits 16..31.  `tr` is
+// this wave's LDS transposition buffer: 64 rows of J + 4 words.
 template <int J, bool kOob, bool kTab>
-__device__ __forceinline__ void write_tile(const TileOut& out, const float* tab, int64_t a0, int64_t b0,
-                                           const uint32_t (&mis)[kR][J], const uint32_t (&den)[kOob ? kR : 1][kOob ? J : 1]) {
+__device__ __forceinline__ void write_tile(const TileOut& out, const float* tab, uint32_t* tr, int lane, int64_t a_tile,
+                                           int64_t b0, const uint32_t (&acc)[kR][J]) {
+    static_assert(kR == 4 && J % 4 == 0 && 256 % J == 0, "tile shape assumed by the vector stores");
     const int64_t N = out.N;
     const float Bf = (float)out.B;
-    if (a0 >= N) return;
+    const int64_t a0 = a_tile + kR * lane;
     // proximity value of a plain count: exact IEEE quotient, from the LDS table when there is one
     auto quotient = [&](uint32_t c) -> float { return kTab ? tab[c] : (float)c / Bf; };
+    auto oob_quotient = [&](uint32_t c, uint32_t d, bool diag) -> float {
+        return diag ? 1.0f : (d ? (float)c / (float)d : 0.0f);
+    };
 
     if (!out.packed && (N & 3) == 0 && b0 + J <= N) {
-        // Full layout, interior tile.  Row b of the output takes this lane's 4 consecutive a values
-        // as one 16-byte (8-byte for uint16) store, contiguous across lanes; the mirrored entries
-        // of row a are J consecutive values per lane, stored 4 at a time.
+        // Full layout, interior tile.  Row b of the output takes this lane's 4 consecutive a values as
+        // one 16-byte (8-byte for uint16) store, contiguous across lanes.
+        if (a0 < N) {
 #pragma unroll
-        for (int j = 0; j < J; ++j) {
-            const int64_t at = (b0 + j) * N + a0;
-            uint32_t c[kR], d[kR];
-            float p[kR];
+            for (int j = 0; j < J; ++j) {
+                const int64_t at = (b0 + j) * N + a0;
+                uint32_t c[kR], d[kR];
+                float p[kR];
 #pragma unroll
-            for (int r = 0; r < kR; ++r) {
-                c[r] = kOob ? mis[r][j] : (uint32_t)out.B - mis[r][j];
-                d[r] = kOob ? den[r][j] : 0u;
-                if (kOob)
-                    p[r] = (a0 + r == b0 + j) ? 1.0f : (d[r] ? (float)c[r] / (float)d[r] : 0.0f);
-                else
-                    p[r] = quotient(c[r]);
+                for (int r = 0; r < kR; ++r) {
+                    c[r] = kOob ? (acc[r][j] & 0xffffu) : (uint32_t)out.B - acc[r][j];
+                    d[r] = kOob ? (acc[r][j] >> 16) : 0u;
+                    p[r] = kOob ? oob_quotient(c[r], d[r], a0 + r == b0 + j) : quotient(c[r]);
+                }
+                if (out.counts) store4_count(out.counts, out.u16, at, c);
+                if (kOob && out.den) store4_count(out.den, out.u16, at, d);
+                if (out.prox) *reinterpret_cast<float4*>(out.prox + at) = make_float4(p[0], p[1], p[2], p[3]);
+                __builtin_amdgcn_sched_barrier(0);  // keep each store's address arithmetic next to it
             }
-            if (out.counts) store4_count(out.counts, out.u16, at, c);
-            if (kOob && out.den) store4_count(out.den, out.u16, at, d);
-            if (out.prox) *reinterpret_cast<float4*>(out.prox + at) = make_float4(p[0], p[1], p[2], p[3]);
         }
+        // Mirrored entries: row a takes J consecutive values.  They are transposed through LDS, one r
+        // at a time, so that J/4 adjacent lanes write one row's J values as a contiguous run instead of
+        // every lane writing 16-byte pieces of a row of its own.
+        constexpr int TS = J + 4;     // LDS words per source lane
+        constexpr int LPR = J / 4;    // lanes per row when reading back
+        constexpr int RPI = 64 / LPR; // rows per read instruction
 #pragma unroll
         for (int r = 0; r < kR; ++r) {
-            const int64_t mt = (a0 + r) * N + b0;
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int q = 0; q < J / 4; ++q)
+                *reinterpret_cast<uint4*>(tr + lane * TS + 4 * q) =
+                    make_uint4(acc[r][4 * q], acc[r][4 * q + 1], acc[r][4 * q + 2], acc[r][4 * q + 3]);
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int q = 0; q < J / 4; ++q) {
-                uint32_t c[4], d[4];
-                float p[4];
+                const int row = q * RPI + lane / LPR;  // source lane whose values this lane writes out
+                const int col = 4 * (lane % LPR);
+                const int64_t a = a_tile + kR * row + r;
+                const uint4 v = *reinterpret_cast<const uint4*>(tr + row * TS + col);
+                if (a < N) {
+                    const int64_t mt = a * N + b0 + col;
+                    const uint32_t raw[4] = {v.x, v.y, v.z, v.w};
+                    uint32_t c[4], d[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int j = 4 * q + e;
-                    c[e] = kOob ? mis[r][j] : (uint32_t)out.B - mis[r][j];
-                    d[e] = kOob ? den[r][j] : 0u;
-                    if (kOob)
-                        p[e] = (a0 + r == b0 + j) ? 1.0f : (d[e] ? (float)c[e] / (float)d[e] : 0.0f);
-                    else
-                        p[e] = quotient(c[e]);
+                    for (int e = 0; e < 4; ++e) {
+                        c[e] = kOob ? (raw[e] & 0xffffu) : (uint32_t)out.B - raw[e];
+                        d[e] = kOob ? (raw[e] >> 16) : 0u;
+                    }
+                    if (out.counts) store4_count(out.counts, out.u16, mt, c);
+                    if (kOob && out.den) store4_count(out.den, out.u16, mt, d);
+                    if (out.prox) {
+                        float p[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            p[e] = kOob ? oob_quotient(c[e], d[e], a == b0 + col + e) : quotient(c[e]);
+                        *reinterpret_cast<float4*>(out.prox + mt) = make_float4(p[0], p[1], p[2], p[3]);
+                    }
                 }
-                if (out.counts) store4_count(out.counts, out.u16, mt + 4 * q, c);
-                if (kOob && out.den) store4_count(out.den, out.u16, mt + 4 * q, d);
-                if (out.prox) *reinterpret_cast<float4*>(out.prox + mt + 4 * q) = make_float4(p[0], p[1], p[2], p[3]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         return;
@@ -162,8 +188,8 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
         for (int r = 0; r < kR; ++r) {
             const int64_t a = a0 + r;
             if (a >= N) continue;
-            uint32_t c = kOob ? mis[r][j] : (uint32_t)out.B - mis[r][j];
-            uint32_t d = kOob ? den[r][j] : (uint32_t)out.B;
+            uint32_t c = kOob ? (acc[r][j] & 0xffffu) : (uint32_t)out.B - acc[r][j];
+            uint32_t d = kOob ? (acc[r][j] >> 16) : (uint32_t)out.B;
             float p;
             if (a == b)
                 p = 1.0f;
@@ -197,44 +223,60 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
     }
 }
 
+#ifndef RFX_PLAIN_WAVES
+#define RFX_PLAIN_WAVES 4
+#endif
+// waves per SIMD the register allocation aims for: the plain kernel's main loop fits 128 VGPRs
+#define RFX_MIN_WAVES(oob) RFX_PLAIN_WAVES
+
 // P = number of leaf-id bit planes, J = b samples per wave, kOob = out-of-bag variant.
 template <int P, int J, bool kOob>
-__global__ __launch_bounds__(64 * kWaves, 2) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
-                                                                 int32_t G, TileOut out) {
+__global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kOob)) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
+                                                                 int32_t G, int32_t n_tile_rows, TileOut out) {
     constexpr int PS = plane_stride(P);
     constexpr int PL = kOob ? P + 1 : P;     // words of a sample actually used
     constexpr int PV = (PL + 3) / 4;         // 16-byte loads per a sample
     constexpr int kBTile = J * kWaves;
     constexpr int kRatio = kATile / kBTile;  // b tiles per a tile
 
-    // triangular tile index: a tile `ta` pairs with b tiles 0 .. (ta+1)*kRatio - 1
-    const int64_t id = blockIdx.x;
-    int64_t ta = (int64_t)((sqrt(8.0 * (double)id / kRatio + 1.0) - 1.0) * 0.5);
-    while (kRatio * (ta + 1) * (ta + 2) / 2 <= id) ++ta;
-    while (kRatio * ta * (ta + 1) / 2 > id) --ta;
-    const int64_t tb = id - kRatio * ta * (ta + 1) / 2;
+    // Tile index.  A tile row `ta` (256 a samples) pairs with b tiles 0 .. (ta+1)*kRatio - 1.
+    // Consecutive workgroup ids go to the 8 XCDs in turn, so XCD x = id % 8 is given the tile rows
+    // ta = x, x+8, x+16, ... and walks each of them from b tile 0 upwards: the workgroups an XCD runs
+    // at any moment share their a planes in that XCD's L2 and write neighbouring column ranges of the
+    // same 256 output rows.  Before row number m of an XCD's list it has done
+    // kRatio * (m*(x+1) + 4*m*(m-1)) tiles.
+    const int64_t x = blockIdx.x & 7, l = blockIdx.x >> 3;
+    auto before = [&](int64_t m) { return (int64_t)kRatio * (m * (x + 1) + 4 * m * (m - 1)); };
+    int64_t m = (int64_t)((-(double)(x - 3) + sqrt((double)((x - 3) * (x - 3)) + 16.0 * (double)l / kRatio)) / 8.0);
+    if (m < 0) m = 0;
+    while (before(m + 1) <= l) ++m;
+    while (m > 0 && before(m) > l) --m;
+    const int64_t ta = x + 8 * m;
+    const int64_t tb = l - before(m);
+    if (ta >= n_tile_rows) return;  // the XCDs' lists differ in length; the grid covers the longest
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t a0 = ta * kATile + lane * kR;
     const int64_t b0 = __builtin_amdgcn_readfirstlane((int)(tb * kBTile + wave * J));
 
-    // table of the quotients c / B, c = 0..B (plain variant with a float32 output only)
-    extern __shared__ float tab[];
+    // LDS: per-wave transposition buffers for the epilogue, then the table of the quotients c / B,
+    // c = 0..B (plain variant with a float32 output only)
+    extern __shared__ uint32_t lds[];
+    constexpr int kTrWords = 64 * (J + 4);
+    uint32_t* tr = lds + wave * kTrWords;
+    float* tab = reinterpret_cast<float*>(lds + kWaves * kTrWords);
     if (out.use_tab) {
         for (int c = threadIdx.x; c <= out.B; c += 64 * kWaves) tab[c] = (float)c / (float)out.B;
         __syncthreads();
     }
 
-    uint32_t mis[kR][J];
-    uint32_t den[kOob ? kR : 1][kOob ? J : 1];
+    // per pair: mismatching trees (plain), or out-of-bag numerator | denominator << 16
+    uint32_t acc[kR][J];
 #pragma unroll
     for (int r = 0; r < kR; ++r)
 #pragma unroll
-        for (int j = 0; j < J; ++j) {
-            mis[r][j] = 0;
-            if (kOob) den[r][j] = 0;
-        }
+        for (int j = 0; j < J; ++j) acc[r][j] = 0;
 
     for (int g = 0; g < G; ++g) {
         const uint4* pa = reinterpret_cast<const uint4*>(planes + ((int64_t)g * Npad + a0) * PS);
@@ -254,7 +296,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void prox_tile_kernel(const uint32_
         for (int j = 0; j < J; ++j) {
             uint32_t xb[PL];
 #pragma unroll
-            for (int p = 0; p < PL; ++p) xb[p] = pb[j * PS + p];
+            for (int p = 0; p < PL; ++p) xb[p] = pb[j * PS + p];  // uniform address: scalar loads into SGPRs
 #pragma unroll
             for (int r = 0; r < kR; ++r) {
                 uint32_t t = xa[r][0] ^ xb[0];
@@ -262,34 +304,42 @@ __global__ __launch_bounds__(64 * kWaves, 2) void prox_tile_kernel(const uint32_
                 for (int p = 1; p < P; ++p) t = __builtin_amdgcn_bitop3_b32(t, xa[r][p], xb[p], 0xf6);  // t | (a ^ b)
                 if (kOob) {
                     // trees where both are out-of-bag and the leaves agree: ~t & oa & ob
-                    uint32_t both_same = __builtin_amdgcn_bitop3_b32(t, xa[r][P], xb[P], 0x08);
-                    mis[r][j] += __builtin_popcount(both_same);
-                    den[r][j] += __builtin_popcount(xa[r][P] & xb[P]);
+                    const uint32_t both_same = __builtin_amdgcn_bitop3_b32(t, xa[r][P], xb[P], 0x08);
+                    const uint32_t both = xa[r][P] & xb[P];
+                    acc[r][j] += __builtin_popcount(both_same);
+                    acc[r][j] += (uint32_t)__builtin_popcount(both) << 16;
                 } else {
-                    mis[r][j] += __builtin_popcount(t);
+                    acc[r][j] += __builtin_popcount(t);
                 }
             }
         }
     }
 
     if (out.use_tab)
-        write_tile<J, kOob, true>(out, tab, a0, b0, mis, den);
+        write_tile<J, kOob, true>(out, tab, tr, lane, ta * kATile, b0, acc);
     else
-        write_tile<J, kOob, false>(out, tab, a0, b0, mis, den);
+        write_tile<J, kOob, false>(out, tab, tr, lane, ta * kATile, b0, acc);
 }
 
 template <int P, int J, bool kOob>
 int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, hipStream_t st) {
     constexpr int kRatio = kATile / (J * kWaves);
-    const int64_t ta = Npad / kATile;
-    const int64_t blocks = kRatio * ta * (ta + 1) / 2;
+    const int64_t rows = Npad / kATile;
+    // XCD x works through tile rows x, x+8, ...; the last XCD that has `cnt` rows has the longest list
+    int64_t longest = 0;
+    for (int64_t x = 0; x < 8 && x < rows; ++x) {
+        const int64_t cnt = (rows - x + 7) / 8;
+        longest = std::max(longest, (int64_t)kRatio * (cnt * (x + 1) + 4 * cnt * (cnt - 1)));
+    }
+    const int64_t blocks = 8 * longest;
     if (blocks > 0x7fffffffLL) return rfx::fail(RFX_ERR_INVALID_ARG, "proximity: N too large for one launch");
     TileOut o = out;
     o.use_tab = (!kOob && out.prox && out.B < 8192) ? 1 : 0;
-    const size_t lds = o.use_tab ? sizeof(float) * (size_t)(out.B + 1) : 0;
+    const size_t lds = sizeof(uint32_t) * kWaves * 64 * (J + 4) +
+                       (o.use_tab ? sizeof(float) * (size_t)(out.B + 1) : 0);
     rfx::TimedLaunch timed(kOob ? "prox_tile_kernel_oob" : "prox_tile_kernel", st);
     hipLaunchKernelGGL((prox_tile_kernel<P, J, kOob>), dim3((unsigned)blocks), dim3(64 * kWaves), lds, st, planes, Npad, G,
-                       o);
+                       (int32_t)rows, o);
     RFX_LAUNCH_CHECK("prox_tile_kernel");
     return RFX_OK;
 }
@@ -299,7 +349,7 @@ int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, cons
 #ifndef RFX_J_PLAIN
 #define RFX_J_PLAIN 16
 #endif
-    constexpr int J = kOob ? 16 : RFX_J_PLAIN;
+    constexpr int J = RFX_J_PLAIN;
     switch (P) {
 #define RFX_CASE(p) \
     case p:         \
@@ -378,6 +428,7 @@ int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t
     int rc = check_common("rfx_prox_oob", leaf, N, B, leaf_bound, count_dtype, layout);
     if (rc != RFX_OK) return rc;
     if (!inbag) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: inbag is null");
+    if (B > 65535) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_oob: more than 65535 trees");
     if (!num && !den && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: no output given");
     TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0};
     return run<true>(leaf, inbag, N, B, leaf_bound, out, rfx::as_stream(stream));
