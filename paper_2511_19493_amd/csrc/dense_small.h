@@ -31,8 +31,11 @@ int chol_inverse(const double* G, int k, SmallWs& ws, double* T, hipStream_t st)
 int jacobi_eigh(const double* H, int k, SmallWs& ws, double* theta, double* W, hipStream_t st);
 // Out = A T with A float32 [N][k], T float64 [k][kout] (row stride k), Out float32 [N][kout].
 int apply_small(const float* A, int64_t N, int k, const double* T, int kout, float* Out, hipStream_t st);
-// Two passes of Cholesky QR: V = orthonormal basis of span(Y); Z is an [N][k] temporary.
-int orthonormalise(const float* Y, int64_t N, int k, SmallWs& ws, float* Z, float* V, hipStream_t st);
+// Cholesky QR: V = orthonormal basis of span(Y); Z is an [N][k] temporary (used by the second pass).
+// The Gram matrix and its factor are float64, so one pass already leaves V orthonormal to float32
+// rounding when cond(Y)^2 is well below 1e16 (a block that has just been multiplied by P from an
+// orthonormal block); passes = 2 repeats the step for blocks of unknown conditioning (start blocks).
+int orthonormalise(const float* Y, int64_t N, int k, SmallWs& ws, float* Z, float* V, hipStream_t st, int passes);
 // Flips every column of V [N][kc] so that its largest-magnitude entry (first one on ties) is positive.
 int fix_signs(float* V, int64_t N, int kc, hipStream_t st);
 

@@ -58,17 +58,22 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restri
         }
 }
 
+// G[e] = sum over blocks of partial[block][e] (symmetrised on request).  16 consecutive lanes share
+// an entry: lane part p adds blocks p, p+16, ..., then the 16 partial sums are added pairwise in a
+// fixed order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ partial, int blocks, int k, int sym,
                                                          double* __restrict__ G) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= k * k) return;
-    const int p = e / k, q = e - p * k;
-    double s = 0.0, st = 0.0;
-    for (int b = 0; b < blocks; ++b) {
+    const int e = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int part = threadIdx.x & 15;
+    const bool live = e < k * k;
+    const int p = live ? e / k : 0, q = live ? e - p * k : 0;
+    double s = 0.0;
+    for (int b = part; b < blocks; b += 16) {
         s += partial[(int64_t)b * k * k + p * k + q];
-        if (sym) st += partial[(int64_t)b * k * k + q * k + p];
+        if (sym) s += partial[(int64_t)b * k * k + q * k + p];
     }
-    G[e] = sym ? 0.5 * (s + st) : s;
+    for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 16);
+    if (live && part == 0) G[e] = sym ? 0.5 * s : s;
 }
 
 // One workgroup.  R (upper, G = R^T R) is formed in LDS by the right-looking Cholesky algorithm,
@@ -131,7 +136,30 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
         Wk[e] = (e / k == e % k) ? 1.0 : 0.0;
     }
     __syncthreads();
+    __shared__ double red_off[256], red_diag[256];
     for (int sw = 0; sw < sweeps; ++sw) {
+        // converged when the off-diagonal mass is negligible against the diagonal
+        double off = 0.0, dg = 0.0;
+        for (int e = threadIdx.x; e < k * k; e += 256) {
+            const double v = A[e];
+            if (e / k == e % k)
+                dg += v * v;
+            else
+                off += v * v;
+        }
+        red_off[threadIdx.x] = off;
+        red_diag[threadIdx.x] = dg;
+        __syncthreads();
+        for (int s2 = 128; s2 > 0; s2 >>= 1) {
+            if (threadIdx.x < s2) {
+                red_off[threadIdx.x] += red_off[threadIdx.x + s2];
+                red_diag[threadIdx.x] += red_diag[threadIdx.x + s2];
+            }
+            __syncthreads();
+        }
+        const bool done = red_off[0] <= 1e-30 * red_diag[0];
+        __syncthreads();
+        if (done) break;
         for (int step = 0; step < K - 1; ++step) {
             for (int pr = threadIdx.x; pr < K / 2; pr += 256) {
                 int p = (step + pr) % (K - 1);
@@ -302,7 +330,7 @@ int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& w
     }
 #undef RFX_GRAM
     RFX_LAUNCH_CHECK("gram_partial_kernel");
-    hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)ceil_div(k * k, 256)), dim3(256), 0, st, ws.partial, blocks, k,
+    hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)ceil_div(k * k, 16)), dim3(256), 0, st, ws.partial, blocks, k,
                        sym ? 1 : 0, G);
     RFX_LAUNCH_CHECK("gram_reduce_kernel");
     return RFX_OK;
@@ -321,7 +349,7 @@ int jacobi_eigh(const double* H, int k, SmallWs& ws, double* theta, double* W, h
     const size_t lds = sizeof(double) * ((size_t)k * k + K) + sizeof(int) * K;
     RFX_HIP(allow_lds(jacobi_kernel, lds));
     double* work = ws.theta + k;  // [k][k] accumulated rotations
-    const int sweeps = 12;
+    const int sweeps = 16;  // upper bound; the kernel stops when the off-diagonal mass is below 1e-30 of the diagonal
     hipLaunchKernelGGL(jacobi_kernel, dim3(1), dim3(256), lds, st, H, k, sweeps, work, theta, W);
     RFX_LAUNCH_CHECK("jacobi_kernel");
     return RFX_OK;
@@ -336,8 +364,13 @@ int apply_small(const float* A, int64_t N, int k, const double* T, int kout, flo
     return RFX_OK;
 }
 
-int orthonormalise(const float* Y, int64_t N, int k, SmallWs& ws, float* Z, float* V, hipStream_t st) {
+int orthonormalise(const float* Y, int64_t N, int k, SmallWs& ws, float* Z, float* V, hipStream_t st, int passes) {
     int rc;
+    if (passes <= 1) {
+        if ((rc = gram(Y, Y, N, k, true, ws, ws.G, st)) != RFX_OK) return rc;
+        if ((rc = chol_inverse(ws.G, k, ws, ws.T, st)) != RFX_OK) return rc;
+        return apply_small(Y, N, k, ws.T, k, V, st);
+    }
     if ((rc = gram(Y, Y, N, k, true, ws, ws.G, st)) != RFX_OK) return rc;
     if ((rc = chol_inverse(ws.G, k, ws, ws.T, st)) != RFX_OK) return rc;
     if ((rc = apply_small(Y, N, k, ws.T, k, Z, st)) != RFX_OK) return rc;

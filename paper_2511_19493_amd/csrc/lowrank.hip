@@ -90,10 +90,10 @@ int rfx_prox_lowrank(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bo
     float* Z = Y + (size_t)N * k;
 
     // V <- orth(V0); (iters - 1) x V <- orth(P V)
-    if ((rc = rfx::orthonormalise(V0, N, k, ws, Z, V, st)) != RFX_OK) return rc;
+    if ((rc = rfx::orthonormalise(V0, N, k, ws, Z, V, st, 2)) != RFX_OK) return rc;
     for (int it = 1; it < iters; ++it) {
         if ((rc = rfx_pv_apply(plan, V, k, Y, stream)) != RFX_OK) return rc;
-        if ((rc = rfx::orthonormalise(Y, N, k, ws, Z, V, st)) != RFX_OK) return rc;
+        if ((rc = rfx::orthonormalise(Y, N, k, ws, Z, V, st, 1)) != RFX_OK) return rc;
     }
     // Rayleigh-Ritz: Y = P V, H = sym(V^T Y) = W diag(theta) W^T, V <- V W
     if ((rc = rfx_pv_apply(plan, V, k, Y, stream)) != RFX_OK) return rc;

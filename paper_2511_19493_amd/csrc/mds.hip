@@ -329,7 +329,7 @@ extern "C" int rfx_mds3d(const int8_t* Q, const float* scales, int64_t N, int32_
     float* Z = Y + (size_t)N * m;
 
     int rc;
-    if ((rc = rfx::orthonormalise(x0, N, m, ws, Z, X, st)) != RFX_OK) return rc;
+    if ((rc = rfx::orthonormalise(x0, N, m, ws, Z, X, st, 2)) != RFX_OK) return rc;
     std::vector<double> theta(m), prev(3, 0.0);
     int it = 0;
     bool converged = false;
@@ -348,7 +348,7 @@ extern "C" int rfx_mds3d(const int8_t* Q, const float* scales, int64_t N, int32_
         }
         for (int d = 0; d < 3; ++d) prev[d] = theta[d];
         if (converged || it >= max_iters) break;
-        if ((rc = rfx::orthonormalise(Y, N, m, ws, Z, X, st)) != RFX_OK) return rc;
+        if ((rc = rfx::orthonormalise(Y, N, m, ws, Z, X, st, 2)) != RFX_OK) return rc;
     }
     // Ritz vectors of the three largest values: coords = X W[:, 0:3] scaled by sqrt(theta)
     if ((rc = rfx::apply_small(X, N, m, ws.W, 3, coords, st)) != RFX_OK) return rc;

@@ -4,14 +4,20 @@
 // Plan (once per forest): for every tree the samples are grouped by leaf with a stable counting
 // sort, giving perm[B][N] (sample indices, leaf by leaf, ascending inside a leaf) and
 // seg_start[B*Lb + 1] (Lb = leaf_bound; slot = b*Lb + leaf).  Ascending order inside a leaf
-// fixes the float summation order, so results are reproducible run to run.
+// fixes the float summation order, so results are reproducible run to run.  The sort splits
+// each tree's samples into Q parts: per-part leaf histograms (in LDS when Lb allows), a per-tree
+// scan that turns them into segment starts and per-part cursors, and a stable per-part scatter.
 //
-// Apply, two kernels, both pure row traffic of k floats:
-//   leaf sums : S[slot,:] = sum over the slot's samples of V[sample,:]   (one wave per chunk
-//               of a slot; long slots are split and their partial sums added in order)
+// Apply, both kernels pure row traffic of k floats:
+//   leaf sums : S[slot,:] = sum over the slot's samples of V[sample,:].  Purity-grown trees have
+//               thousands of tiny leaves and a few huge ones (most samples sit in leaves of more
+//               than a thousand members), so slots up to kBigLeaf members take one wave each and
+//               the rest, listed at plan time, take a 16-wave workgroup each whose waves sum
+//               contiguous ranges and combine their partial sums in wave order.
 //   gather    : Y[i,:] = (1/B) sum_b S[slot_b(i),:]   (a wave keeps a tile of Y rows in
 //               registers and sweeps the trees in order, so all waves touch the same trees'
 //               sums at about the same time and those rows stay cache-resident)
+#include <algorithm>
 #include <vector>
 
 #include "common.h"
@@ -22,82 +28,113 @@ struct rfx_pv_plan {
     uint32_t* d_slot = nullptr;       // [B][N]  b*Lb + leaf_b(i)
     uint32_t* d_perm = nullptr;       // [B*N]
     uint32_t* d_seg_start = nullptr;  // [B*Lb + 1]
+    uint32_t* d_big = nullptr;        // [n_big] slots with more than kBigLeaf members
+    int32_t n_big = 0;
     float* d_S = nullptr;             // [B*Lb][k_cap]
     int32_t k_cap = 0;
 };
 
 namespace {
 
-constexpr int kGatherTile = 32;  // Y rows per wave in the gather
+constexpr int kGatherTile = 32;   // Y rows per wave in the gather
+constexpr int kBigLeaf = 256;     // slots with more members are summed by a whole workgroup
+constexpr int kBigWaves = 16;
+constexpr int kHistLdsLeaves = 16384;  // largest Lb whose histogram fits LDS (64 KB)
 
-__global__ __launch_bounds__(256) void pv_hist_kernel(const uint32_t* __restrict__ leaf, int64_t N, int32_t B, int32_t Lb,
-                                                     uint32_t* __restrict__ slot, uint32_t* __restrict__ count,
-                                                     int* __restrict__ bad) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int b = blockIdx.y;
-    if (i >= N) return;
-    uint32_t id = leaf[(int64_t)b * N + i];
-    if (id >= (uint32_t)Lb) {
-        *bad = 1;
-        id = (uint32_t)Lb - 1;
+// Histogram of one part (blockIdx.x) of one tree (blockIdx.y) and the slot ids of its samples.
+// kLds: the part's histogram is built in LDS and stored whole; otherwise `count` was zeroed and
+// takes global atomics.
+template <bool kLds>
+__global__ __launch_bounds__(1024) void pv_hist_kernel(const uint32_t* __restrict__ leaf, int64_t N, int32_t Lb,
+                                                      int64_t part_len, uint32_t* __restrict__ slot,
+                                                      uint32_t* __restrict__ count, int* __restrict__ bad) {
+    extern __shared__ uint32_t hist[];
+    const int q = blockIdx.x, Q = gridDim.x, b = blockIdx.y;
+    uint32_t* mine = count + ((int64_t)b * Q + q) * Lb;
+    if (kLds) {
+        for (int l = threadIdx.x; l < Lb; l += blockDim.x) hist[l] = 0;
+        __syncthreads();
     }
-    const uint32_t s = (uint32_t)b * (uint32_t)Lb + id;
-    slot[(int64_t)b * N + i] = s;
-    atomicAdd(&count[s], 1u);
+    const int64_t lo = (int64_t)q * part_len, hi = min(N, lo + part_len);
+    for (int64_t i = lo + threadIdx.x; i < hi; i += blockDim.x) {
+        uint32_t id = leaf[(int64_t)b * N + i];
+        if (id >= (uint32_t)Lb) {
+            *bad = 1;
+            id = (uint32_t)Lb - 1;
+        }
+        slot[(int64_t)b * N + i] = (uint32_t)b * (uint32_t)Lb + id;
+        if (kLds)
+            atomicAdd(&hist[id], 1u);
+        else
+            atomicAdd(&mine[id], 1u);
+    }
+    if (kLds) {
+        __syncthreads();
+        for (int l = threadIdx.x; l < Lb; l += blockDim.x) mine[l] = hist[l];
+    }
 }
 
-// One workgroup per tree: seg_start[b*Lb + l] = b*N + (number of samples of tree b in leaves < l);
-// cursor = seg_start.
-__global__ __launch_bounds__(256) void pv_scan_kernel(const uint32_t* __restrict__ count, int64_t N, int32_t B, int32_t Lb,
-                                                     uint32_t* __restrict__ seg_start, uint32_t* __restrict__ cursor) {
+// One workgroup per tree.  With c[q][l] the part histograms: seg_start[b*Lb + l] = b*N + (samples of
+// the tree in leaves < l); c[q][l] is replaced by the cursor seg_start + sum_{q' < q} c[q'][l]; slots
+// with more than kBigLeaf members are appended to the big list.
+__global__ __launch_bounds__(256) void pv_scan_kernel(uint32_t* __restrict__ count, int64_t N, int32_t B, int32_t Lb, int32_t Q,
+                                                     uint32_t* __restrict__ seg_start, uint32_t* __restrict__ big,
+                                                     int* __restrict__ n_big) {
     __shared__ uint32_t part[256];
     const int b = blockIdx.x;
     const int t = threadIdx.x;
     const int per = (Lb + 255) / 256;
     const int lo = min(Lb, t * per), hi = min(Lb, lo + per);
-    const uint32_t* c = count + (int64_t)b * Lb;
+    uint32_t* c = count + (int64_t)b * Q * Lb;
     uint32_t sum = 0;
-    for (int l = lo; l < hi; ++l) sum += c[l];
+    for (int l = lo; l < hi; ++l)
+        for (int q = 0; q < Q; ++q) sum += c[(int64_t)q * Lb + l];
     part[t] = sum;
     __syncthreads();
     if (t == 0) {
         uint32_t run = (uint32_t)((int64_t)b * N);
-        for (int q = 0; q < 256; ++q) {
-            uint32_t v = part[q];
-            part[q] = run;
+        for (int w = 0; w < 256; ++w) {
+            uint32_t v = part[w];
+            part[w] = run;
             run += v;
         }
     }
     __syncthreads();
     uint32_t run = part[t];
     for (int l = lo; l < hi; ++l) {
-        const int64_t at = (int64_t)b * Lb + l;
-        const uint32_t v = c[l];
-        seg_start[at] = run;
-        cursor[at] = run;
-        run += v;
+        seg_start[(int64_t)b * Lb + l] = run;
+        const uint32_t first = run;
+        for (int q = 0; q < Q; ++q) {
+            const uint32_t v = c[(int64_t)q * Lb + l];
+            c[(int64_t)q * Lb + l] = run;
+            run += v;
+        }
+        if (run - first > (uint32_t)kBigLeaf) big[atomicAdd(n_big, 1)] = (uint32_t)b * (uint32_t)Lb + (uint32_t)l;
     }
     if (b == B - 1 && t == 255) seg_start[(int64_t)B * Lb] = (uint32_t)((int64_t)B * N);
 }
 
-// Stable scatter: one wave per tree walks the samples 64 at a time in ascending order.  Lanes with
-// the same slot are ranked by lane index; the group's first lane reserves the group's range with
-// one atomic add, so the order inside every leaf is ascending sample index.
-__global__ __launch_bounds__(64) void pv_scatter_kernel(const uint32_t* __restrict__ slot, int64_t N,
-                                                       uint32_t* __restrict__ cursor, uint32_t* __restrict__ perm) {
-    const int b = blockIdx.x;
+// Stable scatter: one wave per (part, tree) walks its samples 64 at a time in ascending order.  Lanes
+// with the same slot are ranked by lane index; the group's first lane reserves the group's range
+// with one atomic add on the part's cursor, so the order inside every leaf is ascending sample index.
+__global__ __launch_bounds__(64) void pv_scatter_kernel(const uint32_t* __restrict__ slot, int64_t N, int32_t Lb,
+                                                       int64_t part_len, uint32_t* __restrict__ cursor,
+                                                       uint32_t* __restrict__ perm) {
+    const int q = blockIdx.x, Q = gridDim.x, b = blockIdx.y;
     const int lane = threadIdx.x;
     const uint64_t lt_mask = (1ull << lane) - 1ull;
     const uint32_t* s = slot + (int64_t)b * N;
-    for (int64_t i0 = 0; i0 < N; i0 += 64) {
+    uint32_t* cur = cursor + ((int64_t)b * Q + q) * Lb - (int64_t)b * Lb;  // indexed by slot = b*Lb + leaf
+    const int64_t lo = (int64_t)q * part_len, hi = min(N, lo + part_len);
+    for (int64_t i0 = lo; i0 < hi; i0 += 64) {
         const int64_t i = i0 + lane;
-        const bool valid = i < N;
+        const bool valid = i < hi;
         const uint32_t key = valid ? s[i] : 0xffffffffu;
         uint64_t remaining = __ballot(valid);
         int my_leader = lane;
         uint32_t rank = 0, gcount = 0;
         while (remaining) {
-            const int leader = __ffsll((unsigned long long)remaining) - 1;
+            const int leader = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)remaining) - 1);
             const uint32_t lk = __builtin_amdgcn_readlane(key, leader);
             const uint64_t m = __ballot(valid && key == lk);
             if (valid && key == lk) {
@@ -108,7 +145,7 @@ __global__ __launch_bounds__(64) void pv_scatter_kernel(const uint32_t* __restri
             remaining &= ~m;
         }
         uint32_t base = 0;
-        if (valid && my_leader == lane) base = atomicAdd(&cursor[key], gcount);
+        if (valid && my_leader == lane) base = atomicAdd(&cur[key], gcount);
         base = __shfl(base, my_leader);
         if (valid) perm[base + rank] = (uint32_t)i;
     }
@@ -124,32 +161,28 @@ __device__ __forceinline__ int lane_col(int lane) {
     return lane & (64 / RPW - 1);
 }
 
-// Leaf sums.  One wave per slot; the RPW lane groups take members t, t+RPW, ... of the slot in
-// batches of kSumBatch loads, and their partial sums are added in group order at the end.
 constexpr int kSumBatch = 8;
 
+// Sum of the V rows of members perm[lo .. hi) for this lane's columns.  The RPW lane groups take
+// members t, t+RPW, ... in batches of kSumBatch loads; their partial sums are added in group order,
+// so every lane of a column ends with the same total.
 template <int KCH, int RPW>
-__global__ __launch_bounds__(256) void pv_leaf_sum_kernel(const uint32_t* __restrict__ seg_start,
-                                                         const uint32_t* __restrict__ perm, int64_t n_slots,
-                                                         const float* __restrict__ V, int32_t k, float* __restrict__ S) {
-    const int lane = threadIdx.x & 63;
-    const int64_t slot = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (slot >= n_slots) return;
-    const uint32_t lo = seg_start[slot], hi = seg_start[slot + 1];
-    if (lo == hi) return;  // empty leaf: its row of S is never read
+__device__ __forceinline__ void sum_members(const uint32_t* __restrict__ perm, uint32_t lo, uint32_t hi,
+                                            const float* __restrict__ V, int32_t k, int lane, float (&acc)[KCH]) {
     const int grp = lane / (64 / RPW);
     int col[KCH];
 #pragma unroll
-    for (int c = 0; c < KCH; ++c) col[c] = min(lane_col<RPW>(lane) + 64 * c, k - 1);
-    float acc[KCH];
-#pragma unroll
-    for (int c = 0; c < KCH; ++c) acc[c] = 0.0f;
+    for (int c = 0; c < KCH; ++c) {
+        col[c] = min(lane_col<RPW>(lane) + 64 * c, k - 1);
+        acc[c] = 0.0f;
+    }
+    if (lo >= hi) return;
     for (uint32_t t0 = lo; t0 < hi; t0 += kSumBatch * RPW) {
         float v[kSumBatch][KCH];
 #pragma unroll
         for (int u = 0; u < kSumBatch; ++u) {
             const uint32_t t = t0 + u * RPW + grp;
-            const uint32_t j = perm[min(t, hi - 1)];   // clamped: always a valid member
+            const uint32_t j = perm[min(t, hi - 1)];  // clamped: always a valid member
 #pragma unroll
             for (int c = 0; c < KCH; ++c) v[u][c] = V[(int64_t)j * k + col[c]];
         }
@@ -163,18 +196,62 @@ __global__ __launch_bounds__(256) void pv_leaf_sum_kernel(const uint32_t* __rest
     if (RPW > 1) {
 #pragma unroll
         for (int c = 0; c < KCH; ++c) {
-            float tot = acc[c];
+            float tot = __shfl(acc[c], lane_col<RPW>(lane));
 #pragma unroll
             for (int g = 1; g < RPW; ++g) tot += __shfl(acc[c], lane_col<RPW>(lane) + g * (64 / RPW));
             acc[c] = tot;
         }
     }
-    if (grp == 0) {
+}
+
+// Leaf sums of the slots with at most kBigLeaf members: one wave per slot.
+template <int KCH, int RPW>
+__global__ __launch_bounds__(256) void pv_leaf_sum_kernel(const uint32_t* __restrict__ seg_start,
+                                                         const uint32_t* __restrict__ perm, int64_t n_slots,
+                                                         const float* __restrict__ V, int32_t k, float* __restrict__ S) {
+    const int lane = threadIdx.x & 63;
+    const int64_t slot = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (slot >= n_slots) return;
+    const uint32_t lo = seg_start[slot], hi = seg_start[slot + 1];
+    if (lo == hi || hi - lo > (uint32_t)kBigLeaf) return;  // empty (its row of S is never read) or handled below
+    float acc[KCH];
+    sum_members<KCH, RPW>(perm, lo, hi, V, k, lane, acc);
+    if (lane < 64 / RPW) {
 #pragma unroll
         for (int c = 0; c < KCH; ++c) {
-            const int cc = lane_col<RPW>(lane) + 64 * c;
+            const int cc = lane + 64 * c;
             if (cc < k) S[slot * k + cc] = acc[c];
         }
+    }
+}
+
+// Leaf sums of the listed big slots: one 16-wave workgroup per slot.  Wave w sums the w-th contiguous
+// share of the members; the 16 partial rows are then added in wave order.
+template <int KCH, int RPW>
+__global__ __launch_bounds__(64 * kBigWaves) void pv_leaf_sum_big_kernel(const uint32_t* __restrict__ big,
+                                                                        const uint32_t* __restrict__ seg_start,
+                                                                        const uint32_t* __restrict__ perm,
+                                                                        const float* __restrict__ V, int32_t k,
+                                                                        float* __restrict__ S) {
+    __shared__ float part[kBigWaves][KCH * 64];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t slot = big[blockIdx.x];
+    const uint32_t lo = seg_start[slot], hi = seg_start[slot + 1];
+    const uint32_t share = ((hi - lo + kBigWaves - 1) / kBigWaves + kSumBatch * RPW - 1) / (kSumBatch * RPW) * (kSumBatch * RPW);
+    const uint32_t wlo = min(hi, lo + w * share), whi = min(hi, wlo + share);
+    float acc[KCH];
+    sum_members<KCH, RPW>(perm, wlo, whi, V, k, lane, acc);
+    if (lane < 64 / RPW) {
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) part[w][lane + 64 * c] = acc[c];
+    }
+    __syncthreads();
+    for (int cc = threadIdx.x; cc < k; cc += 64 * kBigWaves) {
+        float tot = part[0][cc];
+#pragma unroll
+        for (int u = 1; u < kBigWaves; ++u) tot += part[u][cc];
+        S[slot * k + cc] = tot;
     }
 }
 
@@ -249,6 +326,9 @@ int launch_apply(const rfx_pv_plan* p, const float* V, int32_t k, float* Y, hipS
         rfx::TimedLaunch timed("pv_leaf_sum_kernel", st);
         hipLaunchKernelGGL((pv_leaf_sum_kernel<KCH, RPW>), dim3((unsigned)rfx::ceil_div(n_slots, 4)), dim3(256), 0, st,
                            p->d_seg_start, p->d_perm, n_slots, V, k, p->d_S);
+        if (p->n_big > 0)
+            hipLaunchKernelGGL((pv_leaf_sum_big_kernel<KCH, RPW>), dim3((unsigned)p->n_big), dim3(64 * kBigWaves), 0, st,
+                               p->d_big, p->d_seg_start, p->d_perm, V, k, p->d_S);
     }
     RFX_LAUNCH_CHECK("pv_leaf_sum_kernel");
     const int64_t tiles = rfx::ceil_div(p->N, kGatherTile);
@@ -268,6 +348,7 @@ int rfx_pv_plan_destroy(rfx_pv_plan* p) {
     if (p->d_slot) (void)hipFree(p->d_slot);
     if (p->d_perm) (void)hipFree(p->d_perm);
     if (p->d_seg_start) (void)hipFree(p->d_seg_start);
+    if (p->d_big) (void)hipFree(p->d_big);
     if (p->d_S) (void)hipFree(p->d_S);
     delete p;
     return RFX_OK;
@@ -286,34 +367,46 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
     p->N = N;
     p->B = B;
     p->Lb = leaf_bound;
-    const int64_t n_slots = (int64_t)B * leaf_bound;
-    rfx::DevBuf count, bad;
+    const int Lb = leaf_bound;
+    const int64_t n_slots = (int64_t)B * Lb;
+    // parts per tree: enough (part, tree) pairs to fill the chip, parts of at least 4096 samples
+    const int Q = (int)std::max<int64_t>(1, std::min<int64_t>(16, N / 4096));
+    const int64_t part_len = rfx::ceil_div(rfx::ceil_div(N, Q), 64) * 64;
+    const int64_t max_big = (int64_t)B * N / kBigLeaf + 1;
+    const bool lds_hist = Lb <= kHistLdsLeaves;
+    rfx::DevBuf count, flags;
     hipError_t e = hipMalloc((void**)&p->d_slot, sizeof(uint32_t) * (size_t)B * (size_t)N);
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_perm, sizeof(uint32_t) * (size_t)B * (size_t)N);
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_seg_start, sizeof(uint32_t) * (size_t)(n_slots + 1));
-    if (e == hipSuccess) e = count.alloc(sizeof(uint32_t) * (size_t)n_slots * 2);
-    if (e == hipSuccess) e = bad.alloc(sizeof(int));
-    if (e == hipSuccess) e = hipMemsetAsync(count.p, 0, sizeof(uint32_t) * (size_t)n_slots, st);
-    if (e == hipSuccess) e = hipMemsetAsync(bad.p, 0, sizeof(int), st);
+    if (e == hipSuccess) e = hipMalloc((void**)&p->d_big, sizeof(uint32_t) * (size_t)max_big);
+    if (e == hipSuccess) e = count.alloc(sizeof(uint32_t) * (size_t)n_slots * Q);
+    if (e == hipSuccess) e = flags.alloc(2 * sizeof(int));
+    if (e == hipSuccess && !lds_hist) e = hipMemsetAsync(count.p, 0, sizeof(uint32_t) * (size_t)n_slots * Q, st);
+    if (e == hipSuccess) e = hipMemsetAsync(flags.p, 0, 2 * sizeof(int), st);
     if (e != hipSuccess) {
         rfx_pv_plan_destroy(p);
         return rfx::fail(e == hipErrorOutOfMemory ? RFX_ERR_OOM : RFX_ERR_HIP, "rfx_pv_plan_create: %s", hipGetErrorString(e));
     }
     uint32_t* cnt = count.as<uint32_t>();
-    uint32_t* cursor = cnt + n_slots;
-    hipLaunchKernelGGL(pv_hist_kernel, dim3((unsigned)rfx::ceil_div(N, 256), (unsigned)B), dim3(256), 0, st, leaf, N, B,
-                       leaf_bound, p->d_slot, cnt, bad.as<int>());
-    hipLaunchKernelGGL(pv_scan_kernel, dim3((unsigned)B), dim3(256), 0, st, cnt, N, B, leaf_bound, p->d_seg_start, cursor);
-    hipLaunchKernelGGL(pv_scatter_kernel, dim3((unsigned)B), dim3(64), 0, st, p->d_slot, N, cursor, p->d_perm);
-    int h_bad = 0;
+    int* bad = flags.as<int>();
+    int* n_big = bad + 1;
+    if (lds_hist)
+        hipLaunchKernelGGL(pv_hist_kernel<true>, dim3(Q, B), dim3(1024), sizeof(uint32_t) * Lb, st, leaf, N, Lb, part_len,
+                           p->d_slot, cnt, bad);
+    else
+        hipLaunchKernelGGL(pv_hist_kernel<false>, dim3(Q, B), dim3(1024), 0, st, leaf, N, Lb, part_len, p->d_slot, cnt, bad);
+    hipLaunchKernelGGL(pv_scan_kernel, dim3((unsigned)B), dim3(256), 0, st, cnt, N, B, Lb, Q, p->d_seg_start, p->d_big, n_big);
+    hipLaunchKernelGGL(pv_scatter_kernel, dim3(Q, B), dim3(64), 0, st, p->d_slot, N, Lb, part_len, cnt, p->d_perm);
+    int h_flags[2] = {0, 0};
     e = hipGetLastError();
-    if (e == hipSuccess) e = hipMemcpyAsync(&h_bad, bad.p, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(h_flags, flags.p, 2 * sizeof(int), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess || h_bad) {
+    if (e != hipSuccess || h_flags[0]) {
         rfx_pv_plan_destroy(p);
         if (e != hipSuccess) return rfx::fail(RFX_ERR_HIP, "rfx_pv_plan_create: %s", hipGetErrorString(e));
         return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_plan_create: a leaf id is >= leaf_bound=%d", leaf_bound);
     }
+    p->n_big = h_flags[1];
     *out = p;
     return RFX_OK;
 }

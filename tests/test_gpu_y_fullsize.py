@@ -1,0 +1,284 @@
+"""GPU parity at the workloads' full sizes, in the launch configurations bench.py times.
+
+Workload 2 is compared entry by entry; workloads 3 and 4 on sampled rows the oracle computes one
+by one plus properties that hold at any size; workload 5 with its full row count and a reduced
+number of trees (growing 1,000 trees on 500,000 rows takes the CPU grower tens of minutes).
+Each test prints its own progress lines.
+"""
+import time
+
+import numpy as np
+import pytest
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
+
+
+def say(*a):
+    print("[fullsize]", *a, flush=True)
+
+
+def _u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def _forest(F):
+    import paper_2511_19493_amd as rfx
+    return rfx.Forest(F.n_features, F.node_offset, F.feature, F.threshold, F.left, F.right, F.leaf_id, F.n_leaves)
+
+
+def _load(cfg, B=None):
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    assert torch.cuda.is_available()
+    c = ri.CONFIGS[cfg]
+    t0 = time.time()
+    X, y, F = ri.load_or_grow(c, B=B)
+    say(f"cfg{cfg}: N={c.N} M={c.M} B={F.n_trees}: inputs in {time.time() - t0:.0f}s, {F.total_nodes} nodes, "
+        f"max leaves {int(F.n_leaves.max())}, max depth {int(F.depth.max())}")
+    t0 = time.time()
+    ref_leaf, plen = oracle.leaf_assign(F, X)
+    say(f"oracle leaf assignment in {time.time() - t0:.0f}s, mean path {plen / ref_leaf.size:.2f}")
+    gf = _forest(F)
+    leaf = rfx.leaf_assign(gf, torch.from_numpy(X).cuda())
+    torch.cuda.synchronize()
+    return dict(c=c, X=X, F=F, ref_leaf=ref_leaf, gf=gf, leaf=leaf, Lb=gf.leaf_bound)
+
+
+@pytest.fixture(scope="module")
+def w2():
+    return _load(2)
+
+
+@pytest.fixture(scope="module")
+def w3():
+    return _load(3)
+
+
+@pytest.fixture(scope="module")
+def w4():
+    return _load(4)
+
+
+@pytest.fixture(scope="module")
+def w5_reduced():
+    return _load(5, B=32)
+
+
+def _sample_rows(N, n, seed):
+    rng = np.random.default_rng(seed)
+    rows = set(rng.integers(0, N, size=n).tolist()) | {0, 1, N - 1, N - 2, N // 2, 255, 256, 257}
+    return sorted(r for r in rows if 0 <= r < N)
+
+
+# ------------------------------------------------------------------------------------------ workload 2
+def test_cfg2_everything_entry_by_entry(w2):
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    d = w2
+    B, N = d["ref_leaf"].shape
+    np.testing.assert_array_equal(_u32(d["leaf"]), d["ref_leaf"])
+    say("cfg2 leaf ids bit-exact")
+    t0 = time.time()
+    ref = oracle.counts_full(d["ref_leaf"])
+    say(f"oracle counts in {time.time() - t0:.0f}s")
+    cnt, _ = rfx.prox_dense(d["leaf"], d["Lb"], rfx.U16, rfx.UPPER_PACKED, want_prox=False)
+    np.testing.assert_array_equal(cnt.cpu().numpy().view(np.uint16), oracle.pack_upper(ref).astype(np.uint16))
+    say("cfg2 packed uint16 counts bit-exact")
+    inbag = d["F"].inbag
+    num, den, prox = rfx.prox_oob(d["leaf"], torch.from_numpy(inbag.view(np.int16)).cuda(), d["Lb"], rfx.U32, rfx.FULL)
+    t0 = time.time()
+    rn, rd = oracle.oob_rows(d["ref_leaf"], inbag, 0, N)
+    say(f"oracle out-of-bag counts in {time.time() - t0:.0f}s")
+    np.testing.assert_array_equal(_u32(num), rn)
+    np.testing.assert_array_equal(_u32(den), rd)
+    np.testing.assert_array_equal(prox.cpu().numpy(), oracle.prox_oob_rows(rn, rd, 0))
+    say("cfg2 out-of-bag numerator, denominator, proximity bit-exact")
+
+
+# ------------------------------------------------------------------------------------------ workloads 3, 4
+def _check_leaf(d):
+    np.testing.assert_array_equal(_u32(d["leaf"]), d["ref_leaf"])
+
+
+def _check_dense(d, n_rows):
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    B, N = d["ref_leaf"].shape
+    prox = torch.empty((N, N), dtype=torch.float32, device="cuda")
+    rfx.prox_dense(d["leaf"], d["Lb"], rfx.U32, rfx.FULL, prox=prox, want_counts=False)   # as bench.py launches it
+    torch.cuda.synchronize()
+    say("dense proximity computed")
+    rows = _sample_rows(N, n_rows, 11)
+    for i in rows:
+        ref = oracle.normalise(oracle.counts_rows(d["ref_leaf"], i, i + 1)[0], B)
+        np.testing.assert_array_equal(prox[i].cpu().numpy(), ref, err_msg=f"row {i}")
+        np.testing.assert_array_equal(prox[:, i].cpu().numpy(), ref, err_msg=f"column {i}")
+    say(f"{len(rows)} sampled rows and columns bit-exact")
+    # properties at full size: unit diagonal, range, and sum_ij cnt = sum_b sum_leaf size^2
+    assert bool((torch.diagonal(prox) == 1.0).all())
+    assert float(prox.min()) >= 0.0 and float(prox.max()) == 1.0
+    total = 0.0
+    for s in range(0, N, 8192):
+        total += float(prox[s:s + 8192].sum(dtype=torch.float64))
+    expect = sum(int((np.bincount(d["ref_leaf"][b]).astype(np.int64) ** 2).sum()) for b in range(B)) / B
+    assert abs(total - expect) <= 1e-6 * expect, (total, expect)
+    say("diagonal, range and total-sum identity hold")
+    return prox
+
+
+def _check_oob(d, n_rows):
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    B, N = d["ref_leaf"].shape
+    inbag = d["F"].inbag
+    lib = rfx.load()
+    out = torch.empty((N * (N - 1) // 2,), dtype=torch.float32, device="cuda")
+    rfx._check(lib.rfx_prox_oob(d["leaf"].data_ptr(), torch.from_numpy(inbag.view(np.int16)).cuda().data_ptr(), N, B,
+                                d["Lb"], rfx.U32, rfx.UPPER_PACKED, 0, 0, out.data_ptr(),
+                                torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    rows = [i for i in _sample_rows(N, n_rows, 12) if i < N - 1]
+    for i in rows:
+        rn, rd = oracle.oob_rows(d["ref_leaf"], inbag, i, i + 1)
+        ref = oracle.prox_oob_rows(rn, rd, i)[0, i + 1:]
+        st = i * N - i * (i + 1) // 2
+        np.testing.assert_array_equal(out[st:st + N - i - 1].cpu().numpy(), ref, err_msg=f"row {i}")
+    say(f"out-of-bag packed proximity: {len(rows)} sampled rows bit-exact")
+
+
+def _check_matvec(d, k, n_rows, prox=None):
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    B, N = d["ref_leaf"].shape
+    V = ri.start_block(N, k)
+    plan = rfx.PvPlan(d["leaf"], d["Lb"])
+    dV = torch.from_numpy(V).cuda()
+    Y = plan.apply(dV)
+    torch.cuda.synchronize()
+    rows = _sample_rows(N, n_rows, 13)
+    Yh = Y.cpu().numpy().astype(np.float64)
+    num = den = 0.0
+    for i in rows:
+        ref = oracle.pv_rows(d["ref_leaf"], V.astype(np.float64), i, i + 1)[0]
+        num += float(((Yh[i] - ref) ** 2).sum())
+        den += float((ref ** 2).sum())
+    err = np.sqrt(num / den)
+    say(f"P.V k={k}: relative error on {len(rows)} sampled rows {err:.2e}")
+    assert err <= 1e-5
+    # P.1: B * y_i is the summed size of the leaves holding sample i
+    ones = torch.ones((N, 1), dtype=torch.float32, device="cuda")
+    y1 = plan.apply(ones).cpu().numpy()[:, 0].astype(np.float64) * B
+    sizes = np.zeros(N, np.int64)
+    for b in range(B):
+        sizes += np.bincount(d["ref_leaf"][b])[d["ref_leaf"][b]]
+    assert np.abs(y1 - sizes).max() <= 2e-6 * sizes.max()
+    say("P.1 equals the summed leaf sizes")
+    if prox is not None:
+        # the materialised dense matrix times V (float64 library product, row blocks) against the implicit product
+        worst = 0.0
+        Vd = dV.double()
+        for s in range(0, N, 4096):
+            ref = prox[s:s + 4096].double() @ Vd
+            worst = max(worst, float((ref - Y[s:s + 4096].double()).norm() / ref.norm()))
+        say(f"dense P times V vs implicit product: worst row-block relative error {worst:.2e}")
+        assert worst <= 1e-5
+    plan.close()
+
+
+def _check_lowrank_and_mds(d, k, T, mds_reference="arpack"):
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    B, N = d["ref_leaf"].shape
+    V0 = ri.start_block(N, k)
+    lam, V, Q, s = rfx.prox_lowrank(d["leaf"], d["Lb"], torch.from_numpy(V0).cuda(), T)
+    torch.cuda.synchronize()
+    say("library block iteration done; running the float64 iteration on the CPU ...")
+    t0 = time.time()
+    lam_ref, V_ref = oracle.block_iteration(d["ref_leaf"], V0, T)
+    say(f"oracle block iteration ({T} applications, k={k}) in {time.time() - t0:.0f}s")
+    lam, V = lam.cpu().numpy(), V.cpu().numpy()
+    rel = np.abs(lam - lam_ref) / lam_ref
+    ang = oracle.principal_angle(V, V_ref)
+    say(f"Ritz values: max relative difference {rel.max():.2e}; largest principal angle {ang:.2e} rad")
+    assert rel.max() <= 1e-4 and ang < 1e-3
+    Qr, sr = oracle.quantise_int8(V, lam)
+    np.testing.assert_array_equal(s.cpu().numpy(), sr)
+    np.testing.assert_array_equal(Q.cpu().numpy(), Qr)
+    say("INT8 codes and scales bit-exact")
+    A = oracle.dequantise(Qr, sr)
+    PX = oracle.pv_implicit(d["ref_leaf"], V_ref)
+    err = np.linalg.norm(A @ (A.T @ V_ref) - PX) / np.linalg.norm(PX)
+    say(f"INT8-dequantised P.V on the converged block: relative Frobenius error {err:.2e}")
+    assert err <= 2e-2
+    assert Q.numel() == N * k      # one byte per code: N*k bytes of factor storage
+
+    m = 16
+    x0 = ri.start_block(N, m, seed=778)
+    coords, ev, iters = rfx.mds3d(Q, s, torch.from_numpy(x0).cuda(), rfx.MDS_SQUARED, max_iters=300, tol=1e-7)
+    torch.cuda.synchronize()
+    coords, ev = coords.cpu().numpy().astype(np.float64), ev.cpu().numpy().astype(np.float64)
+    assert np.abs(coords.sum(axis=0)).max() <= 1e-3 * np.abs(coords).max() * np.sqrt(N)
+    np.testing.assert_allclose(coords.T @ coords, np.diag(ev), atol=2e-4 * ev[0])
+    if mds_reference == "arpack":
+        t0 = time.time()
+        ref_c, ref_ev = oracle.mds3d_implicit(Qr, sr, oracle.SQUARED)
+        say(f"oracle implicit scaling (ARPACK, float64) in {time.time() - t0:.0f}s; library took {iters} iterations")
+        say(f"scaling eigenvalues {ev} vs {ref_ev}")
+        np.testing.assert_allclose(ev, ref_ev, rtol=1e-4)
+        gaps = np.abs(np.diff(ref_ev)) / ref_ev[0]
+        if gaps.min() <= 1e-2:
+            U, _, Vt = np.linalg.svd(coords.T @ ref_c)
+            coords = coords @ (U @ Vt)
+        err = np.linalg.norm(coords - ref_c) / np.linalg.norm(ref_c)
+        say(f"scaling coordinates: relative Frobenius difference {err:.2e}")
+        assert err <= 1e-3
+    else:
+        # too large for an eigen-solver run in the test: check the pairs against the float64 operator itself
+        op = oracle.mds_operator(oracle.dequantise(Qr, sr), oracle.SQUARED)
+        Vn = coords / np.sqrt(ev)[None, :]
+        GV = op(Vn)
+        rq = (Vn * GV).sum(axis=0)
+        res = np.linalg.norm(GV - Vn * ev[None, :], axis=0) / ev[0]
+        say(f"library took {iters} iterations; eigenvalues {ev}; Rayleigh quotients {rq}; residuals {res}")
+        np.testing.assert_allclose(rq, ev, rtol=1e-4)
+        assert res.max() <= 5e-3
+
+
+def test_cfg3_dense_and_rank32(w3):
+    _check_leaf(w3)
+    say("cfg3 leaf ids bit-exact")
+    prox = _check_dense(w3, 24)
+    _check_matvec(w3, 32, 24, prox)
+    del prox
+    _check_oob(w3, 12)
+    _check_lowrank_and_mds(w3, 32, 20)
+
+
+def test_cfg4_leaf_and_dense(w4):
+    _check_leaf(w4)
+    say("cfg4 leaf ids bit-exact")
+    prox = _check_dense(w4, 24)
+    _check_matvec(w4, 64, 16, prox)
+    del prox
+    _check_oob(w4, 12)
+
+
+def test_cfg4_rank64_factors_and_scaling(w4):
+    _check_lowrank_and_mds(w4, 64, 20)
+
+
+def test_cfg5_rows_with_reduced_trees(w5_reduced):
+    """500,000 rows x 64 features, 20 classes; 32 of the 1,000 trees (deep trees, ~46k leaves each)."""
+    _check_leaf(w5_reduced)
+    say("cfg5 (32 trees) leaf ids bit-exact")
+    _check_matvec(w5_reduced, 64, 8)
+    _check_lowrank_and_mds(w5_reduced, 64, 20, mds_reference="residual")
