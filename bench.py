@@ -37,6 +37,8 @@ def main():
     ap.add_argument("--rows", type=int, default=0, help="override the row count (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mds-block", type=int, default=16)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one 4 GiB device copy before the steps (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -93,6 +95,16 @@ def main():
         res = timed("mds3d", lambda: rfx.mds3d(Q, s, dx0, rfx.MDS_SQUARED, max_iters=200, tol=1e-5))
         return lam, res
 
+    if args.calibrate_copy:
+        # a plain device-to-device copy of known size: calibrates the HBM byte counters of a --pmc run
+        n_cal = 1 << 30
+        src = torch.empty(n_cal, dtype=torch.int32, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"calibration copy: {4 * n_cal} bytes read and {4 * n_cal} bytes written by one elementwise copy kernel")
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -121,8 +133,12 @@ def main():
     ops_per_launch = tests * (P + 1) / 32.0
     tile_ms = kern["prox_tile_kernel"]["avg_ms"]
     achieved = ops_per_launch / (tile_ms * 1e-3) if tile_ms > 0 else 0.0
+    # HBM-side bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, calibrated on a 4 GiB copy); measured for workload 4 only
+    traffic = (39132487.3 * 2.0 + 39546683.3) * 1024.0 if (c.cfg == 4 and not reduced) else None
     roofline = {"kernel": "prox_tile_kernel", "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_VALU_LANE_OPS / 1e12,
-                "unit": "T lane-ops/s", "frac": achieved / PEAK_VALU_LANE_OPS, "traffic": None,
+                "unit": "T lane-ops/s", "frac": achieved / PEAK_VALU_LANE_OPS, "traffic": traffic,
+                "traffic_source": "profiles/bench_cfg4_pmc_fetch_write.txt (L2-to-fabric bytes; output is 4*N*N)",
                 "ops_per_test": (P + 1) / 32.0, "avg_launch_ms": tile_ms,
                 "tests_per_s": tests / (tile_ms * 1e-3) if tile_ms > 0 else 0.0}
     # implicit product: algorithmic bytes per application = B*N*(2*4k + 4) + 2*4*N*k
@@ -131,6 +147,21 @@ def main():
     pv = {"bytes_per_application": w_pv, "avg_ms": pv_ms, "GBps": w_pv / (pv_ms * 1e-3) / 1e9 if pv_ms > 0 else 0.0,
           "frac_of_hbm_peak": (w_pv / (pv_ms * 1e-3)) / PEAK_HBM_BYTES if pv_ms > 0 else 0.0,
           "leaf_sum_ms": kern["pv_leaf_sum_kernel"]["avg_ms"], "gather_ms": kern["pv_gather_kernel"]["avg_ms"]}
+
+    # leaf assignment: one 8-byte node record and one 4-byte feature value per visited internal node,
+    # plus the leaf-id write and X read once
+    depth_tab = np.zeros((B, Lb), np.int32)
+    for b in range(B):
+        s, e = int(F.node_offset[b]), int(F.node_offset[b + 1])
+        lid = F.leaf_id[s:e]
+        depth_tab[b, lid[lid >= 0]] = F.depth[s:e][lid >= 0]
+    d_depth = torch.from_numpy(depth_tab).to(dev)
+    path_total = int(sum(int(d_depth[b0:b0 + 50].gather(1, leaf[b0:b0 + 50].long()).sum()) for b0 in range(0, B, 50)))
+    w_la = path_total * (8 + 4) + 4 * N * B + 4 * N * c.M
+    la_ms = kern["leaf_assign_kernel"]["avg_ms"]
+    la = {"bytes_model": w_la, "mean_path": path_total / (N * B), "avg_ms": la_ms,
+          "GBps": w_la / (la_ms * 1e-3) / 1e9 if la_ms > 0 else 0.0,
+          "frac_of_hbm_peak": (w_la / (la_ms * 1e-3)) / PEAK_HBM_BYTES if la_ms > 0 else 0.0}
 
     out = {
         "metric": "leaf co-occurrence tests/s (N^2*B/2 per pass of the whole proximity path)",
@@ -151,6 +182,7 @@ def main():
         "phases_ms": phases,
         "dense_tests_per_s": tests / (phases["prox_dense"] * 1e-3),
         "pv": pv,
+        "leaf_assign": la,
         "kernels": kern,
         "roofline": roofline,
     }

@@ -6,56 +6,66 @@
 namespace rfx {
 namespace {
 
-constexpr int kGramRows = 32;   // rows staged per step by the Gram kernel
+constexpr int kGramWaves = 4;   // waves per workgroup of the Gram kernel, each with its own row range
 constexpr int kApplyRows = 32;  // rows per workgroup step of the tall-times-small product
 
-// partial[block][p][q] = sum over the block's rows of A[i][p] * Bm[i][q], float64 accumulation.
-// Thread (ty, tx) of a 16 x 16 workgroup owns entries p = ty + 16u, q = tx + 16v.
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+// partial[wave slot][p][q] = sum over the wave's rows of A[i][p] * Bm[i][q] in float64 on the
+// matrix cores: v_mfma_f64_16x16x4_f64 computes D(16x16) += Aop(16x4) Bop(4x16), 4 rows of the
+// tall blocks per instruction.  Operand layout of a 64-lane wave: lane l supplies
+// Aop[l % 16][l / 16] and Bop[l / 16][l % 16]; the result register v (0..3) of lane l is
+// D[l / 16 + 4 v][l % 16].  With Aop[m][r] = A[i0 + r][16 u + m] and Bop[r][n] = Bm[i0 + r][16 w + n]
+// both operands of lane l are the element (row i0 + l / 16, column 16 * tile + l % 16) of their block:
+// 4 rows x 64 contiguous bytes per load.  A wave keeps PBC x NB output tiles (at most 16) in
+// registers and passes over its rows once per group of PBC tile rows.
 template <int NB>
-__global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restrict__ A, const float* __restrict__ Bm,
-                                                          int64_t N, int k, int64_t rows_per_block,
-                                                          double* __restrict__ partial) {
-    extern __shared__ float gram_sm[];
-    float* As = gram_sm;
-    float* Bs = gram_sm + kGramRows * k;
-    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
-    double acc[NB][NB];
+__global__ __launch_bounds__(64 * kGramWaves) void gram_partial_kernel(const float* __restrict__ A,
+                                                                      const float* __restrict__ Bm, int64_t N, int k,
+                                                                      int64_t rows_per_wave,
+                                                                      double* __restrict__ partial) {
+    constexpr int PBC = NB <= 4 ? NB : (16 / NB > 0 ? 16 / NB : 1);
+    const int lane = threadIdx.x & 63;
+    const int slot = blockIdx.x * kGramWaves + (threadIdx.x >> 6);
+    const int64_t i_begin = (int64_t)slot * rows_per_wave;
+    const int64_t i_end = min(N, i_begin + rows_per_wave);
+    const int r = lane >> 4, c = lane & 15;
+    double* out = partial + (int64_t)slot * k * k;
+    for (int pg = 0; pg < NB; pg += PBC) {
+        double4_t acc[PBC][NB];
 #pragma unroll
-    for (int u = 0; u < NB; ++u)
+        for (int u = 0; u < PBC; ++u)
 #pragma unroll
-        for (int v = 0; v < NB; ++v) acc[u][v] = 0.0;
-    const int64_t i_begin = (int64_t)blockIdx.x * rows_per_block;
-    const int64_t i_end = min(N, i_begin + rows_per_block);
-    for (int64_t i0 = i_begin; i0 < i_end; i0 += kGramRows) {
-        const int rows = (int)min((int64_t)kGramRows, i_end - i0);
-        for (int idx = threadIdx.x; idx < rows * k; idx += 256) {
-            As[idx] = A[i0 * k + idx];
-            Bs[idx] = Bm[i0 * k + idx];
-        }
-        __syncthreads();
-        for (int r = 0; r < rows; ++r) {
-            double a[NB], b[NB];
+            for (int w = 0; w < NB; ++w) acc[u][w] = double4_t{0.0, 0.0, 0.0, 0.0};
+        for (int64_t i0 = i_begin; i0 < i_end; i0 += 4) {
+            const int64_t row = i0 + r;
+            const bool live = row < i_end;
+            double a[PBC], b[NB];
 #pragma unroll
-            for (int u = 0; u < NB; ++u) {
-                const int p = ty + 16 * u, q = tx + 16 * u;
-                a[u] = p < k ? (double)As[r * k + p] : 0.0;
-                b[u] = q < k ? (double)Bs[r * k + q] : 0.0;
+            for (int u = 0; u < PBC; ++u) {
+                const int col = 16 * (pg + u) + c;
+                a[u] = (live && pg + u < NB && col < k) ? (double)A[row * k + col] : 0.0;
             }
 #pragma unroll
-            for (int u = 0; u < NB; ++u)
+            for (int w = 0; w < NB; ++w) {
+                const int col = 16 * w + c;
+                b[w] = (live && col < k) ? (double)Bm[row * k + col] : 0.0;
+            }
 #pragma unroll
-                for (int v = 0; v < NB; ++v) acc[u][v] = fma(a[u], b[v], acc[u][v]);
+            for (int u = 0; u < PBC; ++u)
+#pragma unroll
+                for (int w = 0; w < NB; ++w) acc[u][w] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[w], acc[u][w], 0, 0, 0);
         }
-        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < PBC; ++u)
+#pragma unroll
+            for (int w = 0; w < NB; ++w)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int p = 16 * (pg + u) + r + 4 * v, q = 16 * w + c;
+                    if (pg + u < NB && p < k && q < k) out[p * k + q] = acc[u][w][v];
+                }
     }
-    double* out = partial + (int64_t)blockIdx.x * k * k;
-#pragma unroll
-    for (int u = 0; u < NB; ++u)
-#pragma unroll
-        for (int v = 0; v < NB; ++v) {
-            const int p = ty + 16 * u, q = tx + 16 * v;
-            if (p < k && q < k) out[p * k + q] = acc[u][v];
-        }
 }
 
 // G[e] = sum over blocks of partial[block][e] (symmetrised on request).  16 consecutive lanes share
@@ -293,7 +303,7 @@ hipError_t allow_lds(K kern, size_t bytes) {
 }  // namespace
 
 hipError_t SmallWs::alloc(int64_t N, int k) {
-    gram_blocks = (int)std::min<int64_t>(512, ceil_div(N, kGramRows));
+    gram_blocks = (int)std::min<int64_t>(512, ceil_div(ceil_div(N, 64), kGramWaves) * kGramWaves);  // wave slots
     const size_t kk = (size_t)k * k;
     const size_t doubles = (size_t)gram_blocks * kk + 3 * kk + (size_t)k + kk /*jacobi work*/;
     hipError_t e = buf.alloc(doubles * sizeof(double) + 64);
@@ -315,13 +325,14 @@ hipError_t SmallWs::alloc(int64_t N, int k) {
 }
 
 int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& ws, double* G, hipStream_t st) {
-    const int64_t rpb = ceil_div(ceil_div(N, ws.gram_blocks), kGramRows) * kGramRows;
-    const int blocks = (int)ceil_div(N, rpb);
-    const size_t lds = sizeof(float) * 2 * kGramRows * (size_t)k;
+    // every wave slot takes a multiple of 4 rows (one matrix instruction covers 4)
+    const int64_t rpw = ceil_div(ceil_div(N, ws.gram_blocks), 4) * 4;
+    const int blocks = (int)(ceil_div(ceil_div(N, rpw), kGramWaves) * kGramWaves);  // wave slots written (<= gram_blocks)
     const int NB = (k + 15) / 16;
-#define RFX_GRAM(nb)                                                                                              \
-    case nb:                                                                                                      \
-        hipLaunchKernelGGL(gram_partial_kernel<nb>, dim3(blocks), dim3(256), lds, st, A, Bm, N, k, rpb, ws.partial); \
+#define RFX_GRAM(nb)                                                                                                  \
+    case nb:                                                                                                          \
+        hipLaunchKernelGGL(gram_partial_kernel<nb>, dim3(blocks / kGramWaves), dim3(64 * kGramWaves), 0, st, A, Bm, N, k, \
+                           rpw, ws.partial);                                                                          \
         break;
     switch (NB) {
         RFX_GRAM(1) RFX_GRAM(2) RFX_GRAM(3) RFX_GRAM(4) RFX_GRAM(5) RFX_GRAM(6) RFX_GRAM(7) RFX_GRAM(8)

@@ -87,15 +87,21 @@ struct rfx_forest {
 
 namespace {
 
-constexpr int kTileSamples = 256;  // samples per workgroup
-constexpr int kTreeSlots = 4;      // trees walked concurrently by one workgroup
+constexpr int kTileSamples = 128;  // samples per workgroup
+constexpr int kTreeSlots = 8;      // thread groups (of kTileSamples threads) walking different trees
+constexpr int kWalks = 2;          // trees a thread walks at once
 constexpr int kBlock = kTileSamples * kTreeSlots;
+constexpr int kRound = kTreeSlots * kWalks;  // trees per round of a workgroup
 
-// One thread walks one (sample, tree) pair at a time.  A workgroup owns a tile of 256 samples,
-// keeps their feature rows in LDS (row stride odd, so a wave reading one feature of 64 different
-// rows hits 64 different banks) and walks them down a contiguous range of trees, four trees at a
-// time, each wave being 64 consecutive samples of one tree so that the leaf ids are written
-// coalesced along the sample axis of leaf[B][N].
+// A workgroup owns a tile of 128 samples and keeps their feature rows in LDS (row stride odd, so a
+// wave reading one feature of 64 different rows hits 64 different banks).  It walks them down a
+// contiguous range of trees, 16 trees per round: each of the 8 thread groups takes 2 trees and each
+// thread advances its 2 walks together.  A walk is a dependent chain (node record -> feature value ->
+// child index), so throughput comes from walks in flight: 1024 threads x 2 walks per workgroup and,
+// with the 128-row tile, two workgroups per compute unit.  (Measured at N = 100k, M = 100: 256-row
+// tiles with one walk per thread 4.4 ms per 1000 trees, this shape 2.3 ms; staging the upper tree
+// levels in LDS did not pay.)  A wave is 64 consecutive samples of one tree pair, so leaf ids are
+// written coalesced along the sample axis of leaf[B][N].
 template <bool kRowsInLds>
 __global__ __launch_bounds__(kBlock) void leaf_assign_kernel(const uint2* __restrict__ nodes,
                                                             const int64_t* __restrict__ tree_off, int32_t B,
@@ -103,7 +109,7 @@ __global__ __launch_bounds__(kBlock) void leaf_assign_kernel(const uint2* __rest
                                                             int32_t fbits, int32_t lds_stride,
                                                             int32_t trees_per_block, uint32_t* __restrict__ leaf) {
     extern __shared__ float xs[];
-    const int s = threadIdx.x & (kTileSamples - 1);
+    const int s = threadIdx.x % kTileSamples;
     const int slot = threadIdx.x / kTileSamples;
     const int64_t i0 = (int64_t)blockIdx.x * kTileSamples;
     const int64_t i = i0 + s;
@@ -121,15 +127,33 @@ __global__ __launch_bounds__(kBlock) void leaf_assign_kernel(const uint2* __rest
     const int b0 = blockIdx.y * trees_per_block;
     const int b1 = min(B, b0 + trees_per_block);
     const float* xrow = kRowsInLds ? xs + s * lds_stride : X + i * M;
-    for (int b = b0 + slot; b < b1; b += kTreeSlots) {
-        const uint2* t = nodes + tree_off[b];
-        uint2 rec = t[0];
-        while ((rec.y & fmask) != fmask) {
-            float x = xrow[rec.y & fmask];
-            uint32_t child = (rec.y >> fbits) + ((x <= __uint_as_float(rec.x)) ? 0u : 1u);
-            rec = t[child];
+    for (int bb = b0; bb < b1; bb += kRound) {
+        const uint2* t[kWalks];
+        uint2 rec[kWalks];
+#pragma unroll
+        for (int u = 0; u < kWalks; ++u) {
+            const int b = min(bb + slot * kWalks + u, b1 - 1);
+            t[u] = nodes + tree_off[b];
+            rec[u] = t[u][0];
         }
-        leaf[(int64_t)b * N + i] = rec.y >> fbits;
+        bool any = true;
+        while (any) {
+            any = false;
+#pragma unroll
+            for (int u = 0; u < kWalks; ++u) {
+                if ((rec[u].y & fmask) != fmask) {
+                    const float x = xrow[rec[u].y & fmask];
+                    const uint32_t child = (rec[u].y >> fbits) + ((x <= __uint_as_float(rec[u].x)) ? 0u : 1u);
+                    rec[u] = t[u][child];
+                    any = true;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kWalks; ++u) {
+            const int b = bb + slot * kWalks + u;
+            if (b < b1) leaf[(int64_t)b * N + i] = rec[u].y >> fbits;
+        }
     }
 }
 
@@ -298,8 +322,8 @@ int rfx_leaf_assign(const rfx_forest* F, const float* X, int64_t N, int32_t M, u
 
     const int64_t tiles = rfx::ceil_div(N, kTileSamples);
     // enough workgroups to fill 256 compute units several times over
-    int64_t chunks = std::min<int64_t>(rfx::ceil_div(F->B, kTreeSlots), std::max<int64_t>(1, rfx::ceil_div(4096, tiles)));
-    int32_t tpb = (int32_t)(rfx::ceil_div(rfx::ceil_div(F->B, chunks), kTreeSlots) * kTreeSlots);
+    int64_t chunks = std::min<int64_t>(rfx::ceil_div(F->B, kRound), std::max<int64_t>(1, rfx::ceil_div(4096, tiles)));
+    int32_t tpb = (int32_t)(rfx::ceil_div(rfx::ceil_div(F->B, chunks), kRound) * kRound);
     chunks = rfx::ceil_div(F->B, tpb);
     if (chunks > 65535) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_leaf_assign: too many tree chunks");
     dim3 grid((unsigned)tiles, (unsigned)chunks);
@@ -308,7 +332,7 @@ int rfx_leaf_assign(const rfx_forest* F, const float* X, int64_t N, int32_t M, u
     const size_t lds = sizeof(float) * (size_t)kTileSamples * (size_t)stride;
     hipStream_t st = rfx::as_stream(stream);
     rfx::TimedLaunch timed("leaf_assign_kernel", st);
-    if (lds <= 128 * 1024) {
+    if (lds <= 156 * 1024) {  // up to about 300 features; beyond that the rows are read from global memory
         auto kern = leaf_assign_kernel<true>;
         RFX_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(kern, grid, dim3(kBlock), lds, st, F->d_nodes, F->d_tree_off, F->B, X, N, M, F->fbits, stride,
