@@ -188,12 +188,14 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(leaf, N, B)
+        out["cpu_baseline"] = cpu_baseline(leaf, N, B, X, F, k)
     print(json.dumps(out))
 
 
-def cpu_baseline(leaf_dev, N, B):
-    """The oracle's naive pair counting, as it stands, on a bounded block of rows of the same leaf ids."""
+def cpu_baseline(leaf_dev, N, B, X, F, k):
+    """The oracle as it stands, on the host cores, on bounded samples of the same workload: naive pair
+    counting on a block of rows (the metric's unit), plus leaf assignment and one float64 implicit P.V
+    on the first trees of the forest."""
     import oracle
     leaf = leaf_dev.cpu().numpy().view(np.uint32)
     cores = len(os.sched_getaffinity(0))
@@ -211,8 +213,26 @@ def cpu_baseline(leaf_dev, N, B):
     oracle.counts_rows(leaf, 0, rows2)
     dt = time.perf_counter() - t0
     tests = rows2 * N * B
-    return {"value": tests / dt, "unit": "tests/s", "cores": cores, "kind": "oracle",
-            "sample": f"orc_counts_rows on rows 0..{rows2 - 1} x all {N} columns x {B} trees ({tests:.3g} tests, {dt:.1f}s)"}
+    out = {"value": tests / dt, "unit": "tests/s", "cores": cores, "kind": "oracle",
+           "sample": f"orc_counts_rows on rows 0..{rows2 - 1} x all {N} columns x {B} trees ({tests:.3g} tests, {dt:.1f}s)"}
+    # other phases, on the first Bs trees (context; same byte models as the GPU figures)
+    Bs = min(B, 64)
+    Fs = F.subset(Bs)
+    t0 = time.perf_counter()
+    sub_leaf, plen = oracle.leaf_assign(Fs, X)
+    dt_la = time.perf_counter() - t0
+    w_la = plen * 12 + 4 * N * Bs + 4 * N * X.shape[1]
+    rng = np.random.default_rng(1)
+    V = rng.standard_normal((N, k))
+    t0 = time.perf_counter()
+    oracle.pv_implicit(sub_leaf, V)
+    dt_pv = time.perf_counter() - t0
+    w_pv = Bs * N * (2 * 4 * k + 4) + 2 * 4 * N * k      # the float32 byte model, for comparison with the GPU figure
+    out["phases"] = {
+        "leaf_assign": {"trees": Bs, "seconds": dt_la, "walks_per_s": N * Bs / dt_la, "model_GBps": w_la / dt_la / 1e9},
+        "pv_implicit_f64": {"trees": Bs, "k": k, "seconds": dt_pv, "model_GBps": w_pv / dt_pv / 1e9},
+    }
+    return out
 
 
 if __name__ == "__main__":

@@ -77,24 +77,41 @@ __device__ __forceinline__ int64_t packed_index(int64_t i, int64_t j, int64_t N)
     return i * N - i * (i + 1) / 2 + (j - i - 1);
 }
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// The outputs are written once and never read back by the kernel: streaming (non-temporal) stores
+// keep them from displacing the bit planes in L2.
+#ifndef RFX_NT_STORES
+#define RFX_NT_STORES 1
+#endif
 template <class T>
-__device__ __forceinline__ void store_one(void* base, int64_t at, uint32_t v) {
-    static_cast<T*>(base)[at] = (T)v;
+__device__ __forceinline__ void stream_store(T* p, T v) {
+#if RFX_NT_STORES
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
 }
 
 __device__ __forceinline__ void store_count(void* base, int32_t u16, int64_t at, uint32_t v) {
     if (u16)
-        store_one<uint16_t>(base, at, v);
+        stream_store(static_cast<uint16_t*>(base) + at, (uint16_t)v);
     else
-        store_one<uint32_t>(base, at, v);
+        stream_store(static_cast<uint32_t*>(base) + at, v);
 }
 
 // 4 consecutive counts at base[at .. at+3]; `at` is a multiple of 4 and the row start is 16-byte aligned
 __device__ __forceinline__ void store4_count(void* base, int32_t u16, int64_t at, const uint32_t (&v)[4]) {
     if (u16)
-        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(base) + at) = make_uint2(v[0] | (v[1] << 16), v[2] | (v[3] << 16));
+        stream_store(reinterpret_cast<u32x2_t*>(static_cast<uint16_t*>(base) + at), u32x2_t{v[0] | (v[1] << 16), v[2] | (v[3] << 16)});
     else
-        *reinterpret_cast<uint4*>(static_cast<uint32_t*>(base) + at) = make_uint4(v[0], v[1], v[2], v[3]);
+        stream_store(reinterpret_cast<u32x4_t*>(static_cast<uint32_t*>(base) + at), u32x4_t{v[0], v[1], v[2], v[3]});
+}
+
+__device__ __forceinline__ void store4_float(float* base, int64_t at, const float (&p)[4]) {
+    stream_store(reinterpret_cast<f32x4_t*>(base + at), f32x4_t{p[0], p[1], p[2], p[3]});
 }
 
 // Writes one wave tile.  acc[r][j] belongs to the pair (a_tile + 4*lane + r, b0 + j): the mismatch
@@ -130,7 +147,7 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
                 }
                 if (out.counts) store4_count(out.counts, out.u16, at, c);
                 if (kOob && out.den) store4_count(out.den, out.u16, at, d);
-                if (out.prox) *reinterpret_cast<float4*>(out.prox + at) = make_float4(p[0], p[1], p[2], p[3]);
+                if (out.prox) store4_float(out.prox, at, p);
                 __builtin_amdgcn_sched_barrier(0);  // keep each store's address arithmetic next to it
             }
         }
@@ -170,7 +187,7 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
                             p[e] = kOob ? oob_quotient(c[e], d[e], a == b0 + col + e) : quotient(c[e]);
-                        *reinterpret_cast<float4*>(out.prox + mt) = make_float4(p[0], p[1], p[2], p[3]);
+                        store4_float(out.prox, mt, p);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -202,7 +219,7 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
                     const int64_t at = packed_index(b, a, N);
                     if (out.counts) store_count(out.counts, out.u16, at, c);
                     if (kOob && out.den) store_count(out.den, out.u16, at, d);
-                    if (out.prox) out.prox[at] = p;
+                    if (out.prox) stream_store(out.prox + at, p);
                 }
             } else {
                 const int64_t at = b * N + a, mt = a * N + b;
@@ -215,8 +232,8 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
                     store_count(out.den, out.u16, mt, d);
                 }
                 if (out.prox) {
-                    out.prox[at] = p;
-                    out.prox[mt] = p;
+                    stream_store(out.prox + at, p);
+                    stream_store(out.prox + mt, p);
                 }
             }
         }
