@@ -18,6 +18,7 @@
 //               registers and sweeps the trees in order, so all waves touch the same trees'
 //               sums at about the same time and those rows stay cache-resident)
 #include <algorithm>
+#include <type_traits>
 #include <vector>
 
 #include "common.h"
@@ -76,42 +77,48 @@ __global__ __launch_bounds__(1024) void pv_hist_kernel(const uint32_t* __restric
 
 // One workgroup per tree.  With c[q][l] the part histograms: seg_start[b*Lb + l] = b*N + (samples of
 // the tree in leaves < l); c[q][l] is replaced by the cursor seg_start + sum_{q' < q} c[q'][l]; slots
-// with more than kBigLeaf members are appended to the big list.
+// with more than kBigLeaf members are appended to the big list.  Leaves are taken 256 at a time,
+// one per thread, so that every access to c is coalesced; the running offset is carried across tiles.
 __global__ __launch_bounds__(256) void pv_scan_kernel(uint32_t* __restrict__ count, int64_t N, int32_t B, int32_t Lb, int32_t Q,
                                                      uint32_t* __restrict__ seg_start, uint32_t* __restrict__ big,
                                                      int* __restrict__ n_big) {
-    __shared__ uint32_t part[256];
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t carry;
     const int b = blockIdx.x;
-    const int t = threadIdx.x;
-    const int per = (Lb + 255) / 256;
-    const int lo = min(Lb, t * per), hi = min(Lb, lo + per);
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     uint32_t* c = count + (int64_t)b * Q * Lb;
-    uint32_t sum = 0;
-    for (int l = lo; l < hi; ++l)
-        for (int q = 0; q < Q; ++q) sum += c[(int64_t)q * Lb + l];
-    part[t] = sum;
+    if (t == 0) carry = (uint32_t)((int64_t)b * N);
     __syncthreads();
-    if (t == 0) {
-        uint32_t run = (uint32_t)((int64_t)b * N);
-        for (int w = 0; w < 256; ++w) {
-            uint32_t v = part[w];
-            part[w] = run;
-            run += v;
+    for (int l0 = 0; l0 < Lb; l0 += 256) {
+        const int l = l0 + t;
+        uint32_t tot = 0;
+        if (l < Lb)
+            for (int q = 0; q < Q; ++q) tot += c[(int64_t)q * Lb + l];
+        // inclusive scan inside the wave, then across the 4 waves
+        uint32_t inc = tot;
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t up = __shfl_up(inc, off);
+            if (lane >= off) inc += up;
         }
-    }
-    __syncthreads();
-    uint32_t run = part[t];
-    for (int l = lo; l < hi; ++l) {
-        seg_start[(int64_t)b * Lb + l] = run;
-        const uint32_t first = run;
-        for (int q = 0; q < Q; ++q) {
-            const uint32_t v = c[(int64_t)q * Lb + l];
-            c[(int64_t)q * Lb + l] = run;
-            run += v;
+        if (lane == 63) wave_tot[w] = inc;
+        __syncthreads();
+        uint32_t before = carry;
+        for (int u = 0; u < w; ++u) before += wave_tot[u];
+        uint32_t run = before + inc - tot;  // exclusive
+        if (l < Lb) {
+            seg_start[(int64_t)b * Lb + l] = run;
+            for (int q = 0; q < Q; ++q) {
+                const uint32_t v = c[(int64_t)q * Lb + l];
+                c[(int64_t)q * Lb + l] = run;
+                run += v;
+            }
+            if (tot > (uint32_t)kBigLeaf) big[atomicAdd(n_big, 1)] = (uint32_t)b * (uint32_t)Lb + (uint32_t)l;
         }
-        if (run - first > (uint32_t)kBigLeaf) big[atomicAdd(n_big, 1)] = (uint32_t)b * (uint32_t)Lb + (uint32_t)l;
+        __syncthreads();
+        if (t == 255) carry = before + inc;
+        __syncthreads();
     }
-    if (b == B - 1 && t == 255) seg_start[(int64_t)B * Lb] = (uint32_t)((int64_t)B * N);
+    if (b == B - 1 && t == 0) seg_start[(int64_t)B * Lb] = (uint32_t)((int64_t)B * N);
 }
 
 // Stable scatter: one wave per (part, tree) walks its samples 64 at a time in ascending order.  Lanes
@@ -177,21 +184,32 @@ __device__ __forceinline__ void sum_members(const uint32_t* __restrict__ perm, u
         acc[c] = 0.0f;
     }
     if (lo >= hi) return;
-    for (uint32_t t0 = lo; t0 < hi; t0 += kSumBatch * RPW) {
-        float v[kSumBatch][KCH];
+    // one batch of NBATCH row loads per lane group, all issued before any is added
+    auto batch = [&](uint32_t t0, auto nbatch) {
+        constexpr int NBATCH = decltype(nbatch)::value;
+        float v[NBATCH][KCH];
 #pragma unroll
-        for (int u = 0; u < kSumBatch; ++u) {
+        for (int u = 0; u < NBATCH; ++u) {
             const uint32_t t = t0 + u * RPW + grp;
             const uint32_t j = perm[min(t, hi - 1)];  // clamped: always a valid member
 #pragma unroll
             for (int c = 0; c < KCH; ++c) v[u][c] = V[(int64_t)j * k + col[c]];
         }
 #pragma unroll
-        for (int u = 0; u < kSumBatch; ++u) {
+        for (int u = 0; u < NBATCH; ++u) {
             const bool live = t0 + u * RPW + grp < hi;
 #pragma unroll
             for (int c = 0; c < KCH; ++c) acc[c] += live ? v[u][c] : 0.0f;
         }
+    };
+    // most leaves of a purity-grown tree hold one to four samples: do not pay for a full batch there
+    const uint32_t n = hi - lo;
+    if (n <= 2u * RPW) {
+        batch(lo, std::integral_constant<int, 2>{});
+    } else if (n <= 4u * RPW) {
+        batch(lo, std::integral_constant<int, 4>{});
+    } else {
+        for (uint32_t t0 = lo; t0 < hi; t0 += kSumBatch * RPW) batch(t0, std::integral_constant<int, kSumBatch>{});
     }
     if (RPW > 1) {
 #pragma unroll
@@ -204,23 +222,91 @@ __device__ __forceinline__ void sum_members(const uint32_t* __restrict__ perm, u
     }
 }
 
-// Leaf sums of the slots with at most kBigLeaf members: one wave per slot.
+// Leaf sums of the slots with at most kBigLeaf members.  Most of them hold one to four samples, so
+// a wave's time is three dependent memory round trips (segment bounds, member indices, rows) and
+// almost no traffic; a wave therefore takes kSlotsPerWave consecutive slots at once and has the
+// first four rows of each in flight together before it finishes the longer ones.
+constexpr int kSlotsPerWave = 4;
+
 template <int KCH, int RPW>
 __global__ __launch_bounds__(256) void pv_leaf_sum_kernel(const uint32_t* __restrict__ seg_start,
                                                          const uint32_t* __restrict__ perm, int64_t n_slots,
-                                                         const float* __restrict__ V, int32_t k, float* __restrict__ S) {
+                                                         uint32_t n_perm, const float* __restrict__ V, int32_t k,
+                                                         float* __restrict__ S) {
+    constexpr int G = kSlotsPerWave, NF = 4;  // NF = rows per lane group in the first batch
     const int lane = threadIdx.x & 63;
-    const int64_t slot = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (slot >= n_slots) return;
-    const uint32_t lo = seg_start[slot], hi = seg_start[slot + 1];
-    if (lo == hi || hi - lo > (uint32_t)kBigLeaf) return;  // empty (its row of S is never read) or handled below
-    float acc[KCH];
-    sum_members<KCH, RPW>(perm, lo, hi, V, k, lane, acc);
-    if (lane < 64 / RPW) {
+    const int grp = lane / (64 / RPW);
+    const int64_t slot0 = ((int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * G;
+    if (slot0 >= n_slots) return;
+    int col[KCH];
 #pragma unroll
-        for (int c = 0; c < KCH; ++c) {
-            const int cc = lane + 64 * c;
-            if (cc < k) S[slot * k + cc] = acc[c];
+    for (int c = 0; c < KCH; ++c) col[c] = min(lane_col<RPW>(lane) + 64 * c, k - 1);
+    uint32_t lo[G], hi[G];
+    bool mine[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int64_t s = min(slot0 + g, n_slots - 1);
+        lo[g] = seg_start[s];
+        hi[g] = seg_start[s + 1];
+        // empty slots are never read by the gather; big ones belong to the workgroup kernel
+        mine[g] = slot0 + g < n_slots && hi[g] > lo[g] && hi[g] - lo[g] <= (uint32_t)kBigLeaf;
+    }
+    float v[G][NF][KCH];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int u = 0; u < NF; ++u) {
+            const uint32_t t = lo[g] + u * RPW + grp;
+            const uint32_t j = perm[min(min(t, hi[g] - 1), n_perm - 1)];  // clamped: always a valid index
+#pragma unroll
+            for (int c = 0; c < KCH; ++c) v[g][u][c] = V[(int64_t)j * k + col[c]];
+        }
+    float acc[G][KCH];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) acc[g][c] = 0.0f;
+#pragma unroll
+        for (int u = 0; u < NF; ++u) {
+            const bool live = mine[g] && lo[g] + u * RPW + grp < hi[g];
+#pragma unroll
+            for (int c = 0; c < KCH; ++c) acc[g][c] += live ? v[g][u][c] : 0.0f;
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (!mine[g]) continue;
+        for (uint32_t t0 = lo[g] + NF * RPW; t0 < hi[g]; t0 += kSumBatch * RPW) {
+            float w[kSumBatch][KCH];
+#pragma unroll
+            for (int u = 0; u < kSumBatch; ++u) {
+                const uint32_t t = t0 + u * RPW + grp;
+                const uint32_t j = perm[min(t, hi[g] - 1)];
+#pragma unroll
+                for (int c = 0; c < KCH; ++c) w[u][c] = V[(int64_t)j * k + col[c]];
+            }
+#pragma unroll
+            for (int u = 0; u < kSumBatch; ++u) {
+                const bool live = t0 + u * RPW + grp < hi[g];
+#pragma unroll
+                for (int c = 0; c < KCH; ++c) acc[g][c] += live ? w[u][c] : 0.0f;
+            }
+        }
+        if (RPW > 1) {
+#pragma unroll
+            for (int c = 0; c < KCH; ++c) {
+                float tot = __shfl(acc[g][c], lane_col<RPW>(lane));
+#pragma unroll
+                for (int q = 1; q < RPW; ++q) tot += __shfl(acc[g][c], lane_col<RPW>(lane) + q * (64 / RPW));
+                acc[g][c] = tot;
+            }
+        }
+        if (lane < 64 / RPW) {
+#pragma unroll
+            for (int c = 0; c < KCH; ++c) {
+                const int cc = lane + 64 * c;
+                if (cc < k) S[(slot0 + g) * k + cc] = acc[g][c];
+            }
         }
     }
 }
@@ -324,8 +410,9 @@ int launch_apply(const rfx_pv_plan* p, const float* V, int32_t k, float* Y, hipS
     const int64_t n_slots = (int64_t)p->B * p->Lb;
     {
         rfx::TimedLaunch timed("pv_leaf_sum_kernel", st);
-        hipLaunchKernelGGL((pv_leaf_sum_kernel<KCH, RPW>), dim3((unsigned)rfx::ceil_div(n_slots, 4)), dim3(256), 0, st,
-                           p->d_seg_start, p->d_perm, n_slots, V, k, p->d_S);
+        hipLaunchKernelGGL((pv_leaf_sum_kernel<KCH, RPW>), dim3((unsigned)rfx::ceil_div(n_slots, 4 * kSlotsPerWave)),
+                           dim3(256), 0, st, p->d_seg_start, p->d_perm, n_slots, (uint32_t)((int64_t)p->B * p->N), V, k,
+                           p->d_S);
         if (p->n_big > 0)
             hipLaunchKernelGGL((pv_leaf_sum_big_kernel<KCH, RPW>), dim3((unsigned)p->n_big), dim3(64 * kBigWaves), 0, st,
                                p->d_big, p->d_seg_start, p->d_perm, V, k, p->d_S);
