@@ -135,7 +135,7 @@ def main():
     achieved = ops_per_launch / (tile_ms * 1e-3) if tile_ms > 0 else 0.0
     # HBM-side bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, calibrated on a 4 GiB copy); measured for workload 4 only
-    traffic = (39132487.3 * 2.0 + 39546683.3) * 1024.0 if (c.cfg == 4 and not reduced) else None
+    traffic = (39088853.4 * 2.0 + 42333071.5) * 1024.0 if (c.cfg == 4 and not reduced) else None
     roofline = {"kernel": "prox_tile_kernel", "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_VALU_LANE_OPS / 1e12,
                 "unit": "T lane-ops/s", "frac": achieved / PEAK_VALU_LANE_OPS, "traffic": traffic,
                 "traffic_source": "profiles/bench_cfg4_pmc_fetch_write.txt (L2-to-fabric bytes; output is 4*N*N)",
