@@ -196,7 +196,80 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
         return;
     }
 
-    // Packed layout, ragged edge tiles, or N not a multiple of 4: element-wise stores.
+    if (out.packed && b0 + J <= a_tile && a_tile + kATile <= N) {
+        // Packed layout, tile strictly below the diagonal and inside the matrix.  Row b of the packed
+        // triangle holds this wave's 256 a values as one contiguous run, but the run starts at an
+        // arbitrary element offset.  With phi = offset mod 4, every lane builds the aligned group of 4
+        // that starts phi elements before its own values from its left neighbour's last phi values and
+        // its own first 4 - phi, and stores it as one vector; lane 0 writes only its own part of the
+        // first group and lane 63 appends the last phi values one by one.
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            const int64_t b = b0 + j;
+            const int64_t o = packed_index(b, a_tile, N);  // packed position of (b, a_tile)
+            const int phi = (int)(o & 3);
+            uint32_t c[kR], d[kR];
+            float p[kR];
+#pragma unroll
+            for (int r = 0; r < kR; ++r) {
+                c[r] = kOob ? (acc[r][j] & 0xffffu) : (uint32_t)out.B - acc[r][j];
+                d[r] = kOob ? (acc[r][j] >> 16) : 0u;
+                p[r] = kOob ? oob_quotient(c[r], d[r], false) : quotient(c[r]);
+            }
+            // w[e] = element at aligned position 4*lane + e of the run shifted right by phi
+            auto shifted = [&](const uint32_t (&own)[kR], uint32_t (&w)[kR]) {
+                uint32_t prev[kR];
+#pragma unroll
+                for (int r = 0; r < kR; ++r) prev[r] = __shfl_up(own[r], 1);
+#pragma unroll
+                for (int e = 0; e < kR; ++e) {
+                    // candidates for phi = 0, 1, 2, 3: own[e], then one further to the left each time
+                    const uint32_t s0 = own[e];
+                    const uint32_t s1 = e >= 1 ? own[e - 1] : prev[3 + e];
+                    const uint32_t s2 = e >= 2 ? own[e - 2] : prev[2 + e];
+                    const uint32_t s3 = e >= 3 ? own[e - 3] : prev[1 + e];
+                    w[e] = phi == 0 ? s0 : (phi == 1 ? s1 : (phi == 2 ? s2 : s3));
+                }
+            };
+            auto emit = [&](auto* base, const uint32_t (&own)[kR], auto store4, auto store1) {
+                uint32_t w[kR];
+                shifted(own, w);
+                const int64_t at = o - phi + 4 * lane;  // aligned group of this lane
+                if (lane > 0 || phi == 0) {
+                    store4(base, at, w);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < kR; ++e)
+                        if (e >= phi) store1(base, at + e, w[e]);
+                }
+                if (lane == 63) {
+#pragma unroll
+                    for (int e = 0; e < kR - 1; ++e)
+                        if (e < phi) store1(base, at + 4 + e, own[kR - phi + e]);
+                }
+            };
+            auto count4 = [&](void* base, int64_t at, const uint32_t (&w)[kR]) { store4_count(base, out.u16, at, w); };
+            auto count1 = [&](void* base, int64_t at, uint32_t v) { store_count(base, out.u16, at, v); };
+            if (out.counts) emit(out.counts, c, count4, count1);
+            if (kOob && out.den) emit(out.den, d, count4, count1);
+            if (out.prox) {
+                uint32_t bits[kR];
+#pragma unroll
+                for (int r = 0; r < kR; ++r) bits[r] = __float_as_uint(p[r]);
+                auto float4s = [&](float* base, int64_t at, const uint32_t (&w)[kR]) {
+                    const float f[4] = {__uint_as_float(w[0]), __uint_as_float(w[1]), __uint_as_float(w[2]), __uint_as_float(w[3])};
+                    store4_float(base, at, f);
+                };
+                auto float1 = [&](float* base, int64_t at, uint32_t v) { stream_store(base + at, __uint_as_float(v)); };
+                emit(out.prox, bits, float4s, float1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        return;
+    }
+
+    // Ragged edge tiles, tiles on the diagonal of the packed layout, or N not a multiple of 4:
+    // element-wise stores.
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         const int64_t b = b0 + j;
