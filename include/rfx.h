@@ -171,6 +171,30 @@ int rfx_prox_lowrank(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bo
 int rfx_quantise_int8(const float* V, const float* eigvals, int64_t N, int32_t k, int8_t* Q, float* scales,
                       void* stream);
 
+/* Other encodings of the factor A = V diag(sqrt(lambda)) ("Low-Rank Factorization and Quantization
+ * Trade-offs": NF4 (4-bit), INT8 (8-bit), FP16 (16-bit), FP32 (32-bit)).
+ *   RFX_ENC_INT8  as rfx_quantise_int8: codes int8 [N][k], scales float32 [k].
+ *   RFX_ENC_FP16  codes IEEE binary16 [N][k], round-to-nearest-even; no scales.
+ *   RFX_ENC_FP32  codes float32 [N][k]; no scales.
+ *   RFX_ENC_NF4   the 4-bit NormalFloat type of the QLoRA paper: 16 fixed levels in [-1, 1] applied to
+ *                 values normalised by their block's absolute maximum.  Blocks are 64 consecutive rows
+ *                 of one column.  codes uint8 [ceil(N/2)][k]: rows 2i and 2i+1 of a column in the low and
+ *                 high nibble (a missing last row holds the zero level); scales float32 [ceil(N/64)][k]
+ *                 = block maxima of |A| (1 for an all-zero block).  The nearest level is decided in
+ *                 float32 by counting the midpoints of adjacent levels below the normalised value.
+ * rfx_factor_sizes: bytes of `codes` and number of floats of `scales` for an encoding ([host] out).
+ * rfx_quantise_factor / rfx_dequantise_factor: V, eigvals as rfx_quantise_int8; codes, scales, A
+ * [device]; A float32 [N][k] out.  Asynchronous. */
+#define RFX_ENC_INT8 0
+#define RFX_ENC_FP16 1
+#define RFX_ENC_NF4 2
+#define RFX_ENC_FP32 3
+int rfx_factor_sizes(int encoding, int64_t N, int32_t k, int64_t* code_bytes, int64_t* n_scales);
+int rfx_quantise_factor(const float* V, const float* eigvals, int64_t N, int32_t k, int encoding, void* codes,
+                        float* scales, void* stream);
+int rfx_dequantise_factor(const void* codes, const float* scales, int64_t N, int32_t k, int encoding, float* A,
+                          void* stream);
+
 /* 3-D scaling coordinates from the INT8 factors ("GPU-Accelerated 3D MDS from Low-Rank
  * Proximity Matrices", Steps 1-4).  With A^ = Q diag(scales), P^ = A^ A^^T and D = 1 - P^ (the
  * paper's max P - P with max P = 1): G = -1/2 H D2 H, H = I - 11^T/N, D2 = D o D
@@ -191,6 +215,9 @@ int rfx_quantise_int8(const float* V, const float* eigvals, int64_t N, int32_t k
 int rfx_mds3d(const int8_t* Q, const float* scales, int64_t N, int32_t k, int dissim_mode, int32_t m,
               int32_t max_iters, float tol, const float* x0, float* coords, float* eigvals,
               int32_t* iters_done, void* stream);
+/* The same from a float32 factor A [device] [N][k] (any encoding after rfx_dequantise_factor). */
+int rfx_mds3d_factor(const float* A, int64_t N, int32_t k, int dissim_mode, int32_t m, int32_t max_iters, float tol,
+                     const float* x0, float* coords, float* eigvals, int32_t* iters_done, void* stream);
 
 #ifdef __cplusplus
 }

@@ -302,3 +302,113 @@ def mds3d_implicit(Q, s, mode: int = SQUARED, dims: int = 3, tol: float = 1e-12)
     lam = lam[order]
     U = fix_signs(U[:, order])
     return U * np.sqrt(np.maximum(lam, 0.0))[None, :], lam
+
+
+# --------------------------------------------------------------------------- other factor encodings
+# The paper lists four precisions for the low-rank factors: NF4 (4-bit), INT8, FP16 and FP32
+# ("Low-Rank Factorization and Quantization Trade-offs").  INT8 is quantise_int8 above.  FP16 and
+# FP32 store A = V diag(sqrt(lam)) rounded to nearest-even.  NF4 is the 4-bit NormalFloat type of
+# the QLoRA paper the RFX paper cites: 16 fixed levels in [-1, 1] applied to values normalised by
+# the absolute maximum of their block; this build's reading takes blocks of 64 consecutive rows of
+# one column (the per-column scaling of the INT8 reading, refined to blocks), two codes per byte
+# (even row in the low nibble), and decides "nearest level" in float32 by counting the midpoints
+# between adjacent levels that lie below the normalised value.
+ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
+NF4_BLOCK = 64
+NF4_LEVELS = np.array([-1.0, -0.6961928009986877, -0.5250730514526367, -0.39491748809814453,
+                       -0.28444138169288635, -0.18477343022823334, -0.09105003625154495, 0.0,
+                       0.07958029955625534, 0.16093020141124725, 0.24611230194568634, 0.33791524171829224,
+                       0.44070982933044434, 0.5626170039176941, 0.7229568362236023, 1.0], dtype=np.float32)
+
+
+def _factor(V, lam) -> np.ndarray:
+    V = np.asarray(V, np.float32)
+    lam = np.asarray(lam, np.float32)
+    return (V * np.sqrt(np.maximum(lam, np.float32(0.0)))[None, :]).astype(np.float32)
+
+
+def quantise_factor(V, lam, encoding: int):
+    """Returns (codes, scales) of A = V diag(sqrt(lam)) in the given encoding (float32 arithmetic).
+
+    INT8: int8 [N][k], scales float32 [k].  FP16: float16 [N][k], no scales.  FP32: float32 [N][k].
+    NF4: uint8 [ceil(N/2)][k] (rows 2i and 2i+1 in the low and high nibble; a missing last row is the
+    zero level), scales float32 [ceil(N/64)][k] = block maxima of |A| (1 for an all-zero block).
+    """
+    if encoding == ENC_INT8:
+        return quantise_int8(V, lam)
+    A = _factor(V, lam)
+    N, k = A.shape
+    if encoding == ENC_FP32:
+        return A, np.zeros(0, np.float32)
+    if encoding == ENC_FP16:
+        return A.astype(np.float16), np.zeros(0, np.float32)
+    if encoding != ENC_NF4:
+        raise ValueError("unknown encoding")
+    nb = (N + NF4_BLOCK - 1) // NF4_BLOCK
+    pad = np.zeros((nb * NF4_BLOCK, k), np.float32)
+    pad[:N] = A
+    blocks = pad.reshape(nb, NF4_BLOCK, k)
+    amax = np.abs(blocks).max(axis=1).astype(np.float32)
+    scales = np.where(amax > 0, amax, np.float32(1.0)).astype(np.float32)
+    x = (blocks / scales[:, None, :]).astype(np.float32).reshape(nb * NF4_BLOCK, k)[:N]
+    mid = ((NF4_LEVELS[:-1] + NF4_LEVELS[1:]) * np.float32(0.5)).astype(np.float32)
+    code = (x[:, :, None] > mid[None, None, :]).sum(axis=2).astype(np.uint8)
+    if N % 2:
+        code = np.concatenate([code, np.full((1, k), 7, np.uint8)], axis=0)
+    packed = (code[0::2] | (code[1::2] << 4)).astype(np.uint8)
+    return packed, scales
+
+
+def dequantise_factor(codes, scales, encoding: int, N: int) -> np.ndarray:
+    """float32 [N][k] factor represented by (codes, scales)."""
+    if encoding == ENC_INT8:
+        return (codes.astype(np.float32) * np.asarray(scales, np.float32)[None, :]).astype(np.float32)
+    if encoding in (ENC_FP16, ENC_FP32):
+        return codes.astype(np.float32)
+    k = codes.shape[1]
+    code = np.empty((2 * codes.shape[0], k), np.uint8)
+    code[0::2] = codes & 0xF
+    code[1::2] = codes >> 4
+    vals = NF4_LEVELS[code[:N]]
+    s = np.repeat(np.asarray(scales, np.float32), NF4_BLOCK, axis=0)[:N]
+    return (vals * s).astype(np.float32)
+
+
+def mds3d_from_factor(A, mode: int = SQUARED, dims: int = 3):
+    """Dense Torgerson scaling from a float factor A (P^ = A A^T).  Small N only."""
+    G = mds_gram_dense(np.asarray(A, np.float64), mode)
+    lam, U = np.linalg.eigh(0.5 * (G + G.T))
+    lam = lam[::-1][:dims].copy()
+    U = fix_signs(U[:, ::-1][:, :dims])
+    return U * np.sqrt(np.maximum(lam, 0.0))[None, :], lam
+
+
+def mds3d_from_dense_proximity(P, mode: int = SQUARED, dims: int = 3):
+    """Torgerson scaling of the full proximity matrix (the paper's "CPU full matrix" pathway)."""
+    P = np.asarray(P, np.float64)
+    D = 1.0 - P
+    G = double_centre(D * D if mode == SQUARED else D)
+    lam, U = np.linalg.eigh(0.5 * (G + G.T))
+    lam = lam[::-1][:dims].copy()
+    U = fix_signs(U[:, ::-1][:, :dims])
+    return U * np.sqrt(np.maximum(lam, 0.0))[None, :], lam
+
+
+def mds_correlation(X1, X2, max_pairs: int = 2_000_000, seed: int = 0) -> float:
+    """Pearson correlation between the pairwise Euclidean distances of two embeddings (invariant to
+    rotation, reflection and translation).  This is this build's reading of the paper's "MDS
+    correlation" between compressed and full-matrix embeddings, which the paper does not define."""
+    X1 = np.asarray(X1, np.float64)
+    X2 = np.asarray(X2, np.float64)
+    n = X1.shape[0]
+    rng = np.random.default_rng(seed)
+    if n * (n - 1) // 2 <= max_pairs:
+        i, j = np.triu_indices(n, 1)
+    else:
+        i = rng.integers(0, n, size=max_pairs)
+        j = rng.integers(0, n, size=max_pairs)
+        keep = i != j
+        i, j = i[keep], j[keep]
+    d1 = np.linalg.norm(X1[i] - X1[j], axis=1)
+    d2 = np.linalg.norm(X2[i] - X2[j], axis=1)
+    return float(np.corrcoef(d1, d2)[0, 1])

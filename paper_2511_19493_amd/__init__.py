@@ -20,11 +20,13 @@ _lib = None
 U16, U32 = 0, 1
 FULL, UPPER_PACKED = 0, 1
 MDS_SQUARED, MDS_LINEAR = 0, 1
+ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
 
 EXPORTS = (
     "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
     "rfx_prox_dense", "rfx_prox_oob", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
-    "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d",
+    "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
+    "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
 )
 
 
@@ -69,6 +71,10 @@ def load():
             "rfx_prox_lowrank": [vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp],
             "rfx_quantise_int8": [vp, vp, i64, i32, vp, vp, vp],
             "rfx_mds3d": [vp, vp, i64, i32, ci, i32, i32, f32, vp, vp, vp, ctypes.POINTER(i32), vp],
+            "rfx_mds3d_factor": [vp, i64, i32, ci, i32, i32, f32, vp, vp, vp, ctypes.POINTER(i32), vp],
+            "rfx_factor_sizes": [ci, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)],
+            "rfx_quantise_factor": [vp, vp, i64, i32, ci, vp, vp, vp],
+            "rfx_dequantise_factor": [vp, vp, i64, i32, ci, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(lib, name)
@@ -276,4 +282,45 @@ def mds3d(Q, scales, x0, mode: int = MDS_SQUARED, max_iters: int = 300, tol: flo
     _check(load().rfx_mds3d(_dev(Q, torch.int8), _dev(scales, torch.float32, (k,)), N, k, mode, m, max_iters, tol,
                             _dev(x0, torch.float32, (N, m)), coords.data_ptr(), ev.data_ptr(), ctypes.byref(it),
                             _stream()))
+    return coords, ev, int(it.value)
+
+
+def factor_sizes(encoding: int, N: int, k: int) -> Tuple[int, int]:
+    """rfx_factor_sizes: (bytes of codes, floats of scales)."""
+    cb, ns = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(load().rfx_factor_sizes(encoding, N, k, ctypes.byref(cb), ctypes.byref(ns)))
+    return cb.value, ns.value
+
+
+def quantise_factor(V, eigvals, encoding: int):
+    """rfx_quantise_factor: returns (codes uint8 buffer of rfx_factor_sizes bytes, scales float32)."""
+    import torch
+    N, k = V.shape
+    cb, ns = factor_sizes(encoding, N, k)
+    codes = torch.empty(cb, dtype=torch.uint8, device=V.device)
+    scales = torch.empty(max(ns, 1), dtype=torch.float32, device=V.device)
+    _check(load().rfx_quantise_factor(_dev(V, torch.float32), _dev(eigvals, torch.float32, (k,)), N, k, encoding,
+                                      codes.data_ptr(), scales.data_ptr(), _stream()))
+    return codes, scales[:ns]
+
+
+def dequantise_factor(codes, scales, N: int, k: int, encoding: int):
+    """rfx_dequantise_factor: float32 [N][k]."""
+    import torch
+    A = torch.empty((N, k), dtype=torch.float32, device=codes.device)
+    _check(load().rfx_dequantise_factor(codes.data_ptr(), scales.data_ptr() if scales is not None and scales.numel() else 0,
+                                        N, k, encoding, A.data_ptr(), _stream()))
+    return A
+
+
+def mds3d_factor(A, x0, mode: int = MDS_SQUARED, max_iters: int = 300, tol: float = 1e-6) -> Tuple:
+    """rfx_mds3d_factor: as mds3d, from a float32 factor."""
+    import torch
+    N, k = A.shape
+    m = x0.shape[1]
+    coords = torch.empty((N, 3), dtype=torch.float32, device=A.device)
+    ev = torch.empty(3, dtype=torch.float32, device=A.device)
+    it = ctypes.c_int32(0)
+    _check(load().rfx_mds3d_factor(_dev(A, torch.float32), N, k, mode, m, max_iters, tol, _dev(x0, torch.float32, (N, m)),
+                                   coords.data_ptr(), ev.data_ptr(), ctypes.byref(it), _stream()))
     return coords, ev, int(it.value)

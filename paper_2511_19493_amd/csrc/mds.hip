@@ -52,7 +52,7 @@ __global__ void col_sums_reduce_kernel(const double* __restrict__ partial, int b
 //   partialT[block][c][q]    = sum_i u_i a_iq
 //   partialM[block][c][p][q] = sum_i u_i a_ip a_iq        (SQUARED only)
 template <int NB>
-__global__ __launch_bounds__(256) void mds_moments_kernel(const int8_t* __restrict__ Q, const float* __restrict__ scales,
+__global__ __launch_bounds__(256) void mds_moments_kernel(const float* __restrict__ A,
                                                          const float* __restrict__ X, const double* __restrict__ colsum,
                                                          int64_t N, int k, int m, int64_t rows_per_block, int squared,
                                                          double* __restrict__ partialM, double* __restrict__ partialT) {
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void mds_moments_kernel(const int8_t* __restri
     const int64_t i_end = min(N, i_begin + rows_per_block);
     for (int64_t i0 = i_begin; i0 < i_end; i0 += kRowsStage) {
         const int rows = (int)min((int64_t)kRowsStage, i_end - i0);
-        for (int e = threadIdx.x; e < rows * k; e += 256) As[e] = (float)Q[i0 * k + e] * scales[e % k];
+        for (int e = threadIdx.x; e < rows * k; e += 256) As[e] = A[i0 * k + e];
         if (threadIdx.x < rows) us[threadIdx.x] = (double)X[(i0 + threadIdx.x) * m + c] - mean;
         __syncthreads();
         for (int r = 0; r < rows; ++r) {
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void moments_reduce_kernel(const double* __res
 // (RT/16) x NB register tile per thread of the product A^ M_c, then a row reduction over the
 // 16 threads that share a row.
 template <int NB, int RT>
-__global__ __launch_bounds__(256) void mds_quad_kernel(const int8_t* __restrict__ Q, const float* __restrict__ scales,
+__global__ __launch_bounds__(256) void mds_quad_kernel(const float* __restrict__ A,
                                                       const double* __restrict__ M, const double* __restrict__ T,
                                                       int64_t N, int k, int m, int squared, float* __restrict__ Z) {
     extern __shared__ double quad_sm[];
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void mds_quad_kernel(const int8_t* __restrict_
         for (int e = threadIdx.x; e < k * k; e += 256) Ms[e] = M[(int64_t)c * k * k + e];
     for (int e = threadIdx.x; e < k; e += 256) ts[e] = T[(int64_t)c * k + e];
     for (int e = threadIdx.x; e < RT * k; e += 256)
-        As[e] = e < rows * k ? (float)Q[i0 * k + e] * scales[e % k] : 0.0f;
+        As[e] = e < rows * k ? A[i0 * k + e] : 0.0f;
     __syncthreads();
     constexpr int RU = RT / 16;
     double acc[RU][NB];
@@ -231,13 +231,13 @@ int col_sums(const float* X, int64_t N, int m, MdsWs& w, hipStream_t st) {
 }
 
 template <int NB>
-int apply_gram_nb(const int8_t* Q, const float* scales, int64_t N, int k, int m, int squared, const float* X, float* Z,
+int apply_gram_nb(const float* A, int64_t N, int k, int m, int squared, const float* X, float* Z,
                   float* Y, MdsWs& w, hipStream_t st) {
     int rc;
     if ((rc = col_sums(X, N, m, w, st)) != RFX_OK) return rc;
     {
         const size_t lds = sizeof(float) * kRowsStage * (size_t)k + sizeof(double) * kRowsStage;
-        hipLaunchKernelGGL(mds_moments_kernel<NB>, dim3(w.blocks, m), dim3(256), lds, st, Q, scales, X, w.colsum, N, k, m,
+        hipLaunchKernelGGL(mds_moments_kernel<NB>, dim3(w.blocks, m), dim3(256), lds, st, A, X, w.colsum, N, k, m,
                            w.rows_per_block, squared, w.partialM, w.partialT);
         RFX_LAUNCH_CHECK("mds_moments_kernel");
         if (squared)
@@ -256,12 +256,12 @@ int apply_gram_nb(const int8_t* Q, const float* scales, int64_t N, int k, int m,
             auto kern = mds_quad_kernel<NB, 32>;
             if (lds > 64 * 1024)
                 RFX_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, Q, scales, w.M, w.T, N, k, m, squared, Z);
+            hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, A, w.M, w.T, N, k, m, squared, Z);
         } else {
             auto kern = mds_quad_kernel<NB, 64>;
             if (lds > 64 * 1024)
                 RFX_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, Q, scales, w.M, w.T, N, k, m, squared, Z);
+            hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, A, w.M, w.T, N, k, m, squared, Z);
         }
         RFX_LAUNCH_CHECK("mds_quad_kernel");
     }
@@ -272,31 +272,64 @@ int apply_gram_nb(const int8_t* Q, const float* scales, int64_t N, int k, int m,
 }
 
 // Y = G X for a block X [N][m]; Z is an [N][m] temporary.
-int apply_gram(const int8_t* Q, const float* scales, int64_t N, int k, int m, int squared, const float* X, float* Z,
+int apply_gram(const float* A, int64_t N, int k, int m, int squared, const float* X, float* Z,
                float* Y, MdsWs& w, hipStream_t st) {
     switch ((k + 15) / 16) {
 #define RFX_CASE(nb) \
     case nb:         \
-        return apply_gram_nb<nb>(Q, scales, N, k, m, squared, X, Z, Y, w, st);
+        return apply_gram_nb<nb>(A, N, k, m, squared, X, Z, Y, w, st);
         RFX_CASE(1) RFX_CASE(2) RFX_CASE(3) RFX_CASE(4) RFX_CASE(5) RFX_CASE(6) RFX_CASE(7) RFX_CASE(8)
 #undef RFX_CASE
     }
     return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: k=%d", k);
 }
 
+
+
+// A[e] = Q[e] * scales[e % k]
+__global__ __launch_bounds__(256) void dequantise_int8_kernel(const int8_t* __restrict__ Q, const float* __restrict__ scales,
+                                                             int64_t total, int k, float* __restrict__ A) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < total) A[e] = (float)Q[e] * scales[e % k];
+}
+
+int mds3d_core(const float* A, int64_t N, int32_t k, int dissim_mode, int32_t m, int32_t max_iters, float tol,
+               const float* x0, float* coords, float* eigvals, int32_t* iters_done, hipStream_t st);
+
 }  // namespace
 
 extern "C" int rfx_mds3d(const int8_t* Q, const float* scales, int64_t N, int32_t k, int dissim_mode, int32_t m,
                          int32_t max_iters, float tol, const float* x0, float* coords, float* eigvals,
                          int32_t* iters_done, void* stream) {
-    if (!Q || !scales || !x0 || !coords || !eigvals) return rfx::fail(RFX_ERR_NULL, "rfx_mds3d: null argument");
+    if (!Q || !scales) return rfx::fail(RFX_ERR_NULL, "rfx_mds3d: null argument");
+    if (N < 3 || k < 1 || k > rfx::kMaxRank) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: N=%lld k=%d", (long long)N, k);
+    hipStream_t st = rfx::as_stream(stream);
+    rfx::DevBuf factor;
+    RFX_HIP(factor.alloc(sizeof(float) * (size_t)N * k));
+    hipLaunchKernelGGL(dequantise_int8_kernel, dim3((unsigned)rfx::ceil_div(N * k, 256)), dim3(256), 0, st, Q, scales, N * k, k,
+                       factor.as<float>());
+    RFX_LAUNCH_CHECK("dequantise_int8_kernel");
+    return mds3d_core(factor.as<float>(), N, k, dissim_mode, m, max_iters, tol, x0, coords, eigvals, iters_done, st);
+}
+
+extern "C" int rfx_mds3d_factor(const float* A, int64_t N, int32_t k, int dissim_mode, int32_t m, int32_t max_iters,
+                                float tol, const float* x0, float* coords, float* eigvals, int32_t* iters_done,
+                                void* stream) {
+    if (!A) return rfx::fail(RFX_ERR_NULL, "rfx_mds3d_factor: null argument");
+    return mds3d_core(A, N, k, dissim_mode, m, max_iters, tol, x0, coords, eigvals, iters_done, rfx::as_stream(stream));
+}
+
+namespace {
+
+int mds3d_core(const float* A, int64_t N, int32_t k, int dissim_mode, int32_t m, int32_t max_iters, float tol,
+               const float* x0, float* coords, float* eigvals, int32_t* iters_done, hipStream_t st) {
+    if (!x0 || !coords || !eigvals) return rfx::fail(RFX_ERR_NULL, "rfx_mds3d: null argument");
     if (N < 3 || N * 32 / 256 > 0x7fffffffLL) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: N=%lld", (long long)N);
     if (k < 1 || k > rfx::kMaxRank) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: k=%d outside 1..%d", k, rfx::kMaxRank);
     if (m < 3 || m > 32 || m > N) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: m=%d outside 3..min(32, N)", m);
     if (dissim_mode != RFX_MDS_SQUARED && dissim_mode != RFX_MDS_LINEAR)
         return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: dissim_mode=%d", dissim_mode);
     if (max_iters < 1 || !(tol >= 0.0f)) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: max_iters=%d tol=%g", max_iters, tol);
-    hipStream_t st = rfx::as_stream(stream);
     const int squared = dissim_mode == RFX_MDS_SQUARED;
 
     MdsWs w;
@@ -335,7 +368,7 @@ extern "C" int rfx_mds3d(const int8_t* Q, const float* scales, int64_t N, int32_
     bool converged = false;
     while (true) {
         // Y = G X, H = sym(X^T Y) = W diag(theta) W^T (theta descending by algebraic value)
-        if ((rc = apply_gram(Q, scales, N, k, m, squared, X, Z, Y, w, st)) != RFX_OK) return rc;
+        if ((rc = apply_gram(A, N, k, m, squared, X, Z, Y, w, st)) != RFX_OK) return rc;
         ++it;
         if ((rc = rfx::gram(X, Y, N, m, true, ws, ws.G, st)) != RFX_OK) return rc;
         if ((rc = rfx::jacobi_eigh(ws.G, m, ws, ws.theta, ws.W, st)) != RFX_OK) return rc;
@@ -363,3 +396,5 @@ extern "C" int rfx_mds3d(const int8_t* Q, const float* scales, int64_t N, int32_
     if (h_flag) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: iteration block lost rank (G has rank < m=%d?)", m);
     return RFX_OK;
 }
+
+}  // namespace

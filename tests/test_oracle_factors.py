@@ -161,3 +161,71 @@ def test_mds_operator_and_invariants(cfg1, mode):
         np.testing.assert_allclose(c2, coords, atol=1e-6 * np.abs(coords).max())
     if mode == oracle.LINEAR:
         assert np.linalg.eigvalsh(G).min() > -1e-10                         # 1/2 H P^ H is PSD
+
+
+def test_nf4_levels_and_fp16_nf4_encodings():
+    lv = oracle.NF4_LEVELS
+    assert lv.shape == (16,) and lv[0] == -1.0 and lv[7] == 0.0 and lv[15] == 1.0 and (np.diff(lv) > 0).all()
+    rng = np.random.default_rng(12)
+    N, k = 301, 5                                      # odd row count: the last nibble is padding
+    V = rng.standard_normal((N, k)).astype(np.float32)
+    V[64:128, 2] = 0.0                                 # an all-zero block
+    lam = rng.uniform(0.5, 30, k).astype(np.float32)
+    A = (V * np.sqrt(lam)[None, :]).astype(np.float32)
+    # FP32 / FP16: nearest representable value
+    c32, s32 = oracle.quantise_factor(V, lam, oracle.ENC_FP32)
+    np.testing.assert_array_equal(c32, A)
+    c16, _ = oracle.quantise_factor(V, lam, oracle.ENC_FP16)
+    assert c16.dtype == np.float16
+    back = oracle.dequantise_factor(c16, None, oracle.ENC_FP16, N)
+    assert (np.abs(back - A) <= np.abs(A) * 2.0 ** -11 + 2.0 ** -25).all()      # half an ulp of binary16
+    exact = np.array([[1.0, -0.5, 1024.0, 0.0, 65504.0]], np.float32)
+    np.testing.assert_array_equal(oracle.quantise_factor(exact, np.ones(5, np.float32), oracle.ENC_FP16)[0].astype(np.float32), exact)
+    # NF4
+    codes, scales = oracle.quantise_factor(V, lam, oracle.ENC_NF4)
+    assert codes.dtype == np.uint8 and codes.shape == ((N + 1) // 2, k) and scales.shape == ((N + 63) // 64, k)
+    assert codes.nbytes == ((N + 1) // 2) * k                                      # 4 bits per code
+    assert scales[1, 2] == 1.0                                                     # zero block
+    deq = oracle.dequantise_factor(codes, scales, oracle.ENC_NF4, N)
+    assert (deq[64:128, 2] == 0).all()
+    s_full = np.repeat(scales, 64, axis=0)[:N]
+    half_gap = np.diff(lv).max() / 2
+    assert (np.abs(deq - A) <= s_full * half_gap * (1 + 1e-6)).all()
+    # nearest level, checked by brute force
+    x = A / s_full
+    nearest = np.abs(x[:, :, None].astype(np.float64) - lv[None, None, :].astype(np.float64)).argmin(axis=2)
+    unp = np.empty((2 * codes.shape[0], k), np.uint8)
+    unp[0::2], unp[1::2] = codes & 15, codes >> 4
+    assert (unp[:N] == nearest).mean() > 0.9999 and (np.abs(unp[:N].astype(int) - nearest) <= 1).all()
+    assert (unp[N:] == 7).all()
+    # the element that sets a block's scale maps to -1 or +1
+    blk = np.abs(A[:64, 0]).argmax()
+    assert unp[blk, 0] in (0, 15)
+    # storage closed forms the paper prints for two rank-32 factors at n = 100k: NF4 3.2 MB, INT8 6.4 MB
+    assert 2 * 100_000 * 32 // 2 == 3_200_000 and 2 * 100_000 * 32 == 6_400_000
+
+
+def test_mds_correlation_metric(cfg1):
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((50, 3))
+    R, _ = np.linalg.qr(rng.standard_normal((3, 3)))
+    assert oracle.mds_correlation(X, X @ R + 5.0) == pytest.approx(1.0, abs=1e-12)   # rigid motions do not matter
+    Y = rng.standard_normal((50, 3))
+    assert abs(oracle.mds_correlation(X, Y)) < 0.2
+    from scipy.spatial.distance import pdist
+    from scipy.stats import pearsonr
+    assert oracle.mds_correlation(X, Y) == pytest.approx(pearsonr(pdist(X), pdist(Y))[0], abs=1e-12)
+    assert oracle.mds_correlation(X, X + 0.3 * Y) < 1.0 - 1e-3
+    # compressed factors reproduce the full-matrix embedding of workload 1
+    leaf = cfg1["leaf"]
+    B, N = leaf.shape
+    P = oracle.counts_full(leaf).astype(np.float64) / B
+    full, _ = oracle.mds3d_from_dense_proximity(P)
+    lam, V = oracle.block_iteration(leaf, ri.start_block(N, 16), 20)
+    rho = {}
+    for name, enc in (("fp32", oracle.ENC_FP32), ("fp16", oracle.ENC_FP16), ("int8", oracle.ENC_INT8), ("nf4", oracle.ENC_NF4)):
+        codes, scales = oracle.quantise_factor(V, lam, enc)
+        emb, _ = oracle.mds3d_from_factor(oracle.dequantise_factor(codes, scales, enc, N))
+        rho[name] = oracle.mds_correlation(emb, full)
+    assert rho["fp32"] > 0.95 and rho["fp16"] > 0.95 and rho["int8"] > 0.95 and rho["nf4"] > 0.9, rho
+    assert abs(rho["fp16"] - rho["fp32"]) < 1e-3 and abs(rho["int8"] - rho["fp32"]) < 1e-2
