@@ -138,6 +138,30 @@ def pack_upper(full) -> np.ndarray:
     return np.ascontiguousarray(full[iu])
 
 
+def sparse_upper(leaf, min_count: int = 1, i0: int = 0, i1: int = None):
+    """Thresholded strict upper triangle as coordinate triplets ("CPU TriBlock Proximity": only pairs
+    i < j are kept, and only those whose proximity reaches the threshold; the threshold is given as
+    a count, p >= tau <=> cnt >= ceil(tau B), so the kept set is decided in integers).
+
+    Returns (rows, cols, counts) of all pairs i0 <= i < i1, i < j with cnt(i,j) >= min_count, ordered
+    by (i, j); counts are exact.  Computed row block by row block from the pair-by-pair counts."""
+    leaf = _c(leaf, np.uint32)
+    B, N = leaf.shape
+    i1 = N if i1 is None else i1
+    rows, cols, vals = [], [], []
+    for r0 in range(i0, i1, 256):
+        r1 = min(r0 + 256, i1)
+        cnt = counts_rows(leaf, r0, r1)
+        for i in range(r0, r1):
+            c = cnt[i - r0, i + 1:]
+            j = np.nonzero(c >= min_count)[0]
+            rows.append(np.full(j.size, i, np.int64))
+            cols.append(j + i + 1)
+            vals.append(c[j])
+    cat = lambda parts, dt: np.concatenate(parts).astype(dt) if parts else np.zeros(0, dt)
+    return cat(rows, np.int64), cat(cols, np.int64), cat(vals, np.uint32)
+
+
 # --------------------------------------------------------------------------- a5: products
 def pv_implicit(leaf, V) -> np.ndarray:
     """Y = P V = (1/B) sum_b Z_b (Z_b^T V) in float64 without forming P."""

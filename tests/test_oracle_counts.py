@@ -108,6 +108,35 @@ def test_counts_equal_sparse_one_hot_gram(small2):
     np.testing.assert_array_equal((Z @ Z.T).toarray().astype(np.uint32), oracle.counts_full(leaf))
 
 
+def test_sparse_upper_triplets(small2):
+    """Thresholded strict-upper coordinate form against the library sparse product and closed forms."""
+    leaf = small2["leaf"]
+    B, N = leaf.shape
+    nl = leaf.max(axis=1).astype(np.int64) + 1
+    col = leaf.astype(np.int64) + np.concatenate([[0], np.cumsum(nl)[:-1]])[:, None]
+    Z = sp.csr_matrix((np.ones(B * N, np.int32), (np.tile(np.arange(N), B), col.ravel())), shape=(N, int(nl.sum())))
+    U = sp.triu(Z @ Z.T, k=1).tocoo()
+    for min_count in (1, 2, 7, B):
+        r, c, v = oracle.sparse_upper(leaf, min_count)
+        keep = U.data >= min_count
+        want = sorted(zip(U.row[keep].tolist(), U.col[keep].tolist(), U.data[keep].tolist()))
+        assert list(zip(r.tolist(), c.tolist(), v.tolist())) == want
+        assert (r < c).all() and (v >= min_count).all() and (v <= B).all()
+    r, c, v = oracle.sparse_upper(leaf, 1)
+    # every co-occurring pair exactly once: 2 * sum + N B = sum over trees and leaves of (leaf size)^2
+    total = sum(int((np.bincount(leaf[b]).astype(np.int64) ** 2).sum()) for b in range(B))
+    assert 2 * int(v.astype(np.int64).sum()) + N * B == total
+    assert oracle.sparse_upper(leaf, B + 1)[0].size == 0
+    # a row range returns exactly that range's triplets
+    r2, c2, v2 = oracle.sparse_upper(leaf, 1, 100, 400)
+    sel = (r >= 100) & (r < 400)
+    np.testing.assert_array_equal(r2, r[sel]); np.testing.assert_array_equal(c2, c[sel]); np.testing.assert_array_equal(v2, v[sel])
+    # one tree: the pairs inside each leaf, all with count 1
+    r1, c1, v1 = oracle.sparse_upper(leaf[:1], 1)
+    s = np.bincount(leaf[0]).astype(np.int64)
+    assert r1.size == int((s * (s - 1) // 2).sum()) and (v1 == 1).all() and (leaf[0][r1] == leaf[0][c1]).all()
+
+
 def test_count_special_cases():
     N, B = 9, 4
     np.testing.assert_array_equal(oracle.counts_full(np.zeros((B, N), np.uint32)), np.full((N, N), B))
