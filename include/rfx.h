@@ -41,6 +41,7 @@ extern "C" {
 #define RFX_ERR_HIP (-5)         /* a HIP runtime call failed (message has the HIP error) */
 #define RFX_ERR_UNSUPPORTED (-6) /* valid request outside what this build implements */
 #define RFX_ERR_FOREST (-7)      /* the forest description is malformed */
+#define RFX_ERR_CAPACITY (-8)    /* an output of caller-chosen capacity is too small (the needed size is reported) */
 
 /* count_dtype */
 #define RFX_U16 0
@@ -132,6 +133,25 @@ int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_boun
  * B <= 65535 (numerator and denominator share one 32-bit counter), else RFX_ERR_UNSUPPORTED. */
 int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
                  int count_dtype, int layout, void* num, void* den, float* prox, void* stream);
+
+/* Thresholded sparse proximity ("CPU TriBlock Proximity": only pairs i < j are kept, and only
+ * those whose proximity reaches a threshold; values below it are implicit zeros).  The threshold is
+ * given as a count, p >= tau <=> cnt >= min_count = ceil(tau B); min_count = 1 keeps every non-zero
+ * pair, so the list is then an exact representation of the matrix.
+ *   leaf, leaf_bound, count_dtype  as rfx_prox_dense
+ *   min_count  >= 1
+ *   capacity   entries the output arrays can hold; 0 = only count the qualifying pairs
+ *   rows, cols [device] uint32 [capacity]: i and j of each kept pair, i < j
+ *   counts     [device] nullable, [capacity] of count_dtype: cnt(i,j), exact
+ *   prox       [device] nullable float32 [capacity]: cnt / B in IEEE float32 division
+ *   nnz        [host] out: number of qualifying pairs, also when it exceeds the capacity
+ * The order of the entries is unspecified (it varies from call to call); every qualifying pair
+ * appears exactly once.  Synchronous.  B < 2^20, else RFX_ERR_UNSUPPORTED.  When nnz > capacity > 0
+ * the call returns RFX_ERR_CAPACITY and the arrays hold an unspecified subset.
+ * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_OVERFLOW, RFX_ERR_OOM, RFX_ERR_CAPACITY. */
+int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count, int count_dtype,
+                    int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox, int64_t* nnz,
+                    void* stream);
 
 /* Implicit product Y = P V = (1/B) sum_b Z_b (Z_b^T V), Z_b the N x L_b one-hot leaf
  * membership of tree b, i.e. Y[i,:] = (1/B) sum_b sum_{j : leaf_b(j) = leaf_b(i)} V[j,:];

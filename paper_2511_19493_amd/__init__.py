@@ -18,13 +18,14 @@ _LIB_PATH = Path(__file__).resolve().parent / "lib" / "librfx.so"
 _lib = None
 
 U16, U32 = 0, 1
+ERR_INVALID_ARG, ERR_NULL, ERR_OVERFLOW, ERR_OOM, ERR_HIP, ERR_UNSUPPORTED, ERR_FOREST, ERR_CAPACITY = -1, -2, -3, -4, -5, -6, -7, -8
 FULL, UPPER_PACKED = 0, 1
 MDS_SQUARED, MDS_LINEAR = 0, 1
 ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
 
 EXPORTS = (
     "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
-    "rfx_prox_dense", "rfx_prox_oob", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
+    "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_sparse", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
 )
@@ -64,6 +65,7 @@ def load():
             "rfx_leaf_assign": [vp, vp, i64, i32, vp, vp],
             "rfx_prox_dense": [vp, i64, i32, i32, ci, ci, vp, vp, vp],
             "rfx_prox_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp],
+            "rfx_prox_sparse": [vp, i64, i32, i32, i32, ci, i64, vp, vp, vp, vp, ctypes.POINTER(i64), vp],
             "rfx_pv_plan_create": [vp, i64, i32, i32, ctypes.POINTER(vp), vp],
             "rfx_pv_plan_destroy": [vp],
             "rfx_pv_apply": [vp, vp, i32, vp, vp],
@@ -198,6 +200,38 @@ def prox_oob(leaf, inbag, leaf_bound: int, count_dtype: int = U32, layout: int =
                                count_dtype, layout, num.data_ptr(), den.data_ptr(),
                                prox.data_ptr() if prox is not None else 0, _stream()))
     return num, den, prox
+
+
+def prox_sparse_count(leaf, leaf_bound: int, min_count: int = 1) -> int:
+    """rfx_prox_sparse with capacity 0: the number of pairs i < j with cnt(i,j) >= min_count."""
+    import torch
+    B, N = leaf.shape
+    nnz = ctypes.c_int64(0)
+    _check(load().rfx_prox_sparse(_dev(leaf, torch.int32), N, B, leaf_bound, min_count, U32, 0, 0, 0, 0, 0,
+                                  ctypes.byref(nnz), _stream()))
+    return nnz.value
+
+
+def prox_sparse(leaf, leaf_bound: int, min_count: int = 1, capacity: int = None, count_dtype: int = U32,
+                want_counts: bool = True, want_prox: bool = False):
+    """rfx_prox_sparse: returns (rows, cols, counts, prox), each trimmed to the number of kept pairs.
+
+    `capacity` None runs the counting call first and allocates exactly; a given capacity that is too
+    small raises RfxError with code ERR_CAPACITY."""
+    import torch
+    B, N = leaf.shape
+    if capacity is None:
+        capacity = max(prox_sparse_count(leaf, leaf_bound, min_count), 1)
+    rows = torch.empty(capacity, dtype=torch.int32, device=leaf.device)
+    cols = torch.empty(capacity, dtype=torch.int32, device=leaf.device)
+    counts = torch.empty(capacity, dtype=_count_dtype(count_dtype), device=leaf.device) if want_counts else None
+    prox = torch.empty(capacity, dtype=torch.float32, device=leaf.device) if want_prox else None
+    nnz = ctypes.c_int64(0)
+    _check(load().rfx_prox_sparse(_dev(leaf, torch.int32), N, B, leaf_bound, min_count, count_dtype, capacity,
+                                  rows.data_ptr(), cols.data_ptr(), counts.data_ptr() if counts is not None else 0,
+                                  prox.data_ptr() if prox is not None else 0, ctypes.byref(nnz), _stream()))
+    n = nnz.value
+    return rows[:n], cols[:n], counts[:n] if counts is not None else None, prox[:n] if prox is not None else None
 
 
 class PvPlan:

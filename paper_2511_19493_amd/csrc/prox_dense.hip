@@ -16,6 +16,10 @@
 // counters live in vector registers for the whole tree loop and are written once.  Four waves
 // of a workgroup share the a samples (L1 hits) and take consecutive b ranges.  Only tile pairs
 // on or below the diagonal are launched.
+//
+// The same tile loop also feeds a thresholded sparse output (paper, "CPU TriBlock Proximity":
+// strict upper triangle, only values that reach a threshold): instead of writing its tile, a wave
+// compacts the pairs whose count reaches min_count and appends them to a coordinate list.
 #include <algorithm>
 
 #include "common.h"
@@ -71,6 +75,12 @@ struct TileOut {
     int32_t u16;     // counts / num / den are uint16
     int32_t packed;  // strict-upper packed layout
     int32_t use_tab; // quotient table in LDS (set by the launcher)
+    // sparse output: coordinate triplets appended at *sp_cursor; counts / prox are indexed by entry
+    uint32_t* sp_rows;
+    uint32_t* sp_cols;
+    unsigned long long* sp_cursor;
+    unsigned long long sp_capacity;
+    uint32_t sp_min_count;
 };
 
 __device__ __forceinline__ int64_t packed_index(int64_t i, int64_t j, int64_t N) {
@@ -313,16 +323,86 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
     }
 }
 
+// Sparse epilogue.  Keeps the pairs (i = b, j = a) of this wave's tile with i < j < N whose count
+// reaches sp_min_count and appends (i, j, count[, count / B]) to the coordinate list.  One 64-bit
+// atomic per wave reserves the run; the kept pairs are then compacted through the wave's LDS
+// buffer, 4 b samples at a time (at most 1024 pairs, one word each: count << 12 | j_local << 8 |
+// a_local), and copied out with contiguous stores.  A run that would pass the capacity is counted
+// but not stored.
+template <int J>
+__device__ __forceinline__ void emit_tile(const TileOut& out, uint32_t* tr, int lane, int64_t a_tile, int64_t b0,
+                                          const uint32_t (&acc)[kR][J]) {
+    static_assert(kR == 4 && J == 16, "one keep bit per pair held by a lane; 8-bit a_local, 4-bit j_local");
+    const int64_t N = out.N;
+    const int64_t a0 = a_tile + kR * lane;
+    uint64_t keep = 0;  // bit 4*j + r
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            const uint32_t c = (uint32_t)out.B - acc[r][j];
+            const bool k = a0 + r < N && b0 + j < a0 + r && c >= out.sp_min_count;
+            keep |= (uint64_t)(k ? 1u : 0u) << (4 * j + r);
+        }
+    auto wave_scan = [&](uint32_t n, uint32_t& excl, uint32_t& total) {
+        uint32_t incl = n;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t t = __shfl_up(incl, off);
+            if (lane >= off) incl += t;
+        }
+        excl = incl - n;
+        total = __shfl(incl, 63);
+    };
+    uint32_t excl, total;
+    wave_scan((uint32_t)__builtin_popcountll(keep), excl, total);
+    if (total == 0) return;
+    unsigned long long base = 0;
+    if (lane == 0) base = atomicAdd(out.sp_cursor, (unsigned long long)total);
+    base = ((unsigned long long)(uint32_t)__shfl((int)(base >> 32), 0) << 32) | (uint32_t)__shfl((int)(uint32_t)base, 0);
+    if (base + total > out.sp_capacity) return;
+    const float Bf = (float)out.B;
+#pragma unroll
+    for (int q = 0; q < J / 4; ++q) {
+        const uint32_t kq = (uint32_t)(keep >> (16 * q)) & 0xffffu;
+        uint32_t exq, totq;
+        wave_scan((uint32_t)__builtin_popcount(kq), exq, totq);
+        __builtin_amdgcn_wave_barrier();
+        uint32_t pos = exq;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+            for (int r = 0; r < kR; ++r)
+                if ((kq >> (4 * jj + r)) & 1u) {
+                    const uint32_t c = (uint32_t)out.B - acc[r][4 * q + jj];
+                    tr[pos++] = (c << 12) | (uint32_t)((4 * q + jj) << 8) | (uint32_t)(kR * lane + r);
+                }
+        __builtin_amdgcn_wave_barrier();
+        for (uint32_t t = lane; t < totq; t += 64) {
+            const uint32_t w = tr[t];
+            const unsigned long long e = base + t;
+            const uint32_t c = w >> 12;
+            stream_store(out.sp_rows + e, (uint32_t)(b0 + ((w >> 8) & 15u)));
+            stream_store(out.sp_cols + e, (uint32_t)(a_tile + (w & 255u)));
+            if (out.counts) store_count(out.counts, out.u16, (int64_t)e, c);
+            if (out.prox) stream_store(out.prox + e, (float)c / Bf);
+        }
+        base += totq;
+    }
+}
+
 #ifndef RFX_PLAIN_WAVES
 #define RFX_PLAIN_WAVES 4
 #endif
 // waves per SIMD the register allocation aims for: the plain kernel's main loop fits 128 VGPRs
 #define RFX_MIN_WAVES(oob) RFX_PLAIN_WAVES
 
-// P = number of leaf-id bit planes, J = b samples per wave, kOob = out-of-bag variant.
-template <int P, int J, bool kOob>
-__global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kOob)) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
+// P = number of leaf-id bit planes, J = b samples per wave, kMode = what is counted and how it leaves.
+enum { kModePlain = 0, kModeOob = 1, kModeSparse = 2 };
+template <int P, int J, int kMode>
+__global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kMode == kModeOob)) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
                                                                  int32_t G, int32_t n_tile_rows, TileOut out) {
+    constexpr bool kOob = kMode == kModeOob;
     constexpr int PS = plane_stride(P);
     constexpr int PL = kOob ? P + 1 : P;     // words of a sample actually used
     constexpr int PV = (PL + 3) / 4;         // 16-byte loads per a sample
@@ -405,13 +485,15 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kOob)) void prox_tile_ke
         }
     }
 
-    if (out.use_tab)
+    if (kMode == kModeSparse)
+        emit_tile<J>(out, tr, lane, ta * kATile, b0, acc);
+    else if (out.use_tab)
         write_tile<J, kOob, true>(out, tab, tr, lane, ta * kATile, b0, acc);
     else
         write_tile<J, kOob, false>(out, tab, tr, lane, ta * kATile, b0, acc);
 }
 
-template <int P, int J, bool kOob>
+template <int P, int J, int kMode>
 int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, hipStream_t st) {
     constexpr int kRatio = kATile / (J * kWaves);
     const int64_t rows = Npad / kATile;
@@ -423,18 +505,19 @@ int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut&
     }
     const int64_t blocks = 8 * longest;
     if (blocks > 0x7fffffffLL) return rfx::fail(RFX_ERR_INVALID_ARG, "proximity: N too large for one launch");
+    constexpr bool kOob = kMode == kModeOob;
     TileOut o = out;
-    o.use_tab = (!kOob && out.prox && out.B < 8192) ? 1 : 0;
+    o.use_tab = (kMode == kModePlain && out.prox && out.B < 8192) ? 1 : 0;
     const size_t lds = sizeof(uint32_t) * kWaves * 64 * (J + 4) +
                        (o.use_tab ? sizeof(float) * (size_t)(out.B + 1) : 0);
-    rfx::TimedLaunch timed(kOob ? "prox_tile_kernel_oob" : "prox_tile_kernel", st);
-    hipLaunchKernelGGL((prox_tile_kernel<P, J, kOob>), dim3((unsigned)blocks), dim3(64 * kWaves), lds, st, planes, Npad, G,
+    rfx::TimedLaunch timed(kOob ? "prox_tile_kernel_oob" : (kMode == kModeSparse ? "prox_tile_kernel_sparse" : "prox_tile_kernel"), st);
+    hipLaunchKernelGGL((prox_tile_kernel<P, J, kMode>), dim3((unsigned)blocks), dim3(64 * kWaves), lds, st, planes, Npad, G,
                        (int32_t)rows, o);
     RFX_LAUNCH_CHECK("prox_tile_kernel");
     return RFX_OK;
 }
 
-template <bool kOob>
+template <int kMode>
 int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, hipStream_t st) {
 #ifndef RFX_J_PLAIN
 #define RFX_J_PLAIN 16
@@ -443,7 +526,7 @@ int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, cons
     switch (P) {
 #define RFX_CASE(p) \
     case p:         \
-        return launch_tiles<p, J, kOob>(planes, Npad, G, out, st);
+        return launch_tiles<p, J, kMode>(planes, Npad, G, out, st);
 #ifdef RFX_ONLY_P  // development builds: a single plane count compiles in seconds
         RFX_CASE(RFX_ONLY_P)
 #else
@@ -480,7 +563,7 @@ int planes_for(int32_t leaf_bound) {
     return P <= 16 ? P : (P + 1) & ~1;
 }
 
-template <bool kOob>
+template <int kMode>
 int run(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound, const TileOut& out,
         hipStream_t st) {
     const int P = planes_for(leaf_bound);
@@ -492,7 +575,7 @@ int run(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32
     hipLaunchKernelGGL(pack_planes_kernel, dim3((unsigned)rfx::ceil_div(Npad, 256), (unsigned)G), dim3(256), 0, st, leaf,
                        inbag, N, B, Npad, P, PS, planes.as<uint32_t>());
     RFX_LAUNCH_CHECK("pack_planes_kernel");
-    int rc = dispatch_planes<kOob>(P, planes.as<uint32_t>(), Npad, G, out, st);
+    int rc = dispatch_planes<kMode>(P, planes.as<uint32_t>(), Npad, G, out, st);
     // the scratch is freed on return, so wait for the kernels that read it
     hipError_t e = hipStreamSynchronize(st);
     if (rc != RFX_OK) return rc;
@@ -509,8 +592,8 @@ int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_boun
     int rc = check_common("rfx_prox_dense", leaf, N, B, leaf_bound, count_dtype, layout);
     if (rc != RFX_OK) return rc;
     if (!counts && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_dense: neither counts nor prox given");
-    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0};
-    return run<false>(leaf, nullptr, N, B, leaf_bound, out, rfx::as_stream(stream));
+    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0};
+    return run<kModePlain>(leaf, nullptr, N, B, leaf_bound, out, rfx::as_stream(stream));
 }
 
 int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
@@ -520,8 +603,35 @@ int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t
     if (!inbag) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: inbag is null");
     if (B > 65535) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_oob: more than 65535 trees");
     if (!num && !den && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: no output given");
-    TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0};
-    return run<true>(leaf, inbag, N, B, leaf_bound, out, rfx::as_stream(stream));
+    TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0};
+    return run<kModeOob>(leaf, inbag, N, B, leaf_bound, out, rfx::as_stream(stream));
+}
+
+int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count, int count_dtype,
+                    int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox, int64_t* nnz,
+                    void* stream) {
+    int rc = check_common("rfx_prox_sparse", leaf, N, B, leaf_bound, count_dtype, RFX_UPPER_PACKED);
+    if (rc != RFX_OK) return rc;
+    if (!nnz) return rfx::fail(RFX_ERR_NULL, "rfx_prox_sparse: nnz is null");
+    if (min_count < 1) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_sparse: min_count=%d below 1", min_count);
+    if (capacity < 0) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_sparse: capacity=%lld", (long long)capacity);
+    if (capacity > 0 && (!rows || !cols)) return rfx::fail(RFX_ERR_NULL, "rfx_prox_sparse: rows / cols are null");
+    if (B >= (1 << 20)) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_sparse: 2^20 trees or more");
+    hipStream_t st = rfx::as_stream(stream);
+    rfx::DevBuf cursor;
+    RFX_HIP(cursor.alloc(sizeof(unsigned long long)));
+    RFX_HIP(hipMemsetAsync(cursor.p, 0, sizeof(unsigned long long), st));
+    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, 1, 0, rows, cols, cursor.as<unsigned long long>(),
+                (unsigned long long)capacity, (uint32_t)min_count};
+    rc = run<kModeSparse>(leaf, nullptr, N, B, leaf_bound, out, st);
+    if (rc != RFX_OK) return rc;
+    unsigned long long total = 0;
+    RFX_HIP(hipMemcpy(&total, cursor.p, sizeof(total), hipMemcpyDeviceToHost));
+    *nnz = (int64_t)total;
+    if (total > (unsigned long long)capacity && capacity > 0)
+        return rfx::fail(RFX_ERR_CAPACITY, "rfx_prox_sparse: %llu pairs reach the threshold, capacity is %lld", total,
+                         (long long)capacity);
+    return RFX_OK;
 }
 
 }  // extern "C"

@@ -40,6 +40,11 @@ def test_host_side_argument_checks():
     assert lib.rfx_prox_dense(fake, 10, 4, 8, rfx.U32, rfx.FULL, None, None, None) == -2
     assert lib.rfx_prox_oob(fake, None, 10, 4, 8, rfx.U32, rfx.FULL, fake, fake, None, None) == -2
     assert lib.rfx_pv_apply(None, fake, 4, fake, None) == -2
+    nnz = ctypes.c_int64(0)
+    assert lib.rfx_prox_sparse(fake, 10, 4, 8, 0, rfx.U32, 0, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_prox_sparse(fake, 10, 4, 8, 1, rfx.U32, 5, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_NULL
+    assert lib.rfx_prox_sparse(fake, 10, 4, 8, 1, rfx.U32, 0, None, None, None, None, None, None) == rfx.ERR_NULL
+    assert lib.rfx_prox_sparse(fake, 10, 1 << 20, 8, 1, rfx.U32, 0, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_UNSUPPORTED
     assert lib.rfx_prox_lowrank(fake, 10, 4, 8, 300, 5, fake, fake, fake, None, None, None) == -1
     assert lib.rfx_prox_lowrank(fake, 10, 4, 8, 4, 0, fake, fake, fake, None, None, None) == -1
     assert lib.rfx_forest_create(None, None) == -2

@@ -1,0 +1,103 @@
+"""GPU parity for the thresholded sparse proximity (strict upper triangle as coordinate triplets).
+The order of the triplets is unspecified, so both sides are compared as sorted lists."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def _dev(torch, leaf):
+    return torch.from_numpy(np.ascontiguousarray(leaf).view(np.int32)).cuda()
+
+
+def _sorted_triplets(rows, cols, counts, prox=None):
+    r = rows.cpu().numpy().astype(np.int64)
+    c = cols.cpu().numpy().astype(np.int64)
+    v = counts.cpu().numpy()
+    v = v.view(np.uint16) if v.dtype == np.int16 else v.view(np.uint32)
+    order = np.lexsort((c, r))
+    p = prox.cpu().numpy()[order] if prox is not None else None
+    return r[order], c[order], v[order].astype(np.uint32), p
+
+
+def _compare(torch, rfx, oracle, leaf, bound, min_count, dtype):
+    B, N = leaf.shape
+    rr, rc, rv = oracle.sparse_upper(leaf, min_count)
+    assert rfx.prox_sparse_count(_dev(torch, leaf), bound, min_count) == rr.size
+    rows, cols, counts, prox = rfx.prox_sparse(_dev(torch, leaf), bound, min_count, count_dtype=dtype, want_prox=True)
+    r, c, v, p = _sorted_triplets(rows, cols, counts, prox)
+    np.testing.assert_array_equal(r, rr)
+    np.testing.assert_array_equal(c, rc)
+    np.testing.assert_array_equal(v, rv)
+    np.testing.assert_array_equal(p, (rv.astype(np.float32) / np.float32(B)).astype(np.float32))
+
+
+@pytest.mark.parametrize("N,B,bound", [(1, 3, 5), (2, 1, 2), (255, 31, 40), (256, 32, 40), (257, 33, 40), (515, 65, 2),
+                                       (300, 97, 1), (1100, 40, 3000)])
+def test_sparse_on_boundary_shapes(torch_cuda, N, B, bound):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    print(f"sparse boundary shapes N={N} B={B} bound={bound}", flush=True)
+    rng = np.random.default_rng(7000 * N + B)
+    leaf = rng.integers(0, bound, size=(B, N)).astype(np.uint32)
+    for min_count in sorted({1, 2, max(1, B // 4), B}):
+        _compare(torch_cuda, rfx, oracle, leaf, bound, min_count, rfx.U32)
+    if B <= 65535:
+        _compare(torch_cuda, rfx, oracle, leaf, bound, 1, rfx.U16)
+
+
+def test_sparse_on_grown_forests(torch_cuda, cfg1, small2):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    for name, w in (("cfg1", cfg1), ("small2", small2)):
+        leaf = w["leaf"]
+        B, N = leaf.shape
+        bound = int(leaf.max()) + 1
+        print(f"sparse {name} N={N} B={B}", flush=True)
+        for min_count in (1, 3, B // 2):
+            _compare(torch_cuda, rfx, oracle, leaf, bound, min_count, rfx.U16)
+        # the list with min_count 1 is an exact representation: it rebuilds the dense counts
+        rows, cols, counts, _ = rfx.prox_sparse(_dev(torch_cuda, leaf), bound, 1)
+        dense = np.zeros((N, N), np.uint32)
+        r, c, v, _ = _sorted_triplets(rows, cols, counts)
+        dense[r, c] = v
+        dense = dense + dense.T
+        np.fill_diagonal(dense, B)
+        np.testing.assert_array_equal(dense, oracle.counts_full(leaf))
+
+
+def test_sparse_capacity_and_argument_errors(torch_cuda, cfg1):
+    import oracle
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    leaf = cfg1["leaf"]
+    B, N = leaf.shape
+    bound = int(leaf.max()) + 1
+    d = _dev(torch, leaf)
+    need = oracle.sparse_upper(leaf, 1)[0].size
+    assert need > 10
+    with pytest.raises(rfx.RfxError) as e:
+        rfx.prox_sparse(d, bound, 1, capacity=need - 1)
+    assert e.value.code == rfx.ERR_CAPACITY and str(need) in str(e.value)
+    rows, cols, counts, _ = rfx.prox_sparse(d, bound, 1, capacity=need)         # exactly enough
+    assert rows.numel() == need
+    rows, cols, counts, _ = rfx.prox_sparse(d, bound, 1, capacity=need + 1000)  # more than enough: trimmed
+    assert rows.numel() == need
+    with pytest.raises(rfx.RfxError) as e:
+        rfx.prox_sparse(d, bound, 0)
+    assert e.value.code == rfx.ERR_INVALID_ARG
+    # nothing qualifies: empty list, no error
+    rows, cols, counts, _ = rfx.prox_sparse(d, bound, B + 1, capacity=16)
+    assert rows.numel() == 0
+    # two calls in a row give the same set (the order may differ)
+    a = _sorted_triplets(*rfx.prox_sparse(d, bound, 2)[:3])
+    b = _sorted_triplets(*rfx.prox_sparse(d, bound, 2)[:3])
+    for x, y in zip(a[:3], b[:3]):
+        np.testing.assert_array_equal(x, y)
