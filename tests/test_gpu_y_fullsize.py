@@ -151,6 +151,44 @@ def _check_oob(d, n_rows):
     say(f"out-of-bag packed proximity: {len(rows)} sampled rows bit-exact")
 
 
+def _check_sparse(d, n_rows, budget_bytes=40e9):
+    """Thresholded sparse proximity at full size: sampled rows and columns against the oracle, and
+    for min_count = 1 the exact identity 2 * sum(counts) + N B = sum over trees and leaves of size^2."""
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    B, N = d["ref_leaf"].shape
+    min_count = 1
+    while True:
+        t0 = time.time()
+        nnz = rfx.prox_sparse_count(d["leaf"], d["Lb"], min_count)
+        say(f"sparse: {nnz} pairs with count >= {min_count} ({nnz / (N * (N - 1) / 2):.2%} of the triangle), counted in {time.time() - t0:.3f}s")
+        if nnz * 12 <= budget_bytes:
+            break
+        min_count += 1
+    t0 = time.time()
+    rows, cols, counts, _ = rfx.prox_sparse(d["leaf"], d["Lb"], min_count, capacity=max(nnz, 1), count_dtype=rfx.U32)
+    torch.cuda.synchronize()
+    say(f"sparse: list of {rows.numel()} triplets written in {time.time() - t0:.3f}s")
+    assert rows.numel() == nnz
+    assert bool((rows < cols).all()) and bool((rows >= 0).all()) and int(cols.max()) < N and int(counts.min()) >= min_count
+    if min_count == 1:
+        expect = sum(int((np.bincount(d["ref_leaf"][b]).astype(np.int64) ** 2).sum()) for b in range(B))
+        assert 2 * int(counts.sum(dtype=torch.int64)) + N * B == expect
+        say("sparse: sum identity holds exactly")
+    for i in _sample_rows(N, n_rows, 14):
+        ref = oracle.counts_rows(d["ref_leaf"], i, i + 1)[0]
+        for own, other, lo, hi in ((rows, cols, i + 1, N), (cols, rows, 0, i)):
+            m = own == i
+            j = other[m].cpu().numpy().astype(np.int64)
+            v = counts[m].cpu().numpy().view(np.uint32)
+            order = np.argsort(j)
+            want_j = np.nonzero(ref[lo:hi] >= min_count)[0] + lo
+            np.testing.assert_array_equal(j[order], want_j, err_msg=f"sample {i}")
+            np.testing.assert_array_equal(v[order], ref[want_j], err_msg=f"sample {i}")
+    say(f"sparse: {n_rows}+ sampled rows and columns exact")
+
+
 def _check_matvec(d, k, n_rows, prox=None):
     import torch
     import oracle
@@ -259,6 +297,7 @@ def test_cfg3_dense_and_rank32(w3):
     prox = _check_dense(w3, 24)
     _check_matvec(w3, 32, 24, prox)
     del prox
+    _check_sparse(w3, 16)
     _check_oob(w3, 12)
     _check_lowrank_and_mds(w3, 32, 20)
 
@@ -269,6 +308,7 @@ def test_cfg4_leaf_and_dense(w4):
     prox = _check_dense(w4, 24)
     _check_matvec(w4, 64, 16, prox)
     del prox
+    _check_sparse(w4, 12)
     _check_oob(w4, 12)
 
 
@@ -281,4 +321,5 @@ def test_cfg5_rows_with_reduced_trees(w5_reduced):
     _check_leaf(w5_reduced)
     say("cfg5 (32 trees) leaf ids bit-exact")
     _check_matvec(w5_reduced, 64, 8)
+    _check_sparse(w5_reduced, 8)
     _check_lowrank_and_mds(w5_reduced, 64, 20, mds_reference="residual")
