@@ -12,6 +12,7 @@ roofline of the dominant kernel and the CPU oracle timed on a bounded sample of 
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -123,7 +124,20 @@ def main():
     for name in ("leaf_assign_kernel", "prox_tile_kernel", "prox_tile_kernel_oob", "pv_leaf_sum_kernel", "pv_gather_kernel"):
         ms, n = rfx.timing_get(name)
         kern[name] = {"avg_ms": ms / max(n, 1), "launches": n}
+    # outside the timed step: the thresholded sparse form of the same counts (every non-zero pair)
+    nnz = rfx.prox_sparse_count(leaf, Lb, 1)
+    sp_rows = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+    sp_cols = torch.empty_like(sp_rows)
+    sp_cnt = torch.empty(max(nnz, 1), dtype=torch.int16, device=dev)
+    got = ctypes.c_int64(0)
+    rfx.timing_enable(True)
+    for _ in range(2):
+        rfx._check(lib.rfx_prox_sparse(leaf.data_ptr(), N, B, Lb, 1, rfx.U16, max(nnz, 1), sp_rows.data_ptr(),
+                                       sp_cols.data_ptr(), sp_cnt.data_ptr(), 0, ctypes.byref(got), st))
+    sp_ms, sp_n = rfx.timing_get("prox_tile_kernel_sparse")
+    sp_ms /= max(sp_n, 1)
     rfx.timing_enable(False)
+    del sp_rows, sp_cols, sp_cnt
 
     tests = N * N * B / 2.0
     P = int(np.ceil(np.log2(max(Lb, 2))))
@@ -135,7 +149,7 @@ def main():
     achieved = ops_per_launch / (tile_ms * 1e-3) if tile_ms > 0 else 0.0
     # HBM-side bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, calibrated on a 4 GiB copy); measured for workload 4 only
-    traffic = (39088853.4 * 2.0 + 42333071.5) * 1024.0 if (c.cfg == 4 and not reduced) else None
+    traffic = (39087769.4 * 2.0 + 42359959.7) * 1024.0 if (c.cfg == 4 and not reduced) else None
     roofline = {"kernel": "prox_tile_kernel", "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_VALU_LANE_OPS / 1e12,
                 "unit": "T lane-ops/s", "frac": achieved / PEAK_VALU_LANE_OPS, "traffic": traffic,
                 "traffic_source": "profiles/bench_cfg4_pmc_fetch_write.txt (L2-to-fabric bytes; output is 4*N*N)",
@@ -185,6 +199,11 @@ def main():
         "leaf_assign": la,
         "kernels": kern,
         "roofline": roofline,
+        "sparse": {"note": "not part of the step: strict-upper (i, j, count) triplets of every non-zero pair",
+                   "min_count": 1, "pairs": nnz, "fraction_of_triangle": nnz / max(N * (N - 1) / 2.0, 1.0),
+                   "bytes_out": 10 * nnz, "avg_launch_ms": sp_ms,
+                   "tests_per_s": tests / (sp_ms * 1e-3) if sp_ms > 0 else 0.0,
+                   "frac_of_alu_peak": (tests * (P + 1) / 32.0 / (sp_ms * 1e-3)) / PEAK_VALU_LANE_OPS if sp_ms > 0 else 0.0},
     }
 
     if not args.no_cpu_baseline:
