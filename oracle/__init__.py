@@ -162,6 +162,69 @@ def sparse_upper(leaf, min_count: int = 1, i0: int = 0, i1: int = None):
     return cat(rows, np.int64), cat(cols, np.int64), cat(vals, np.uint32)
 
 
+# --------------------------------------------------------------------------- proximity consumers
+def outlier_printed(cnt, B: int, rows=None) -> np.ndarray:
+    """Case-wise outlier measure as the paper prints it ("Case-wise Proximity"):
+    (1/(n-1)) sum_{j != i} 1 / p(i,j)^2, p = cnt / B in float64.  The term of a pair with p = 0 is
+    undefined; such pairs are skipped (they are the implicit zeros of the paper's sparse storage).
+    `cnt` holds the count rows of the samples `rows` (all samples, in order, when None)."""
+    cnt = np.asarray(cnt)
+    n = cnt.shape[1]
+    rows = range(cnt.shape[0]) if rows is None else rows
+    out = np.zeros(len(rows), np.float64)
+    for r, i in enumerate(rows):
+        for j in range(n):
+            if j != i and cnt[r, j] > 0:
+                p = float(cnt[r, j]) / float(B)
+                out[r] += 1.0 / (p * p)
+        out[r] /= (n - 1)
+    return out
+
+
+def outlier_classic(cnt, B: int, labels=None, rows=None) -> np.ndarray:
+    """Breiman and Cutler's raw outlier measure, which the paper's section builds on: n divided by the
+    sum of squared proximities to the other samples of the same class (all other samples when no
+    labels are given).  A sample with no proximity to any of them gets +inf.  `cnt`, `rows` as in
+    outlier_printed."""
+    cnt = np.asarray(cnt)
+    n = cnt.shape[1]
+    rows = range(cnt.shape[0]) if rows is None else rows
+    out = np.empty(len(rows), np.float64)
+    for r, i in enumerate(rows):
+        s = 0.0
+        for j in range(n):
+            if j != i and (labels is None or labels[j] == labels[i]):
+                p = float(cnt[r, j]) / float(B)
+                s += p * p
+        out[r] = float(n) / s if s > 0 else np.inf
+    return out
+
+
+def oob_vote(leaf, inbag, leaf_class, n_classes: int):
+    """Out-of-bag votes and prediction ("OOB Error Estimation"): for sample i only the trees whose
+    bootstrap sample missed i vote, each with the class of the leaf i falls in; the prediction is the
+    class with most votes (lowest class on ties), -1 for a sample that was never out-of-bag.
+    Returns (votes uint32 [N][C], pred int32 [N])."""
+    leaf = np.asarray(leaf)
+    B, N = leaf.shape
+    votes = np.zeros((N, n_classes), np.uint32)
+    for b in range(B):
+        for i in range(N):
+            if inbag[b, i] == 0:
+                votes[i, leaf_class[b, leaf[b, i]]] += 1
+    pred = np.where(votes.sum(axis=1) > 0, votes.argmax(axis=1), -1).astype(np.int32)
+    return votes, pred
+
+
+def oob_error(pred, y):
+    """(wrong, voted): samples whose out-of-bag prediction differs from the label, and samples that
+    have a prediction; the error rate is wrong / voted (= the paper's (1/n) sum when every sample
+    was out-of-bag at least once)."""
+    pred = np.asarray(pred)
+    voted = pred >= 0
+    return int((pred[voted] != np.asarray(y)[voted]).sum()), int(voted.sum())
+
+
 # --------------------------------------------------------------------------- a5: products
 def pv_implicit(leaf, V) -> np.ndarray:
     """Y = P V = (1/B) sum_b Z_b (Z_b^T V) in float64 without forming P."""

@@ -1,7 +1,7 @@
 """Seeded synthetic inputs shared by the CPU oracle, the tests and the benchmark.
 
 This package generates inputs only: Gaussian-mixture sample matrices, grown
-forests (flattened trees plus bootstrap in-bag counts) and random start blocks.
+forests (flattened trees plus bootstrap in-bag counts and leaf class labels) and random start blocks.
 It contains none of the proximity path's arithmetic.
 
 The five workloads follow the shapes of the paper's evaluation: its only
@@ -11,7 +11,7 @@ measured data set is 178 rows x 13 features in 3 classes (Results,
 Gaussian mixtures of the same shapes stand in for them.
 """
 from .mixture import CONFIGS, WorkloadConfig, gaussian_mixture, start_block, workload
-from .forest import Forest, build_grower, grow_forest, load_or_grow
+from .forest import Forest, build_grower, grow_forest, leaf_classes, load_or_grow
 
 __all__ = [
     "CONFIGS",
@@ -22,5 +22,6 @@ __all__ = [
     "Forest",
     "build_grower",
     "grow_forest",
+    "leaf_classes",
     "load_or_grow",
 ]

@@ -97,6 +97,20 @@ def grow_forest(X: np.ndarray, y: np.ndarray, n_classes: int, n_trees: int, mtry
     return Forest(n_trees, M, off, feat, thr, left, right, leaf, depth, nl, inbag, tl)
 
 
+def leaf_classes(forest: Forest, y: np.ndarray, n_classes: int) -> np.ndarray:
+    """Class label of every leaf: the class with the largest in-bag weight among the training rows that
+    ended in it (lowest class on ties).  int32 [B][max leaves per tree], -1 past a tree's last leaf."""
+    y = np.asarray(y, np.int64)
+    out = np.full((forest.n_trees, int(forest.n_leaves.max())), -1, np.int32)
+    for b in range(forest.n_trees):
+        tl = forest.train_leaf[b]
+        rows = np.nonzero(tl >= 0)[0]
+        table = np.zeros((int(forest.n_leaves[b]), n_classes), np.int64)
+        np.add.at(table, (tl[rows], y[rows]), forest.inbag[b][rows].astype(np.int64))
+        out[b, : table.shape[0]] = table.argmax(axis=1)
+    return out
+
+
 def cache_dir() -> Path:
     return Path(os.environ.get("RFX_INPUT_CACHE", str(_HERE.parent / ".rfx_cache")))
 
