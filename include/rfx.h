@@ -153,6 +153,39 @@ int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
                     int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox, int64_t* nnz,
                     void* stream);
 
+/* Case-wise outlier measures from the proximity rows ("Case-wise Proximity"), computed tile by
+ * tile without storing the matrix.  With p(i,j) = cnt(i,j) / B:
+ *   printed[i] = (1/(N-1)) sum_{j != i, p(i,j) > 0} 1 / p(i,j)^2   the paper's equation; pairs with
+ *                p = 0, whose term is undefined, are skipped;
+ *   classic[i] = N / sum_{j != i, labels[j] = labels[i]} p(i,j)^2  Breiman and Cutler's raw measure
+ *                (all j != i when labels is null); +inf when the sum is 0.
+ *   leaf, leaf_bound as rfx_prox_dense;  labels [device] nullable int32 [N];
+ *   printed, classic [device] nullable float64 [N] (at least one given).
+ * The sum of squares is accumulated as an exact integer; the sum of inverse squares in float64
+ * with atomics, so its last bits can differ from call to call.  Synchronous.  N >= 2, B < 2^20.
+ * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_UNSUPPORTED, RFX_ERR_OOM. */
+int rfx_prox_outlier(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const int32_t* labels,
+                     double* printed, double* classic, void* stream);
+
+/* Out-of-bag vote ("OOB Error Estimation"): sample i is predicted by the trees whose bootstrap
+ * sample missed it (inbag = 0), each voting for the class label of the leaf that holds i;
+ * pred[i] = the class with most votes (the lowest class on ties), -1 if i was never out-of-bag.
+ *   leaf        [device] uint32 [B][N]
+ *   inbag       [device] uint16 [B][N] bootstrap in-bag counts
+ *   leaf_class  [device] int32 [B][leaf_stride]: class label of leaf l of tree b at [b][l];
+ *               a leaf id >= leaf_stride or a label outside 0..n_classes-1 casts no vote
+ *   n_classes   1..128
+ *   y           [device] nullable int32 [N] true labels (needed for `wrong`)
+ *   votes       [device] nullable uint32 [N][n_classes] out
+ *   pred        [device] int32 [N] out
+ *   wrong       [host] nullable out: samples with a prediction that differs from y
+ *   voted       [host] nullable out: samples that have a prediction
+ * The error rate is wrong / voted (the paper's (1/n) sum when every sample was out-of-bag at
+ * least once).  Synchronous.  Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_OOM. */
+int rfx_oob_vote(const uint32_t* leaf, const uint16_t* inbag, const int32_t* leaf_class, int64_t N, int32_t B,
+                 int32_t leaf_stride, int32_t n_classes, const int32_t* y, uint32_t* votes, int32_t* pred,
+                 int64_t* wrong, int64_t* voted, void* stream);
+
 /* Implicit product Y = P V = (1/B) sum_b Z_b (Z_b^T V), Z_b the N x L_b one-hot leaf
  * membership of tree b, i.e. Y[i,:] = (1/B) sum_b sum_{j : leaf_b(j) = leaf_b(i)} V[j,:];
  * P is never formed.  A plan holds the per-tree grouping of samples by leaf (built once per

@@ -25,7 +25,7 @@ ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
 
 EXPORTS = (
     "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
-    "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_sparse", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
+    "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_sparse", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
 )
@@ -66,6 +66,8 @@ def load():
             "rfx_prox_dense": [vp, i64, i32, i32, ci, ci, vp, vp, vp],
             "rfx_prox_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp],
             "rfx_prox_sparse": [vp, i64, i32, i32, i32, ci, i64, vp, vp, vp, vp, ctypes.POINTER(i64), vp],
+            "rfx_prox_outlier": [vp, i64, i32, i32, vp, vp, vp, vp],
+            "rfx_oob_vote": [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, ctypes.POINTER(i64), ctypes.POINTER(i64), vp],
             "rfx_pv_plan_create": [vp, i64, i32, i32, ctypes.POINTER(vp), vp],
             "rfx_pv_plan_destroy": [vp],
             "rfx_pv_apply": [vp, vp, i32, vp, vp],
@@ -232,6 +234,34 @@ def prox_sparse(leaf, leaf_bound: int, min_count: int = 1, capacity: int = None,
                                   prox.data_ptr() if prox is not None else 0, ctypes.byref(nnz), _stream()))
     n = nnz.value
     return rows[:n], cols[:n], counts[:n] if counts is not None else None, prox[:n] if prox is not None else None
+
+
+def prox_outlier(leaf, leaf_bound: int, labels=None, want_printed: bool = True, want_classic: bool = True):
+    """rfx_prox_outlier: returns (printed, classic), float64 [N] each (None when not asked for)."""
+    import torch
+    B, N = leaf.shape
+    printed = torch.empty(N, dtype=torch.float64, device=leaf.device) if want_printed else None
+    classic = torch.empty(N, dtype=torch.float64, device=leaf.device) if want_classic else None
+    _check(load().rfx_prox_outlier(_dev(leaf, torch.int32), N, B, leaf_bound, _dev(labels, torch.int32, (N,)),
+                                   printed.data_ptr() if printed is not None else 0,
+                                   classic.data_ptr() if classic is not None else 0, _stream()))
+    return printed, classic
+
+
+def oob_vote(leaf, inbag, leaf_class, n_classes: int, y=None, want_votes: bool = True):
+    """rfx_oob_vote: returns (votes, pred, wrong, voted); wrong is None without labels."""
+    import torch
+    B, N = leaf.shape
+    if leaf_class.dim() != 2 or leaf_class.shape[0] != B:
+        raise ValueError("leaf_class must be [B][leaf_stride]")
+    votes = torch.empty((N, n_classes), dtype=torch.int32, device=leaf.device) if want_votes else None
+    pred = torch.empty(N, dtype=torch.int32, device=leaf.device)
+    wrong, voted = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(load().rfx_oob_vote(_dev(leaf, torch.int32), _dev(inbag, torch.int16, (B, N)), _dev(leaf_class, torch.int32),
+                               N, B, leaf_class.shape[1], n_classes, _dev(y, torch.int32, (N,)),
+                               votes.data_ptr() if votes is not None else 0, pred.data_ptr(),
+                               ctypes.byref(wrong) if y is not None else None, ctypes.byref(voted), _stream()))
+    return votes, pred, (wrong.value if y is not None else None), voted.value
 
 
 class PvPlan:

@@ -81,6 +81,11 @@ struct TileOut {
     unsigned long long* sp_cursor;
     unsigned long long sp_capacity;
     uint32_t sp_min_count;
+    // outlier sums, per sample: sum over the other samples of (B / cnt)^2 where cnt > 0, and of cnt^2
+    // over the other samples with the same label (all others when there are no labels)
+    double* o_inv;
+    unsigned long long* o_sq;
+    const int32_t* o_labels;
 };
 
 __device__ __forceinline__ int64_t packed_index(int64_t i, int64_t j, int64_t N) {
@@ -391,6 +396,101 @@ __device__ __forceinline__ void emit_tile(const TileOut& out, uint32_t* tr, int 
     }
 }
 
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+__device__ __forceinline__ unsigned long long wave_sum(unsigned long long v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// Outlier epilogue (paper, "Case-wise Proximity": per-sample sums over the proximity row).  Every
+// pair i < j of the tile adds f(cnt) to both of its samples: the b side is summed over the wave and
+// added by one lane, the a side is first combined over the workgroup's four waves in LDS.  The sum of
+// squares is an exact integer; the sum of inverse squares is float64 and its rounding depends on
+// the order in which the workgroups' atomics arrive.
+template <int J>
+__device__ __forceinline__ void outlier_tile(const TileOut& out, uint32_t* lds, int lane, int wave, int64_t a_tile,
+                                             int64_t b0, const uint32_t (&acc)[kR][J]) {
+    const int64_t N = out.N;
+    const int64_t a0 = a_tile + kR * lane;
+    const double Bd = (double)out.B;
+    int32_t la[kR];
+#pragma unroll
+    for (int r = 0; r < kR; ++r) la[r] = (out.o_labels && a0 + r < N) ? out.o_labels[a0 + r] : 0;
+    double inv_a[kR];
+    unsigned long long sq_a[kR];
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        inv_a[r] = 0.0;
+        sq_a[r] = 0;
+    }
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int64_t b = b0 + j;
+        const int32_t lb = (out.o_labels && b < N) ? out.o_labels[b] : 0;
+        double inv_b = 0.0;
+        unsigned long long sq_b = 0;
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            const int64_t a = a0 + r;
+            const uint32_t c = (uint32_t)out.B - acc[r][j];
+            if (a < N && b < a && c > 0) {
+                if (out.o_inv) {
+                    const double q = Bd / (double)c;
+                    inv_a[r] += q * q;
+                    inv_b += q * q;
+                }
+                if (out.o_sq && (!out.o_labels || la[r] == lb)) {
+                    const unsigned long long sq = (unsigned long long)c * c;
+                    sq_a[r] += sq;
+                    sq_b += sq;
+                }
+            }
+        }
+        inv_b = wave_sum(inv_b);
+        sq_b = wave_sum(sq_b);
+        if (lane == 0 && b < N) {
+            if (out.o_inv && inv_b != 0.0) unsafeAtomicAdd(out.o_inv + b, inv_b);
+            if (out.o_sq && sq_b != 0) atomicAdd(out.o_sq + b, sq_b);
+        }
+    }
+    double* l_inv = reinterpret_cast<double*>(lds);                                               // [kWaves][kATile]
+    unsigned long long* l_sq = reinterpret_cast<unsigned long long*>(lds) + kWaves * kATile;   // [kWaves][kATile]
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        l_inv[wave * kATile + kR * lane + r] = inv_a[r];
+        l_sq[wave * kATile + kR * lane + r] = sq_a[r];
+    }
+    __syncthreads();
+    const int t = threadIdx.x;  // one a sample per thread: kATile == 64 * kWaves
+    double si = 0.0;
+    unsigned long long ss = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        si += l_inv[w * kATile + t];
+        ss += l_sq[w * kATile + t];
+    }
+    const int64_t a = a_tile + t;
+    if (a < N) {
+        if (out.o_inv && si != 0.0) unsafeAtomicAdd(out.o_inv + a, si);
+        if (out.o_sq && ss != 0) atomicAdd(out.o_sq + a, ss);
+    }
+}
+
+__global__ __launch_bounds__(256) void outlier_finalise_kernel(const double* __restrict__ inv,
+                                                              const unsigned long long* __restrict__ sq, int64_t N,
+                                                              int32_t B, double* __restrict__ printed,
+                                                              double* __restrict__ classic) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    if (printed) printed[i] = inv[i] / (double)(N - 1);
+    if (classic) classic[i] = sq[i] ? (double)N * ((double)B * (double)B) / (double)sq[i] : __builtin_inf();
+}
+
 #ifndef RFX_PLAIN_WAVES
 #define RFX_PLAIN_WAVES 4
 #endif
@@ -398,7 +498,7 @@ __device__ __forceinline__ void emit_tile(const TileOut& out, uint32_t* tr, int 
 #define RFX_MIN_WAVES(oob) RFX_PLAIN_WAVES
 
 // P = number of leaf-id bit planes, J = b samples per wave, kMode = what is counted and how it leaves.
-enum { kModePlain = 0, kModeOob = 1, kModeSparse = 2 };
+enum { kModePlain = 0, kModeOob = 1, kModeSparse = 2, kModeOutlier = 3 };
 template <int P, int J, int kMode>
 __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kMode == kModeOob)) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
                                                                  int32_t G, int32_t n_tile_rows, TileOut out) {
@@ -432,7 +532,7 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kMode == kModeOob)) void
 
     // LDS: per-wave transposition buffers for the epilogue, then the table of the quotients c / B,
     // c = 0..B (plain variant with a float32 output only)
-    extern __shared__ uint32_t lds[];
+    extern __shared__ __align__(16) uint32_t lds[];
     constexpr int kTrWords = 64 * (J + 4);
     uint32_t* tr = lds + wave * kTrWords;
     float* tab = reinterpret_cast<float*>(lds + kWaves * kTrWords);
@@ -487,6 +587,8 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kMode == kModeOob)) void
 
     if (kMode == kModeSparse)
         emit_tile<J>(out, tr, lane, ta * kATile, b0, acc);
+    else if (kMode == kModeOutlier)
+        outlier_tile<J>(out, lds, lane, wave, ta * kATile, b0, acc);
     else if (out.use_tab)
         write_tile<J, kOob, true>(out, tab, tr, lane, ta * kATile, b0, acc);
     else
@@ -508,9 +610,10 @@ int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut&
     constexpr bool kOob = kMode == kModeOob;
     TileOut o = out;
     o.use_tab = (kMode == kModePlain && out.prox && out.B < 8192) ? 1 : 0;
+    static_assert(sizeof(uint32_t) * kWaves * 64 * (J + 4) >= 16 * kWaves * kATile, "outlier sums reuse the transposition buffers");
     const size_t lds = sizeof(uint32_t) * kWaves * 64 * (J + 4) +
                        (o.use_tab ? sizeof(float) * (size_t)(out.B + 1) : 0);
-    rfx::TimedLaunch timed(kOob ? "prox_tile_kernel_oob" : (kMode == kModeSparse ? "prox_tile_kernel_sparse" : "prox_tile_kernel"), st);
+    rfx::TimedLaunch timed(kOob ? "prox_tile_kernel_oob" : (kMode == kModeSparse ? "prox_tile_kernel_sparse" : (kMode == kModeOutlier ? "prox_tile_kernel_outlier" : "prox_tile_kernel")), st);
     hipLaunchKernelGGL((prox_tile_kernel<P, J, kMode>), dim3((unsigned)blocks), dim3(64 * kWaves), lds, st, planes, Npad, G,
                        (int32_t)rows, o);
     RFX_LAUNCH_CHECK("prox_tile_kernel");
@@ -592,7 +695,7 @@ int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_boun
     int rc = check_common("rfx_prox_dense", leaf, N, B, leaf_bound, count_dtype, layout);
     if (rc != RFX_OK) return rc;
     if (!counts && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_dense: neither counts nor prox given");
-    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0};
+    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
     return run<kModePlain>(leaf, nullptr, N, B, leaf_bound, out, rfx::as_stream(stream));
 }
 
@@ -603,7 +706,7 @@ int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t
     if (!inbag) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: inbag is null");
     if (B > 65535) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_oob: more than 65535 trees");
     if (!num && !den && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: no output given");
-    TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0};
+    TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
     return run<kModeOob>(leaf, inbag, N, B, leaf_bound, out, rfx::as_stream(stream));
 }
 
@@ -622,7 +725,7 @@ int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
     RFX_HIP(cursor.alloc(sizeof(unsigned long long)));
     RFX_HIP(hipMemsetAsync(cursor.p, 0, sizeof(unsigned long long), st));
     TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, 1, 0, rows, cols, cursor.as<unsigned long long>(),
-                (unsigned long long)capacity, (uint32_t)min_count};
+                (unsigned long long)capacity, (uint32_t)min_count, nullptr, nullptr, nullptr};
     rc = run<kModeSparse>(leaf, nullptr, N, B, leaf_bound, out, st);
     if (rc != RFX_OK) return rc;
     unsigned long long total = 0;
@@ -631,6 +734,30 @@ int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
     if (total > (unsigned long long)capacity && capacity > 0)
         return rfx::fail(RFX_ERR_CAPACITY, "rfx_prox_sparse: %llu pairs reach the threshold, capacity is %lld", total,
                          (long long)capacity);
+    return RFX_OK;
+}
+
+int rfx_prox_outlier(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const int32_t* labels,
+                     double* printed, double* classic, void* stream) {
+    int rc = check_common("rfx_prox_outlier", leaf, N, B, leaf_bound, RFX_U32, RFX_FULL);
+    if (rc != RFX_OK) return rc;
+    if (!printed && !classic) return rfx::fail(RFX_ERR_NULL, "rfx_prox_outlier: neither output given");
+    if (N < 2) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_outlier: needs at least 2 samples");
+    if (B >= (1 << 20)) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_outlier: 2^20 trees or more");
+    hipStream_t st = rfx::as_stream(stream);
+    rfx::DevBuf sums;  // inv [N] float64, then sq [N] uint64
+    RFX_HIP(sums.alloc(16 * (size_t)N));
+    RFX_HIP(hipMemsetAsync(sums.p, 0, 16 * (size_t)N, st));
+    double* inv = sums.as<double>();
+    unsigned long long* sq = reinterpret_cast<unsigned long long*>(inv + N);
+    TileOut out{nullptr, nullptr, nullptr, N, B, 0, 0, 0, nullptr, nullptr, nullptr, 0, 0, printed ? inv : nullptr,
+                classic ? sq : nullptr, labels};
+    rc = run<kModeOutlier>(leaf, nullptr, N, B, leaf_bound, out, st);
+    if (rc != RFX_OK) return rc;
+    hipLaunchKernelGGL(outlier_finalise_kernel, dim3((unsigned)rfx::ceil_div(N, 256)), dim3(256), 0, st, inv, sq, N, B,
+                       printed, classic);
+    RFX_LAUNCH_CHECK("outlier_finalise_kernel");
+    RFX_HIP(hipStreamSynchronize(st));  // the sums are freed on return
     return RFX_OK;
 }
 
