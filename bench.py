@@ -136,8 +136,20 @@ def main():
                                        sp_cols.data_ptr(), sp_cnt.data_ptr(), 0, ctypes.byref(got), st))
     sp_ms, sp_n = rfx.timing_get("prox_tile_kernel_sparse")
     sp_ms /= max(sp_n, 1)
-    rfx.timing_enable(False)
     del sp_rows, sp_cols, sp_cnt
+    # consumers of the proximity rows, also outside the step
+    d_y = torch.from_numpy(y.astype(np.int32)).to(dev)
+    d_lc = torch.from_numpy(ri.leaf_classes(F, y, c.C)).to(dev)
+    for _ in range(2):
+        rfx.prox_outlier(leaf, Lb, d_y)
+        _, _, oob_wrong, oob_voted = rfx.oob_vote(leaf, d_inbag, d_lc, c.C, d_y, want_votes=False)
+    ol_ms, ol_n = rfx.timing_get("prox_tile_kernel_outlier")
+    ov_ms, ov_n = rfx.timing_get("oob_vote_kernel")
+    consumers = {"note": "not part of the step",
+                 "outlier_avg_launch_ms": ol_ms / max(ol_n, 1), "oob_vote_avg_launch_ms": ov_ms / max(ov_n, 1),
+                 "oob_vote_GBps": (6.0 * N * B + 8.0 * N) / (ov_ms / max(ov_n, 1) * 1e-3) / 1e9 if ov_ms > 0 else 0.0,
+                 "oob_error": oob_wrong / max(oob_voted, 1)}
+    rfx.timing_enable(False)
 
     tests = N * N * B / 2.0
     P = int(np.ceil(np.log2(max(Lb, 2))))
@@ -199,6 +211,7 @@ def main():
         "leaf_assign": la,
         "kernels": kern,
         "roofline": roofline,
+        "consumers": consumers,
         "sparse": {"note": "not part of the step: strict-upper (i, j, count) triplets of every non-zero pair",
                    "min_count": 1, "pairs": nnz, "fraction_of_triangle": nnz / max(N * (N - 1) / 2.0, 1.0),
                    "bytes_out": 10 * nnz, "avg_launch_ms": sp_ms,

@@ -189,6 +189,41 @@ def _check_sparse(d, n_rows, budget_bytes=40e9):
     say(f"sparse: {n_rows}+ sampled rows and columns exact")
 
 
+def _check_consumers(d, n_rows):
+    """Outlier measures and out-of-bag vote at full size, on sampled samples the oracle computes one by one."""
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    B, N = d["ref_leaf"].shape
+    _, y = ri.gaussian_mixture(d["c"])
+    C = d["c"].C
+    dy = torch.from_numpy(y.astype(np.int32)).cuda()
+    t0 = time.time()
+    printed, classic = rfx.prox_outlier(d["leaf"], d["Lb"], dy)
+    torch.cuda.synchronize()
+    say(f"outlier measures in {time.time() - t0:.3f}s")
+    rows = _sample_rows(N, n_rows, 15)
+    cnt = np.concatenate([oracle.counts_rows(d["ref_leaf"], i, i + 1) for i in rows])
+    np.testing.assert_allclose(printed.cpu().numpy()[rows], oracle.outlier_printed(cnt, B, rows), rtol=1e-12)
+    np.testing.assert_allclose(classic.cpu().numpy()[rows], oracle.outlier_classic(cnt, B, y, rows), rtol=1e-12)
+    say(f"outlier measures: {len(rows)} sampled samples within 1e-12")
+    lc = ri.leaf_classes(d["F"], y, C)
+    t0 = time.time()
+    votes, pred, wrong, voted = rfx.oob_vote(d["leaf"], torch.from_numpy(d["F"].inbag.view(np.int16)).cuda(),
+                                             torch.from_numpy(lc).cuda(), C, dy)
+    say(f"out-of-bag vote in {time.time() - t0:.3f}s: error {wrong}/{voted} = {wrong / max(voted, 1):.4f}")
+    cols = np.array(_sample_rows(N, 200, 16))
+    rv, rp = oracle.oob_vote(d["ref_leaf"][:, cols], d["F"].inbag[:, cols], lc, C)
+    np.testing.assert_array_equal(votes.cpu().numpy().view(np.uint32)[cols], rv)
+    np.testing.assert_array_equal(pred.cpu().numpy()[cols], rp)
+    # whole-array properties: votes per sample = number of trees that missed it; tallies agree with the predictions
+    np.testing.assert_array_equal(votes.sum(dim=1).cpu().numpy(), (d["F"].inbag == 0).sum(axis=0))
+    p = pred.cpu().numpy()
+    assert voted == int((p >= 0).sum()) and wrong == int(((p != y) & (p >= 0)).sum())
+    say(f"out-of-bag vote: {cols.size} sampled samples exact, tallies consistent")
+
+
 def _check_matvec(d, k, n_rows, prox=None):
     import torch
     import oracle
@@ -298,6 +333,7 @@ def test_cfg3_dense_and_rank32(w3):
     _check_matvec(w3, 32, 24, prox)
     del prox
     _check_sparse(w3, 16)
+    _check_consumers(w3, 12)
     _check_oob(w3, 12)
     _check_lowrank_and_mds(w3, 32, 20)
 
@@ -309,6 +345,7 @@ def test_cfg4_leaf_and_dense(w4):
     _check_matvec(w4, 64, 16, prox)
     del prox
     _check_sparse(w4, 12)
+    _check_consumers(w4, 8)
     _check_oob(w4, 12)
 
 
