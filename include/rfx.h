@@ -109,6 +109,16 @@ int32_t rfx_forest_leaf_bound(const rfx_forest* forest);
 int rfx_leaf_assign(const rfx_forest* forest, const float* X, int64_t N, int32_t M, uint32_t* leaf,
                     void* stream);
 
+/* Measurement aids (not part of the proximity path).  rfx_probe_valu runs a dependency-free loop
+ * of the two vector operations the compare-and-count kernel is made of (3-input boolean op,
+ * population count with accumulate) on every CU for `rounds` rounds (1..2^20) and reports the
+ * lane-operations per second reached; rfx_probe_copy copies `bytes` (2^20..2^36) of device
+ * memory with a plain kernel and reports bytes read + written per second (best of 3).  Both
+ * allocate their own buffers and are synchronous.  Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG,
+ * RFX_ERR_OOM. */
+int rfx_probe_valu(int32_t rounds, double* lane_ops_per_s, void* stream);
+int rfx_probe_copy(int64_t bytes, double* bytes_per_s, void* stream);
+
 /* Dense proximity (equation p(i,j) = (1/B) sum_b I(node_b(i) = node_b(j)), "Proximity
  * Matrices").
  *   leaf        [device] uint32 [B][N], every entry < leaf_bound

@@ -24,7 +24,7 @@ MDS_SQUARED, MDS_LINEAR = 0, 1
 ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
 
 EXPORTS = (
-    "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
+    "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_probe_valu", "rfx_probe_copy", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
     "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_sparse", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
@@ -62,6 +62,8 @@ def load():
             "rfx_forest_destroy": [vp],
             "rfx_timing_enable": [ci],
             "rfx_timing_get": [ctypes.c_char_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)],
+            "rfx_probe_valu": [i32, ctypes.POINTER(ctypes.c_double), vp],
+            "rfx_probe_copy": [i64, ctypes.POINTER(ctypes.c_double), vp],
             "rfx_leaf_assign": [vp, vp, i64, i32, vp, vp],
             "rfx_prox_dense": [vp, i64, i32, i32, ci, ci, vp, vp, vp],
             "rfx_prox_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp],
@@ -121,6 +123,20 @@ def timing_get(kernel: str):
     ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
     _check(load().rfx_timing_get(kernel.encode(), ctypes.byref(ms), ctypes.byref(n)))
     return ms.value, n.value
+
+
+def probe_valu(rounds: int = 4096) -> float:
+    """rfx_probe_valu: lane-operations per second of a dependency-free integer vector loop."""
+    r = ctypes.c_double(0.0)
+    _check(load().rfx_probe_valu(rounds, ctypes.byref(r), _stream()))
+    return r.value
+
+
+def probe_copy(nbytes: int = 1 << 32) -> float:
+    """rfx_probe_copy: bytes read + written per second by a plain device copy of nbytes."""
+    r = ctypes.c_double(0.0)
+    _check(load().rfx_probe_copy(nbytes, ctypes.byref(r), _stream()))
+    return r.value
 
 
 class Forest:
