@@ -39,6 +39,41 @@ def build_core(force: bool = False) -> Path:
     return _LIB_PATH
 
 
+_GROW_PATH = _HERE / "liboracle_grow.so"
+_grow_lib = None
+
+
+def build_grow(force: bool = False) -> Path:
+    """Compiles grow_core.c with gcc (in-tree)."""
+    src = _HERE / "grow_core.c"
+    if force or not _GROW_PATH.exists() or _GROW_PATH.stat().st_mtime < src.stat().st_mtime:
+        subprocess.run(["gcc", "-O2", "-std=c99", "-fopenmp", "-Wall", "-shared", "-fPIC", str(src), "-o",
+                        str(_GROW_PATH)], check=True)
+    return _GROW_PATH
+
+
+def _grow():
+    global _grow_lib
+    if _grow_lib is None:
+        build_grow()
+        lib = ctypes.CDLL(str(_GROW_PATH))
+        vp, i64, i32, u64 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64
+        lib.orc_draw.restype = u64
+        lib.orc_draw.argtypes = [u64, u64, u64, u64]
+        lib.orc_grow.restype = vp
+        lib.orc_grow.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, u64]
+        lib.orc_grown_total_nodes.restype = i64
+        lib.orc_grown_total_nodes.argtypes = [vp]
+        lib.orc_grown_max_leaves.restype = i32
+        lib.orc_grown_max_leaves.argtypes = [vp]
+        lib.orc_grown_export.restype = None
+        lib.orc_grown_export.argtypes = [vp] * 12
+        lib.orc_grown_free.restype = None
+        lib.orc_grown_free.argtypes = [vp]
+        _grow_lib = lib
+    return _grow_lib
+
+
 def _core():
     global _lib
     if _lib is None:
@@ -61,6 +96,42 @@ def _core():
 
 def _c(a, dtype):
     return np.ascontiguousarray(a, dtype=dtype)
+
+
+# --------------------------------------------------------------------------- forest growth
+def draw(seed: int, tree: int, a: int, b: int) -> int:
+    """The counter-based 64-bit draw that the growth uses (see grow_core.c)."""
+    return int(_grow().orc_draw(seed, tree, a, b))
+
+
+def grow(X, y, n_classes: int, n_trees: int, mtry: int, seed: int, first_tree: int = 0):
+    """Grows trees first_tree .. first_tree + n_trees - 1 to purity (Methodology: bootstrap sample,
+    mtry random features per node, best Gini decrease over the values present in the node; the open
+    points are fixed in grow_core.c's header).  Returns a dict of flat arrays: node_offset [B+1],
+    feature, threshold, left, right, leaf_id, depth [nodes], n_leaves [B], inbag uint16 [B][N],
+    train_leaf [B][N], leaf_class [B][max leaves]."""
+    lib = _grow()
+    X = _c(X, np.float32)
+    y = _c(y, np.int32)
+    N, M = X.shape
+    h = lib.orc_grow(X.ctypes.data, N, M, y.ctypes.data, n_classes, first_tree, n_trees, mtry, seed)
+    if not h:
+        raise ValueError("orc_grow rejected its arguments")
+    try:
+        nn = lib.orc_grown_total_nodes(h)
+        ml = lib.orc_grown_max_leaves(h)
+        out = dict(node_offset=np.empty(n_trees + 1, np.int64), feature=np.empty(nn, np.int32),
+                   threshold=np.empty(nn, np.float32), left=np.empty(nn, np.int32), right=np.empty(nn, np.int32),
+                   leaf_id=np.empty(nn, np.int32), depth=np.empty(nn, np.int32), n_leaves=np.empty(n_trees, np.int32),
+                   inbag=np.empty((n_trees, N), np.uint16), train_leaf=np.empty((n_trees, N), np.int32),
+                   leaf_class=np.empty((n_trees, ml), np.int32))
+        lib.orc_grown_export(h, *(out[k].ctypes.data for k in ("node_offset", "feature", "threshold", "left", "right",
+                                                               "leaf_id", "depth", "n_leaves", "inbag", "train_leaf",
+                                                               "leaf_class")))
+    finally:
+        lib.orc_grown_free(h)
+    out["n_trees"], out["n_features"] = n_trees, M
+    return out
 
 
 # --------------------------------------------------------------------------- a1: leaf assignment
