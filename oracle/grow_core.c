@@ -26,6 +26,8 @@
  *   - If none of the drawn features takes two values in the node, the remaining features are tried
  *     in index order and the first that does is used (with its best threshold); if no feature does,
  *     the node becomes a leaf although it is impure.
+ *   - A threshold that is a zero is stored as +0 (x <= tau does not distinguish the two zeros, so the
+ *     value present in the node may be either).
  *   - Leaves are numbered 0..L-1 in node order; a leaf's class is the class of largest weight
  *     (lowest class on ties).
  *
@@ -115,7 +117,7 @@ static int best_of_feature(const item_t* it, int64_t n, int32_t C, uint64_t* wl,
             found = 1;
             *best_num = num;
             *best_den = den;
-            *best_thr = it[p].x;
+            *best_thr = it[p].x + 0.0f; /* a zero threshold is stored as +0 */
         }
     }
     return found;
