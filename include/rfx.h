@@ -100,6 +100,39 @@ int rfx_forest_destroy(rfx_forest* forest);
  * emit, to be passed as `leaf_bound` below. */
 int32_t rfx_forest_leaf_bound(const rfx_forest* forest);
 
+/* Forest growth on the GPU ("GPU Tree Growth Strategies", "Batched Multi-Tree Processing";
+ * Methodology: every tree on a bootstrap sample, mtry random features per node, the split with
+ * the largest Gini decrease over the values present in the node, x <= tau goes left, growth until
+ * the nodes are pure).  Trees first_tree .. first_tree + n_trees - 1 are grown in batches, level
+ * by level.  What the paper leaves open is fixed as follows:
+ *   - random numbers: draw(seed, tree, a, b) = mix(mix(mix(seed ^ (tree+1) K) ^ a) ^ b), mix = the
+ *     output function of splitmix64, K = 0x9e3779b97f4a7c15; an integer below n is
+ *     ((draw >> 32) * n) >> 32.  Bootstrap row t of a tree = bounded(draw(seed, tree, 0, t), N);
+ *     the features of node v = the first mtry entries of a Fisher-Yates shuffle of 0..M-1 whose
+ *     s-th swap partner is s + bounded(draw(seed, tree, 1 + v, s), M - s);
+ *   - nodes are numbered breadth first in creation order, leaves 0..L-1 in node order;
+ *   - rows are weighted by their in-bag count; split scores are compared exactly (integer
+ *     cross-multiplication); candidates in feature draw order, then ascending threshold, a later
+ *     one wins only if strictly better; if no drawn feature takes two values in a node the other
+ *     features are tried in index order and the first that does is used; if none does the node is
+ *     a leaf with the class of largest weight (lowest class on ties).
+ *   X [device] float32 [N][M] without NaN;  y [device] int32 [N] in 0..n_classes-1;
+ *   1 <= N < 2^20, 1 <= mtry <= min(M, 64), n_classes <= 64.
+ * The result lives on the host.  rfx_grown_sizes reports the node total, the largest number of
+ * leaves in a tree and the number of level passes made; rfx_grown_export fills caller arrays in the layout of
+ * rfx_forest_desc (host; node arrays of length total_nodes, node_offset [B+1], n_leaves [B]) plus,
+ * all nullable, depth [nodes], inbag uint16 [B][N] and leaf_class int32 [B][max_leaves] (-1 past a
+ * tree's last leaf), ready for rfx_forest_create, rfx_prox_oob and rfx_oob_vote.  Synchronous.
+ * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_OOM, RFX_ERR_HIP. */
+typedef struct rfx_grown rfx_grown;
+int rfx_forest_grow(const float* X, const int32_t* y, int64_t N, int32_t M, int32_t n_classes, int32_t first_tree,
+                    int32_t n_trees, int32_t mtry, uint64_t seed, rfx_grown** out, void* stream);
+int rfx_grown_sizes(const rfx_grown* grown, int64_t* total_nodes, int32_t* max_leaves, int32_t* levels);
+int rfx_grown_export(const rfx_grown* grown, int64_t* node_offset, int32_t* feature, float* threshold, int32_t* left,
+                     int32_t* right, int32_t* leaf_id, int32_t* depth, int32_t* n_leaves, uint16_t* inbag,
+                     int32_t* leaf_class);
+int rfx_grown_destroy(rfx_grown* grown);
+
 /* Leaf assignment: leaf[b*N + i] = dense leaf index of sample i in tree b, for every tree and
  * every sample, in-bag or not ("for each tree, terminal node assignments are computed for all
  * samples", CPU Proximity Computation; traversal rule: "Threshold-based Splits").

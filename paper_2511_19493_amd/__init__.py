@@ -24,7 +24,7 @@ MDS_SQUARED, MDS_LINEAR = 0, 1
 ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
 
 EXPORTS = (
-    "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_probe_valu", "rfx_probe_copy", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
+    "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_probe_valu", "rfx_probe_copy", "rfx_forest_grow", "rfx_grown_sizes", "rfx_grown_export", "rfx_grown_destroy", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
     "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_sparse", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
@@ -64,6 +64,10 @@ def load():
             "rfx_timing_get": [ctypes.c_char_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)],
             "rfx_probe_valu": [i32, ctypes.POINTER(ctypes.c_double), vp],
             "rfx_probe_copy": [i64, ctypes.POINTER(ctypes.c_double), vp],
+            "rfx_forest_grow": [vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_uint64, ctypes.POINTER(vp), vp],
+            "rfx_grown_sizes": [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)],
+            "rfx_grown_export": [vp] * 11,
+            "rfx_grown_destroy": [vp],
             "rfx_leaf_assign": [vp, vp, i64, i32, vp, vp],
             "rfx_prox_dense": [vp, i64, i32, i32, ci, ci, vp, vp, vp],
             "rfx_prox_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp],
@@ -137,6 +141,32 @@ def probe_copy(nbytes: int = 1 << 32) -> float:
     r = ctypes.c_double(0.0)
     _check(load().rfx_probe_copy(nbytes, ctypes.byref(r), _stream()))
     return r.value
+
+
+def forest_grow(X, y, n_classes: int, n_trees: int, mtry: int, seed: int, first_tree: int = 0) -> dict:
+    """rfx_forest_grow + rfx_grown_export: grows the trees on the GPU and returns the host arrays
+    node_offset, feature, threshold, left, right, leaf_id, depth, n_leaves, inbag, leaf_class
+    (plus n_trees, n_features, levels)."""
+    import torch
+    N, M = X.shape
+    lib = load()
+    h = ctypes.c_void_p()
+    _check(lib.rfx_forest_grow(_dev(X, torch.float32), _dev(y, torch.int32, (N,)), N, M, n_classes, first_tree, n_trees, mtry,
+                               seed, ctypes.byref(h), _stream()))
+    try:
+        nn, ml, lv = ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_int32(0)
+        _check(lib.rfx_grown_sizes(h, ctypes.byref(nn), ctypes.byref(ml), ctypes.byref(lv)))
+        nn, ml = nn.value, ml.value
+        out = dict(node_offset=np.empty(n_trees + 1, np.int64), feature=np.empty(nn, np.int32),
+                   threshold=np.empty(nn, np.float32), left=np.empty(nn, np.int32), right=np.empty(nn, np.int32),
+                   leaf_id=np.empty(nn, np.int32), depth=np.empty(nn, np.int32), n_leaves=np.empty(n_trees, np.int32),
+                   inbag=np.empty((n_trees, N), np.uint16), leaf_class=np.empty((n_trees, ml), np.int32))
+        _check(lib.rfx_grown_export(h, *(out[k].ctypes.data for k in ("node_offset", "feature", "threshold", "left", "right",
+                                                                        "leaf_id", "depth", "n_leaves", "inbag", "leaf_class"))))
+    finally:
+        lib.rfx_grown_destroy(h)
+    out["n_trees"], out["n_features"], out["levels"] = n_trees, M, lv.value
+    return out
 
 
 class Forest:

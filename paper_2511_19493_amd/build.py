@@ -35,16 +35,28 @@ def _stale(target: Path, deps) -> bool:
     return any(d.stat().st_mtime > t for d in deps)
 
 
+# sources that are compiled several times, once per set of kernel instantiations: (object stem, extra flags)
+VARIANTS = {
+    "prox_dense.hip": [(f"prox_dense_mode{m}", [f"-DRFX_TILE_MODE={m}"]) for m in range(4)],
+}
+
+
 def build(force: bool = False, verbose: bool = True) -> Path:
-    srcs = sorted(CSRC.glob("*.hip"))
+    srcs = []
+    for src in sorted(CSRC.glob("*.hip")):
+        for stem, extra in VARIANTS.get(src.name, [(src.stem, [])]):
+            srcs.append((src, stem, extra))
+    # the longest compilations first
+    srcs.sort(key=lambda t: (t[0].name not in VARIANTS and t[0].name != "grow.hip", t[1]))
     hdrs = sorted(CSRC.glob("*.h")) + sorted((ROOT / "include").glob("*.h"))
     OBJ.mkdir(exist_ok=True)
     LIB.parent.mkdir(exist_ok=True)
 
-    def compile_one(src: Path):
-        obj = OBJ / (src.stem + ".o")
+    def compile_one(job):
+        src, stem, extra = job
+        obj = OBJ / (stem + ".o")
         if force or _stale(obj, [src, *hdrs]):
-            cmd = [HIPCC, *FLAGS, "-c", str(src), "-o", str(obj)]
+            cmd = [HIPCC, *FLAGS, *extra, "-c", str(src), "-o", str(obj)]
             if verbose:
                 print("[build]", " ".join(cmd), flush=True)
             r = subprocess.run(cmd, capture_output=True, text=True)
@@ -59,6 +71,9 @@ def build(force: bool = False, verbose: bool = True) -> Path:
     jobs = min(len(srcs), int(os.environ.get("MAX_JOBS", "8")), 16)
     with ThreadPoolExecutor(max_workers=max(1, jobs)) as ex:
         objs = list(ex.map(compile_one, srcs))
+    for old in OBJ.glob("*.o"):      # objects of sources or variants that no longer exist
+        if old not in objs:
+            old.unlink()
     if force or _stale(LIB, objs):
         cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *map(str, objs), "-o", str(LIB)]
         if verbose:

@@ -690,6 +690,9 @@ int run(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32
 
 extern "C" {
 
+// RFX_TILE_MODE (0..3), when defined, compiles the entry point of one mode only, so that the build can
+// compile the four sets of kernel instantiations side by side.
+#if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 0
 int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
                    void* counts, float* prox, void* stream) {
     int rc = check_common("rfx_prox_dense", leaf, N, B, leaf_bound, count_dtype, layout);
@@ -699,6 +702,9 @@ int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_boun
     return run<kModePlain>(leaf, nullptr, N, B, leaf_bound, out, rfx::as_stream(stream));
 }
 
+#endif
+
+#if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 1
 int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
                  int count_dtype, int layout, void* num, void* den, float* prox, void* stream) {
     int rc = check_common("rfx_prox_oob", leaf, N, B, leaf_bound, count_dtype, layout);
@@ -710,6 +716,9 @@ int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t
     return run<kModeOob>(leaf, inbag, N, B, leaf_bound, out, rfx::as_stream(stream));
 }
 
+#endif
+
+#if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 2
 int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count, int count_dtype,
                     int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox, int64_t* nnz,
                     void* stream) {
@@ -737,6 +746,9 @@ int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
     return RFX_OK;
 }
 
+#endif
+
+#if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 3
 int rfx_prox_outlier(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const int32_t* labels,
                      double* printed, double* classic, void* stream) {
     int rc = check_common("rfx_prox_outlier", leaf, N, B, leaf_bound, RFX_U32, RFX_FULL);
@@ -761,4 +773,5 @@ int rfx_prox_outlier(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bo
     return RFX_OK;
 }
 
+#endif
 }  // extern "C"
