@@ -90,19 +90,25 @@ __global__ __launch_bounds__(256) void bootstrap_kernel(u64 seed, int32_t first_
     atomicAdd(&cnt[tb * N + bounded(draw(seed, (u64)(first_tree + tb), 0, (u64)t), (uint32_t)N)], 1u);
 }
 
-// in-bag counts as uint16, the number of distinct in-bag rows and the class weights of every root
-__global__ __launch_bounds__(256) void inbag_kernel(const uint32_t* __restrict__ cnt, const int32_t* __restrict__ y, int32_t Tb,
-                                                   int64_t N, int32_t C, uint16_t* __restrict__ inbag,
-                                                   uint32_t* __restrict__ n_in, uint32_t* __restrict__ root_tot) {
-    const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= (int64_t)Tb * N) return;
-    const int64_t tb = g / N, i = g - tb * N;
-    const uint32_t c = cnt[g];
-    inbag[g] = (uint16_t)c;
-    if (c) {
-        atomicAdd(&n_in[tb], 1u);
-        atomicAdd(&root_tot[tb * C + y[i]], c);
+// In-bag counts as uint16, a 0/1 flag per (tree, row) whose prefix sum places the in-bag rows, and the
+// class weights of every root.  blockIdx.y is the tree, so a workgroup first adds its rows' weights
+// up in LDS and then issues one global atomic per class.
+__global__ __launch_bounds__(256) void inbag_kernel(const uint32_t* __restrict__ cnt, const int32_t* __restrict__ y, int64_t N,
+                                                   int32_t C, uint16_t* __restrict__ inbag, uint32_t* __restrict__ flag,
+                                                   uint32_t* __restrict__ root_tot) {
+    __shared__ uint32_t hist[kMaxClasses];
+    const int64_t tb = blockIdx.y;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (threadIdx.x < kMaxClasses) hist[threadIdx.x] = 0;
+    __syncthreads();
+    if (i < N) {
+        const uint32_t c = cnt[tb * N + i];
+        inbag[tb * N + i] = (uint16_t)c;
+        flag[tb * N + i] = c ? 1u : 0u;
+        if (c) atomicAdd(&hist[y[i]], c);
     }
+    __syncthreads();
+    if ((int)threadIdx.x < C && hist[threadIdx.x]) atomicAdd(&root_tot[tb * C + threadIdx.x], hist[threadIdx.x]);
 }
 
 __device__ __forceinline__ int32_t heaviest_class(const uint32_t* tot, int32_t C, int32_t* present) {
@@ -116,11 +122,10 @@ __device__ __forceinline__ int32_t heaviest_class(const uint32_t* tot, int32_t C
 }
 
 // Level 0: a root that holds one class is a leaf, the others are the first level.  One thread.
-__global__ void roots_kernel(int32_t Tb, int32_t C, int64_t cap, const uint32_t* __restrict__ n_in,
-                             const uint32_t* __restrict__ tree_start, const uint32_t* __restrict__ root_tot, Level lv,
-                             int32_t* __restrict__ root_active, int32_t* __restrict__ nd_feature,
-                             int32_t* __restrict__ nd_class, int32_t* __restrict__ nd_depth, int32_t* __restrict__ next_id,
-                             uint32_t* __restrict__ n_active) {
+__global__ void roots_kernel(int32_t Tb, int32_t C, int64_t N, int64_t cap, const uint32_t* __restrict__ pos,
+                             const uint32_t* __restrict__ root_tot, Level lv, int32_t* __restrict__ root_active,
+                             int32_t* __restrict__ nd_feature, int32_t* __restrict__ nd_class, int32_t* __restrict__ nd_depth,
+                             int32_t* __restrict__ next_id, uint32_t* __restrict__ n_active) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     uint32_t A = 0;
     for (int32_t tb = 0; tb < Tb; ++tb) {
@@ -131,8 +136,8 @@ __global__ void roots_kernel(int32_t Tb, int32_t C, int64_t cap, const uint32_t*
         if (present > 1) {
             lv.tree[A] = tb;
             lv.node[A] = 0;
-            lv.start[A] = tree_start[tb];
-            lv.count[A] = n_in[tb];
+            lv.start[A] = pos[(int64_t)tb * N];  // in-bag rows are placed in (tree, row) order
+            lv.count[A] = pos[(int64_t)(tb + 1) * N] - pos[(int64_t)tb * N];
             for (int32_t c = 0; c < C; ++c) lv.tot[(int64_t)A * C + c] = root_tot[(int64_t)tb * C + c];
             root_active[tb] = (int32_t)A;
             ++A;
@@ -145,15 +150,14 @@ __global__ void roots_kernel(int32_t Tb, int32_t C, int64_t cap, const uint32_t*
     *n_active = A;
 }
 
-__global__ __launch_bounds__(256) void fill_rows_kernel(const uint16_t* __restrict__ inbag, int32_t Tb, int64_t N,
-                                                       const uint32_t* __restrict__ tree_start,
-                                                       const int32_t* __restrict__ root_active, uint32_t* __restrict__ cursor,
+__global__ __launch_bounds__(256) void fill_rows_kernel(const uint32_t* __restrict__ flag, const uint32_t* __restrict__ pos,
+                                                       int32_t Tb, int64_t N, const int32_t* __restrict__ root_active,
                                                        uint32_t* __restrict__ rows, int32_t* __restrict__ row_node) {
     const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= (int64_t)Tb * N) return;
     const int64_t tb = g / N, i = g - tb * N;
-    if (!inbag[g]) return;
-    const uint32_t e = tree_start[tb] + atomicAdd(&cursor[tb], 1u);
+    if (!flag[g]) return;
+    const uint32_t e = pos[g];
     rows[e] = (uint32_t)i;
     row_node[e] = root_active[tb];
 }
@@ -421,27 +425,68 @@ __global__ __launch_bounds__(256) void fallback_choose_kernel(uint32_t n_seg, in
     atomicAdd(n_resolved, 1u);
 }
 
-// side of every row (0 left, 1 right, 2 = its node is not split) and the children's class weights
-__global__ __launch_bounds__(256) void sides_kernel(const float* __restrict__ X, int32_t M, int64_t N, int32_t C, uint32_t S,
+// The rows of a split node are reordered inside the node's own range, left child first: a 0/1 flag
+// per row (1 = goes left), its prefix sum over all rows, and a scatter.  Nothing here needs atomics,
+// and the order of the rows stays ascending inside each child.
+__global__ __launch_bounds__(256) void sides_kernel(const float* __restrict__ X, int32_t M, uint32_t S,
                                                    const uint32_t* __restrict__ rows, const int32_t* __restrict__ row_node,
-                                                   Level lv, const int32_t* __restrict__ has_split,
+                                                   const int32_t* __restrict__ has_split,
                                                    const int32_t* __restrict__ split_feat, const uint32_t* __restrict__ split_key,
-                                                   const int32_t* __restrict__ y, const uint16_t* __restrict__ inbag,
-                                                   uint8_t* __restrict__ side, uint32_t* __restrict__ child_tot,
-                                                   uint32_t* __restrict__ child_cnt) {
+                                                   uint32_t* __restrict__ goes_left) {
     const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= S) return;
     const int32_t a = row_node[e];
-    if (a < 0 || !has_split[a]) {
-        side[e] = 2;
-        return;
+    uint32_t l = 0;
+    if (a >= 0 && has_split[a]) l = order_key(X[(int64_t)rows[e] * M + split_feat[a]]) <= split_key[a] ? 1u : 0u;
+    goes_left[e] = l;
+}
+
+__global__ __launch_bounds__(256) void partition_kernel(uint32_t S, const uint32_t* __restrict__ rows,
+                                                       const int32_t* __restrict__ row_node, Level lv,
+                                                       const int32_t* __restrict__ has_split,
+                                                       const uint32_t* __restrict__ goes_left,
+                                                       const uint32_t* __restrict__ left_before, uint32_t* __restrict__ rows_tmp) {
+    const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= S) return;
+    const int32_t a = row_node[e];
+    if (a < 0 || !has_split[a]) return;
+    const uint32_t st = lv.start[a];
+    const uint32_t lb = left_before[e] - left_before[st];                  // left rows of the node before this one
+    const uint32_t nl = left_before[st + lv.count[a]] - left_before[st];   // left rows of the node
+    rows_tmp[goes_left[e] ? st + lb : st + nl + (e - st - lb)] = rows[e];
+}
+
+// class weights and row count of both children of every split node: one wave per child, lane c sums class c
+__global__ __launch_bounds__(256) void child_stats_kernel(uint32_t A, int32_t C, int64_t N, Level lv,
+                                                         const int32_t* __restrict__ has_split,
+                                                         const uint32_t* __restrict__ left_before,
+                                                         const uint32_t* __restrict__ rows_tmp, const int32_t* __restrict__ y,
+                                                         const uint16_t* __restrict__ inbag, uint32_t* __restrict__ child_tot,
+                                                         uint32_t* __restrict__ child_cnt) {
+    const int lane = threadIdx.x & 63;
+    const uint32_t ch = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (ch >= 2 * A) return;
+    const uint32_t a = ch >> 1;
+    if (!has_split[a]) return;
+    const uint32_t st = lv.start[a], n = lv.count[a];
+    const uint32_t nl = left_before[st + n] - left_before[st];
+    const uint32_t lo = (ch & 1) ? st + nl : st, hi = (ch & 1) ? st + n : st + nl;
+    const uint16_t* w_of = inbag + (int64_t)lv.tree[a] * N;
+    uint32_t mine = 0;  // lane c: weight of class c
+    for (uint32_t t0 = lo; t0 < hi; t0 += 64) {
+        const uint32_t p = t0 + lane;
+        const uint32_t r = p < hi ? rows_tmp[p] : 0u;
+        const int32_t cls = p < hi ? y[r] : -1;
+        const uint32_t w = p < hi ? (uint32_t)w_of[r] : 0u;
+        for (int32_t c = 0; c < C; ++c) {
+            uint32_t v = cls == c ? w : 0u;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+            if (lane == c) mine += v;
+        }
     }
-    const uint32_t r = rows[e];
-    const uint32_t s = order_key(X[(int64_t)r * M + split_feat[a]]) <= split_key[a] ? 0u : 1u;
-    side[e] = (uint8_t)s;
-    const int64_t ch = 2 * (int64_t)a + s;
-    atomicAdd(&child_tot[ch * C + y[r]], (uint32_t)inbag[(int64_t)lv.tree[a] * N + r]);
-    atomicAdd(&child_cnt[ch], 1u);
+    if (lane < C) child_tot[(int64_t)ch * C + lane] = mine;
+    if (lane == 0) child_cnt[ch] = hi - lo;
 }
 
 // per node: is it split, how many of its children go on to the next level, with how many rows
@@ -538,21 +583,27 @@ __global__ __launch_bounds__(256) void advance_ids_kernel(uint32_t A, const int3
     }
 }
 
-__global__ __launch_bounds__(256) void scatter_rows_kernel(uint32_t S, const uint32_t* __restrict__ rows,
-                                                          const int32_t* __restrict__ row_node, const uint8_t* __restrict__ side,
+// rows of the children that go on, moved to the next level's (dense) row array
+__global__ __launch_bounds__(256) void compact_rows_kernel(uint32_t S, const uint32_t* __restrict__ rows_tmp,
+                                                          const int32_t* __restrict__ row_node, Level lv,
+                                                          const int32_t* __restrict__ has_split,
+                                                          const uint32_t* __restrict__ left_before,
                                                           const int32_t* __restrict__ child_dest,
-                                                          const int32_t* __restrict__ child_next, uint32_t* __restrict__ cursor,
-                                                          uint32_t* __restrict__ rows_next, int32_t* __restrict__ row_node_next) {
-    const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= S) return;
-    const uint32_t s = side[e];
-    if (s > 1) return;
-    const int64_t ch = 2 * (int64_t)row_node[e] + s;
+                                                          const int32_t* __restrict__ child_next, uint32_t* __restrict__ rows_next,
+                                                          int32_t* __restrict__ row_node_next) {
+    const uint32_t p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= S) return;
+    const int32_t a = row_node[p];  // a node keeps its range of positions while its rows are reordered
+    if (a < 0 || !has_split[a]) return;
+    const uint32_t st = lv.start[a];
+    const uint32_t nl = left_before[st + lv.count[a]] - left_before[st];
+    const uint32_t s = (p - st < nl) ? 0u : 1u;
+    const int64_t ch = 2 * (int64_t)a + s;
     const int32_t d = child_dest[ch];
     if (d < 0) return;
-    const uint32_t p = (uint32_t)d + atomicAdd(&cursor[ch], 1u);
-    rows_next[p] = rows[e];
-    row_node_next[p] = child_next[ch];
+    const uint32_t q = (uint32_t)d + (s ? p - st - nl : p - st);
+    rows_next[q] = rows_tmp[p];
+    row_node_next[q] = child_next[ch];
 }
 
 // leaves numbered in node order: one wave per tree
@@ -640,34 +691,30 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
                int32_t mtry, u64 seed, hipStream_t st) {
     const int64_t cap = 2 * N;  // node numbers of a tree stay below twice its number of in-bag rows
     const int64_t TN = (int64_t)Tb * N;
-    rfx::DevBuf cnt32, inbag, n_in, root_tot, tree_start, cursor, root_active, next_id, counters;
+    rfx::DevBuf cnt32, inbag, ib_flag, ib_pos, root_tot, root_active, next_id, counters;
+    Scratch tmp;
     RFX_HIP(alloc_n<uint32_t>(cnt32, TN));
     RFX_HIP(alloc_n<uint16_t>(inbag, TN));
-    RFX_HIP(alloc_n<uint32_t>(n_in, Tb));
+    RFX_HIP(alloc_n<uint32_t>(ib_flag, TN + 1));
+    RFX_HIP(alloc_n<uint32_t>(ib_pos, TN + 1));
     RFX_HIP(alloc_n<uint32_t>(root_tot, (size_t)Tb * C));
-    RFX_HIP(alloc_n<uint32_t>(tree_start, Tb));
-    RFX_HIP(alloc_n<uint32_t>(cursor, Tb));
     RFX_HIP(alloc_n<int32_t>(root_active, Tb));
     RFX_HIP(alloc_n<int32_t>(next_id, Tb));
     RFX_HIP(alloc_n<uint32_t>(counters, 8));
     RFX_HIP(hipMemsetAsync(cnt32.p, 0, sizeof(uint32_t) * TN, st));
-    RFX_HIP(hipMemsetAsync(n_in.p, 0, sizeof(uint32_t) * Tb, st));
     RFX_HIP(hipMemsetAsync(root_tot.p, 0, sizeof(uint32_t) * Tb * C, st));
-    RFX_HIP(hipMemsetAsync(cursor.p, 0, sizeof(uint32_t) * Tb, st));
     hipLaunchKernelGGL(bootstrap_kernel, blocks_for(TN), dim3(256), 0, st, seed, first, Tb, N, cnt32.as<uint32_t>());
-    hipLaunchKernelGGL(inbag_kernel, blocks_for(TN), dim3(256), 0, st, cnt32.as<uint32_t>(), y, Tb, N, C, inbag.as<uint16_t>(),
-                       n_in.as<uint32_t>(), root_tot.as<uint32_t>());
+    hipLaunchKernelGGL(inbag_kernel, dim3((unsigned)rfx::ceil_div(N, 256), (unsigned)Tb), dim3(256), 0, st, cnt32.as<uint32_t>(), y, N,
+                       C, inbag.as<uint16_t>(), ib_flag.as<uint32_t>(), root_tot.as<uint32_t>());
     RFX_LAUNCH_CHECK("bootstrap kernels");
-    std::vector<uint32_t> h_n_in(Tb), h_start(Tb);
-    RFX_HIP(hipMemcpyAsync(h_n_in.data(), n_in.p, sizeof(uint32_t) * Tb, hipMemcpyDeviceToHost, st));
+    // position of every in-bag (tree, row) pair among all of them: the rows of the roots, tree after tree
+    int rc0 = scan_u32(tmp, ib_flag.as<uint32_t>(), ib_pos.as<uint32_t>(), (uint32_t)(TN + 1), st);
+    if (rc0 != RFX_OK) return rc0;
+    uint32_t s0 = 0;
+    RFX_HIP(hipMemcpyAsync(&s0, ib_pos.as<uint32_t>() + TN, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     RFX_HIP(hipStreamSynchronize(st));
-    uint64_t S0 = 0;
-    for (int32_t t = 0; t < Tb; ++t) {
-        h_start[t] = (uint32_t)S0;
-        S0 += h_n_in[t];
-    }
+    const uint64_t S0 = s0;
     if (S0 * (uint64_t)std::max(mtry, 1) >= (1ull << 31)) return rfx::fail(RFX_ERR_INVALID_ARG, "forest growth: batch too large");
-    RFX_HIP(hipMemcpyAsync(tree_start.p, h_start.data(), sizeof(uint32_t) * Tb, hipMemcpyHostToDevice, st));
 
     // node records of the batch: [Tb][cap]
     rfx::DevBuf nd_feature, nd_thr, nd_left, nd_right, nd_class, nd_depth, nd_leaf;
@@ -702,8 +749,8 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
     };
     const size_t K_max = S_max * (size_t)mtry, G_max = A_max * (size_t)mtry;
     rfx::DevBuf keys[2], vals[2], seg_node, seg_feat, seg_begin, seg_end, node_first_seg, node_nseg, best, has_split, split_feat,
-        split_key, split_thr, fb_next, fb_seg_node, fb_seg_feat, fb_seg_begin, fb_seg_end, fb_best, side, child_tot, child_cnt,
-        child_cursor, child_dest, child_next, f_split, f_active, f_rows, x_split, x_active, x_rows, tree_first;
+        split_key, split_thr, fb_next, fb_seg_node, fb_seg_feat, fb_seg_begin, fb_seg_end, fb_best, rows_tmp, goes_left,
+        left_before, child_tot, child_cnt, child_dest, child_next, f_split, f_active, f_rows, x_split, x_active, x_rows, tree_first;
     for (int i = 0; i < 2; ++i) {
         RFX_HIP(alloc_n<uint32_t>(keys[i], K_max));
         RFX_HIP(alloc_n<uint32_t>(vals[i], K_max));
@@ -725,10 +772,11 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
     RFX_HIP(alloc_n<uint32_t>(fb_seg_begin, A_max));
     RFX_HIP(alloc_n<uint32_t>(fb_seg_end, A_max));
     RFX_HIP(alloc_n<SegBest>(fb_best, A_max));
-    RFX_HIP(alloc_n<uint8_t>(side, S_max));
+    RFX_HIP(alloc_n<uint32_t>(rows_tmp, S_max));
+    RFX_HIP(alloc_n<uint32_t>(goes_left, S_max + 1));
+    RFX_HIP(alloc_n<uint32_t>(left_before, S_max + 1));
     RFX_HIP(alloc_n<uint32_t>(child_tot, 2 * A_max * C));
     RFX_HIP(alloc_n<uint32_t>(child_cnt, 2 * A_max));
-    RFX_HIP(alloc_n<uint32_t>(child_cursor, 2 * A_max));
     RFX_HIP(alloc_n<int32_t>(child_dest, 2 * A_max));
     RFX_HIP(alloc_n<int32_t>(child_next, 2 * A_max));
     RFX_HIP(alloc_n<uint32_t>(f_split, A_max + 1));
@@ -738,14 +786,13 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
     RFX_HIP(alloc_n<uint32_t>(x_active, A_max + 1));
     RFX_HIP(alloc_n<uint32_t>(x_rows, A_max + 1));
     RFX_HIP(alloc_n<uint32_t>(tree_first, Tb));
-    Scratch tmp;
 
     int cur = 0;
-    hipLaunchKernelGGL(roots_kernel, dim3(1), dim3(64), 0, st, Tb, C, cap, n_in.as<uint32_t>(), tree_start.as<uint32_t>(),
-                       root_tot.as<uint32_t>(), level_of(cur), root_active.as<int32_t>(), nd_feature.as<int32_t>(),
-                       nd_class.as<int32_t>(), nd_depth.as<int32_t>(), next_id.as<int32_t>(), counters.as<uint32_t>());
-    hipLaunchKernelGGL(fill_rows_kernel, blocks_for(TN), dim3(256), 0, st, inbag.as<uint16_t>(), Tb, N, tree_start.as<uint32_t>(),
-                       root_active.as<int32_t>(), cursor.as<uint32_t>(), rows[cur].as<uint32_t>(), row_node[cur].as<int32_t>());
+    hipLaunchKernelGGL(roots_kernel, dim3(1), dim3(64), 0, st, Tb, C, N, cap, ib_pos.as<uint32_t>(), root_tot.as<uint32_t>(),
+                       level_of(cur), root_active.as<int32_t>(), nd_feature.as<int32_t>(), nd_class.as<int32_t>(),
+                       nd_depth.as<int32_t>(), next_id.as<int32_t>(), counters.as<uint32_t>());
+    hipLaunchKernelGGL(fill_rows_kernel, blocks_for(TN), dim3(256), 0, st, ib_flag.as<uint32_t>(), ib_pos.as<uint32_t>(), Tb, N,
+                       root_active.as<int32_t>(), rows[cur].as<uint32_t>(), row_node[cur].as<int32_t>());
     RFX_LAUNCH_CHECK("root kernels");
     uint32_t A = 0, S = (uint32_t)S0;
     RFX_HIP(hipMemcpyAsync(&A, counters.p, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
@@ -820,12 +867,15 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
             }
         }
         // split the rows, classify the children, number them, build the next level
-        RFX_HIP(hipMemsetAsync(child_tot.p, 0, sizeof(uint32_t) * 2 * (size_t)A * C, st));
-        RFX_HIP(hipMemsetAsync(child_cnt.p, 0, sizeof(uint32_t) * 2 * (size_t)A, st));
-        RFX_HIP(hipMemsetAsync(child_cursor.p, 0, sizeof(uint32_t) * 2 * (size_t)A, st));
-        hipLaunchKernelGGL(sides_kernel, blocks_for(S), dim3(256), 0, st, X, M, N, C, S, rows[cur].as<uint32_t>(),
-                           row_node[cur].as<int32_t>(), lv, has_split.as<int32_t>(), split_feat.as<int32_t>(),
-                           split_key.as<uint32_t>(), y, inbag.as<uint16_t>(), side.as<uint8_t>(), child_tot.as<uint32_t>(),
+        hipLaunchKernelGGL(sides_kernel, blocks_for(S), dim3(256), 0, st, X, M, S, rows[cur].as<uint32_t>(), row_node[cur].as<int32_t>(),
+                           has_split.as<int32_t>(), split_feat.as<int32_t>(), split_key.as<uint32_t>(), goes_left.as<uint32_t>());
+        RFX_LAUNCH_CHECK("sides_kernel");
+        if ((rc = scan_u32(tmp, goes_left.as<uint32_t>(), left_before.as<uint32_t>(), S + 1, st)) != RFX_OK) return rc;
+        hipLaunchKernelGGL(partition_kernel, blocks_for(S), dim3(256), 0, st, S, rows[cur].as<uint32_t>(), row_node[cur].as<int32_t>(),
+                           lv, has_split.as<int32_t>(), goes_left.as<uint32_t>(), left_before.as<uint32_t>(),
+                           rows_tmp.as<uint32_t>());
+        hipLaunchKernelGGL(child_stats_kernel, blocks_for(2 * (int64_t)A, 4), dim3(256), 0, st, A, C, N, lv, has_split.as<int32_t>(),
+                           left_before.as<uint32_t>(), rows_tmp.as<uint32_t>(), y, inbag.as<uint16_t>(), child_tot.as<uint32_t>(),
                            child_cnt.as<uint32_t>());
         hipLaunchKernelGGL(children_kernel, blocks_for(A), dim3(256), 0, st, A, C, has_split.as<int32_t>(), child_tot.as<uint32_t>(),
                            child_cnt.as<uint32_t>(), f_split.as<uint32_t>(), f_active.as<uint32_t>(), f_rows.as<uint32_t>());
@@ -842,9 +892,9 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
                            child_next.as<int32_t>());
         hipLaunchKernelGGL(advance_ids_kernel, blocks_for(A), dim3(256), 0, st, A, lv.tree, x_split.as<uint32_t>(),
                            f_split.as<uint32_t>(), tree_first.as<uint32_t>(), next_id.as<int32_t>());
-        hipLaunchKernelGGL(scatter_rows_kernel, blocks_for(S), dim3(256), 0, st, S, rows[cur].as<uint32_t>(),
-                           row_node[cur].as<int32_t>(), side.as<uint8_t>(), child_dest.as<int32_t>(), child_next.as<int32_t>(),
-                           child_cursor.as<uint32_t>(), rows[cur ^ 1].as<uint32_t>(), row_node[cur ^ 1].as<int32_t>());
+        hipLaunchKernelGGL(compact_rows_kernel, blocks_for(S), dim3(256), 0, st, S, rows_tmp.as<uint32_t>(), row_node[cur].as<int32_t>(),
+                           lv, has_split.as<int32_t>(), left_before.as<uint32_t>(), child_dest.as<int32_t>(),
+                           child_next.as<int32_t>(), rows[cur ^ 1].as<uint32_t>(), row_node[cur ^ 1].as<int32_t>());
         RFX_LAUNCH_CHECK("emit kernels");
         uint32_t nextA = 0, nextS = 0;
         RFX_HIP(hipMemcpyAsync(&nextA, x_active.as<uint32_t>() + A, sizeof(uint32_t), hipMemcpyDeviceToHost, st));

@@ -360,3 +360,30 @@ def test_cfg5_rows_with_reduced_trees(w5_reduced):
     _check_matvec(w5_reduced, 64, 8)
     _check_sparse(w5_reduced, 8)
     _check_lowrank_and_mds(w5_reduced, 64, 20, mds_reference="residual")
+
+
+# ------------------------------------------------------------------------------------------ forest growth
+@pytest.mark.parametrize("cfg,trees", [(4, 128), (5, 8)])
+def test_growth_at_full_row_counts(cfg, trees):
+    """The library's forest against the oracle's at the workloads' full row counts (a reduced number of
+    trees keeps the sequential oracle to about ten seconds); every array bit-exact."""
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    c = ri.CONFIGS[cfg]
+    X, y = ri.gaussian_mixture(c)
+    dX, dy = torch.from_numpy(X).cuda(), torch.from_numpy(y.astype(np.int32)).cuda()
+    rfx.forest_grow(dX, dy, c.C, 2, c.mtry, 99)                       # first call: allocator warm-up
+    t0 = time.time()
+    got = rfx.forest_grow(dX, dy, c.C, trees, c.mtry, 20251119, first_tree=3)
+    t_gpu = time.time() - t0
+    t0 = time.time()
+    ref = oracle.grow(X, y, c.C, trees, c.mtry, 20251119, first_tree=3)
+    t_cpu = time.time() - t0
+    say(f"cfg{cfg}: {trees} trees on {c.N} rows: library {t_gpu:.2f}s, oracle {t_cpu:.1f}s; {int(ref['node_offset'][-1])} nodes, "
+        f"deepest level {int(ref['depth'].max())}, most leaves {int(ref['n_leaves'].max())}")
+    for k in ("node_offset", "feature", "left", "right", "leaf_id", "depth", "n_leaves", "inbag", "leaf_class"):
+        np.testing.assert_array_equal(got[k], ref[k], err_msg=k)
+    np.testing.assert_array_equal(got["threshold"].view(np.uint32), ref["threshold"].view(np.uint32))
+    say("forest identical to the oracle's")
