@@ -159,6 +159,16 @@ def main():
     torch.cuda.synchronize()
     pv_plan_ms = (time.perf_counter() - t0) * 1e3
     plan.close()
+    # growth of the same forest shape on the GPU (outside the step; the step's forest comes from the input generator)
+    torch.cuda.synchronize()
+    rfx.forest_grow(dX, d_y, c.C, min(B, 8), c.mtry, 1)                      # warm-up
+    t0 = time.perf_counter()
+    grown = rfx.forest_grow(dX, d_y, c.C, B, c.mtry, ri.mixture.FOREST_ISEED)
+    grow_s = time.perf_counter() - t0
+    growth = {"note": "not part of the step", "trees": B, "seconds": grow_s, "trees_per_s": B / grow_s,
+              "nodes": int(grown["node_offset"][-1]), "level_passes": grown["levels"], "sorted_pairs": grown["sorted_pairs"],
+              "pairs_per_s": grown["sorted_pairs"] / grow_s}
+    del grown
     # practical ceilings of this GPU next to the published peaks
     valu_rate = rfx.probe_valu(4096)
     copy_rate = rfx.probe_copy(1 << 32)
@@ -243,6 +253,7 @@ def main():
         "kernels": kern,
         "roofline": roofline,
         "consumers": consumers,
+        "growth": growth,
         "sparse": {"note": "not part of the step: strict-upper (i, j, count) triplets of every non-zero pair",
                    "min_count": 1, "pairs": nnz, "fraction_of_triangle": nnz / max(N * (N - 1) / 2.0, 1.0),
                    "bytes_out": 10 * nnz, "avg_launch_ms": sp_ms,
@@ -251,11 +262,11 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(leaf, N, B, X, F, k)
+        out["cpu_baseline"] = cpu_baseline(leaf, N, B, X, F, k, y, c)
     print(json.dumps(out))
 
 
-def cpu_baseline(leaf_dev, N, B, X, F, k):
+def cpu_baseline(leaf_dev, N, B, X, F, k, y, c):
     """The oracle as it stands, on the host cores, on bounded samples of the same workload: naive pair
     counting on a block of rows (the metric's unit), plus leaf assignment and one float64 implicit P.V
     on the first trees of the forest."""
@@ -305,7 +316,12 @@ def cpu_baseline(leaf_dev, N, B, X, F, k):
     oracle.pv_implicit(sub_leaf, V)
     dt_pv = time.perf_counter() - t0
     w_pv = Bs * N * (2 * 4 * k + 4) + 2 * 4 * N * k      # the float32 byte model, for comparison with the GPU figure
+    t0 = time.perf_counter()
+    n_grow = min(B, cores)
+    oracle.grow(X, y, c.C, n_grow, c.mtry, 1)
+    dt_grow = time.perf_counter() - t0
     out["phases"] = {
+        "growth": {"trees": n_grow, "seconds": dt_grow, "trees_per_s": n_grow / dt_grow},
         "leaf_assign": {"trees": Bs, "seconds": dt_la, "walks_per_s": N * Bs / dt_la, "model_GBps": w_la / dt_la / 1e9},
         "pv_implicit_f64": {"trees": Bs, "k": k, "seconds": dt_pv, "model_GBps": w_pv / dt_pv / 1e9},
     }

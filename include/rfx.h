@@ -119,7 +119,8 @@ int32_t rfx_forest_leaf_bound(const rfx_forest* forest);
  *   X [device] float32 [N][M] without NaN;  y [device] int32 [N] in 0..n_classes-1;
  *   1 <= N < 2^20, 1 <= mtry <= min(M, 64), n_classes <= 64.
  * The result lives on the host.  rfx_grown_sizes reports the node total, the largest number of
- * leaves in a tree and the number of level passes made; rfx_grown_export fills caller arrays in the layout of
+ * leaves in a tree, the number of level passes made and the number of (row, feature) pairs that were
+ * sorted and scored over all levels (each output nullable); rfx_grown_export fills caller arrays in the layout of
  * rfx_forest_desc (host; node arrays of length total_nodes, node_offset [B+1], n_leaves [B]) plus,
  * all nullable, depth [nodes], inbag uint16 [B][N] and leaf_class int32 [B][max_leaves] (-1 past a
  * tree's last leaf), ready for rfx_forest_create, rfx_prox_oob and rfx_oob_vote.  Synchronous.
@@ -127,7 +128,8 @@ int32_t rfx_forest_leaf_bound(const rfx_forest* forest);
 typedef struct rfx_grown rfx_grown;
 int rfx_forest_grow(const float* X, const int32_t* y, int64_t N, int32_t M, int32_t n_classes, int32_t first_tree,
                     int32_t n_trees, int32_t mtry, uint64_t seed, rfx_grown** out, void* stream);
-int rfx_grown_sizes(const rfx_grown* grown, int64_t* total_nodes, int32_t* max_leaves, int32_t* levels);
+int rfx_grown_sizes(const rfx_grown* grown, int64_t* total_nodes, int32_t* max_leaves, int32_t* levels,
+                    int64_t* sorted_pairs);
 int rfx_grown_export(const rfx_grown* grown, int64_t* node_offset, int32_t* feature, float* threshold, int32_t* left,
                      int32_t* right, int32_t* leaf_id, int32_t* depth, int32_t* n_leaves, uint16_t* inbag,
                      int32_t* leaf_class);

@@ -65,7 +65,7 @@ def load():
             "rfx_probe_valu": [i32, ctypes.POINTER(ctypes.c_double), vp],
             "rfx_probe_copy": [i64, ctypes.POINTER(ctypes.c_double), vp],
             "rfx_forest_grow": [vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_uint64, ctypes.POINTER(vp), vp],
-            "rfx_grown_sizes": [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)],
+            "rfx_grown_sizes": [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i64)],
             "rfx_grown_export": [vp] * 11,
             "rfx_grown_destroy": [vp],
             "rfx_leaf_assign": [vp, vp, i64, i32, vp, vp],
@@ -146,7 +146,7 @@ def probe_copy(nbytes: int = 1 << 32) -> float:
 def forest_grow(X, y, n_classes: int, n_trees: int, mtry: int, seed: int, first_tree: int = 0) -> dict:
     """rfx_forest_grow + rfx_grown_export: grows the trees on the GPU and returns the host arrays
     node_offset, feature, threshold, left, right, leaf_id, depth, n_leaves, inbag, leaf_class
-    (plus n_trees, n_features, levels)."""
+    (plus n_trees, n_features, levels, sorted_pairs)."""
     import torch
     N, M = X.shape
     lib = load()
@@ -154,8 +154,8 @@ def forest_grow(X, y, n_classes: int, n_trees: int, mtry: int, seed: int, first_
     _check(lib.rfx_forest_grow(_dev(X, torch.float32), _dev(y, torch.int32, (N,)), N, M, n_classes, first_tree, n_trees, mtry,
                                seed, ctypes.byref(h), _stream()))
     try:
-        nn, ml, lv = ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_int32(0)
-        _check(lib.rfx_grown_sizes(h, ctypes.byref(nn), ctypes.byref(ml), ctypes.byref(lv)))
+        nn, ml, lv, sp = ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int64(0)
+        _check(lib.rfx_grown_sizes(h, ctypes.byref(nn), ctypes.byref(ml), ctypes.byref(lv), ctypes.byref(sp)))
         nn, ml = nn.value, ml.value
         out = dict(node_offset=np.empty(n_trees + 1, np.int64), feature=np.empty(nn, np.int32),
                    threshold=np.empty(nn, np.float32), left=np.empty(nn, np.int32), right=np.empty(nn, np.int32),
@@ -165,7 +165,7 @@ def forest_grow(X, y, n_classes: int, n_trees: int, mtry: int, seed: int, first_
                                                                         "leaf_id", "depth", "n_leaves", "inbag", "leaf_class"))))
     finally:
         lib.rfx_grown_destroy(h)
-    out["n_trees"], out["n_features"], out["levels"] = n_trees, M, lv.value
+    out["n_trees"], out["n_features"], out["levels"], out["sorted_pairs"] = n_trees, M, lv.value, sp.value
     return out
 
 

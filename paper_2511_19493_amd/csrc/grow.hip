@@ -669,7 +669,8 @@ struct rfx_grown {
     std::vector<int32_t> feature, left, right, leaf_id, depth, node_class, n_leaves;
     std::vector<float> threshold;
     std::vector<uint16_t> inbag;
-    int32_t levels = 0;  // deepest level reached by any tree
+    int32_t levels = 0;        // level passes of the deepest batch
+    int64_t sorted_pairs = 0;  // (row, feature) pairs sorted and scored over all levels and batches
 };
 
 namespace {
@@ -803,6 +804,7 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
         if ((size_t)A > A_max || (size_t)S > S_max) return rfx::fail(RFX_ERR_HIP, "forest growth: level tables overflow");
         Level lv = level_of(cur), nx = level_of(cur ^ 1);
         const uint32_t n_seg = A * (uint32_t)mtry;
+        g.sorted_pairs += (int64_t)S * mtry;
         RFX_HIP(hipMemsetAsync(counters.p, 0, sizeof(uint32_t) * 8, st));
         hipLaunchKernelGGL(draw_features_kernel, blocks_for(A), dim3(256), 0, st, seed, first, A, M, mtry, lv, seg_node.as<int32_t>(),
                            seg_feat.as<int32_t>(), seg_begin.as<uint32_t>(), seg_end.as<uint32_t>(),
@@ -975,11 +977,12 @@ int rfx_forest_grow(const float* X, const int32_t* y, int64_t N, int32_t M, int3
     return RFX_OK;
 }
 
-int rfx_grown_sizes(const rfx_grown* g, int64_t* total_nodes, int32_t* max_leaves, int32_t* levels) {
+int rfx_grown_sizes(const rfx_grown* g, int64_t* total_nodes, int32_t* max_leaves, int32_t* levels, int64_t* sorted_pairs) {
     if (!g) return rfx::fail(RFX_ERR_NULL, "rfx_grown_sizes: null handle");
     if (total_nodes) *total_nodes = (int64_t)g->feature.size();
     if (max_leaves) *max_leaves = g->n_leaves.empty() ? 0 : *std::max_element(g->n_leaves.begin(), g->n_leaves.end());
     if (levels) *levels = g->levels;
+    if (sorted_pairs) *sorted_pairs = g->sorted_pairs;
     return RFX_OK;
 }
 
