@@ -21,6 +21,7 @@ import time
 import numpy as np
 
 PEAK_VALU_LANE_OPS = 256 * 64 * 2.4e9   # 256 CUs x 64 lanes/clk x 2.4 GHz: plain 32-bit vector ops per second
+FUSED_FETCH_KIB, FUSED_WRITE_KIB = 39202305.0, 63045597.1   # rocprofv3 per-launch counters of the fused kernel, workload 4
 PEAK_HBM_BYTES = 8.0e12
 
 
@@ -89,11 +90,21 @@ def main():
         phase_ms.setdefault(name, []).append((e0, e1))
         return out
 
-    def step():
-        timed("leaf_assign", lambda: rfx.leaf_assign(gf, dX, leaf))
+    fused = B <= 1023   # plain and out-of-bag proximities from one pass over the trees
+
+    def dense_and_oob_separately():
         timed("prox_dense", lambda: rfx.prox_dense(leaf, Lb, rfx.U32, rfx.FULL, prox=prox, want_counts=False))
         timed("prox_oob", lambda: rfx._check(lib.rfx_prox_oob(leaf.data_ptr(), d_inbag.data_ptr(), N, B, Lb, rfx.U32,
                                                                rfx.UPPER_PACKED, 0, 0, prox_oob.data_ptr(), st)))
+
+    def step():
+        timed("leaf_assign", lambda: rfx.leaf_assign(gf, dX, leaf))
+        if fused:
+            timed("prox_dense_oob", lambda: rfx._check(lib.rfx_prox_dense_oob(
+                leaf.data_ptr(), d_inbag.data_ptr(), N, B, Lb, rfx.U32, rfx.FULL, 0, prox.data_ptr(), rfx.UPPER_PACKED, 0, 0,
+                prox_oob.data_ptr(), st)))
+        else:
+            dense_and_oob_separately()
         lam, V, Q, s = timed("prox_lowrank", lambda: rfx.prox_lowrank(leaf, Lb, dV0, T))
         res = timed("mds3d", lambda: rfx.mds3d(Q, s, dx0, rfx.MDS_SQUARED, max_iters=200, tol=1e-5))
         return lam, res
@@ -122,8 +133,16 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
 
     phases = {n: float(np.mean([a.elapsed_time(b) for a, b in evs])) for n, evs in phase_ms.items()}
+    if fused:
+        # the two passes the fused one replaces, outside the step, for their own kernel times
+        for _ in range(2):
+            dense_and_oob_separately()
+        torch.cuda.synchronize()
+        phases["separate_prox_dense"] = float(np.mean([a.elapsed_time(b) for a, b in phase_ms.pop("prox_dense")]))
+        phases["separate_prox_oob"] = float(np.mean([a.elapsed_time(b) for a, b in phase_ms.pop("prox_oob")]))
     kern = {}
-    for name in ("leaf_assign_kernel", "prox_tile_kernel", "prox_tile_kernel_oob", "pv_leaf_sum_kernel", "pv_gather_kernel"):
+    for name in ("leaf_assign_kernel", "prox_tile_kernel_both", "prox_tile_kernel", "prox_tile_kernel_oob", "pv_leaf_sum_kernel",
+                 "pv_gather_kernel"):
         ms, n = rfx.timing_get(name)
         kern[name] = {"avg_ms": ms / max(n, 1), "launches": n}
     # outside the timed step: the thresholded sparse form of the same counts (every non-zero pair)
@@ -177,17 +196,26 @@ def main():
     P = int(np.ceil(np.log2(max(Lb, 2))))
     P = 8 if P < 8 else (P if P <= 16 else (P + 1) & ~1)   # plane count the library uses for this bound
     # dominant kernel: bit-plane compare-and-count.  One launch covers the tile pairs on and below the
-    # diagonal of the (padded) N x N grid, 32 trees per (P+1) vector ops: algorithmic lane-ops per launch
-    ops_per_launch = tests * (P + 1) / 32.0
-    tile_ms = kern["prox_tile_kernel"]["avg_ms"]
+    # diagonal of the (padded) N x N grid; per 32 trees and pair, P + 1 vector ops for the plain count, P + 7 for the
+    # fused pass that also yields the out-of-bag numerator and denominator: algorithmic lane-ops per launch
+    dom = "prox_tile_kernel_both" if fused else "prox_tile_kernel"
+    ops_per_test = (P + 7) / 32.0 if fused else (P + 1) / 32.0
+    ops_per_launch = tests * ops_per_test
+    tile_ms = kern[dom]["avg_ms"]
     achieved = ops_per_launch / (tile_ms * 1e-3) if tile_ms > 0 else 0.0
     # HBM-side bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, calibrated on a 4 GiB copy); measured for workload 4 only
-    traffic = (39087769.4 * 2.0 + 42359959.7) * 1024.0 if (c.cfg == 4 and not reduced) else None
-    roofline = {"kernel": "prox_tile_kernel", "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_VALU_LANE_OPS / 1e12,
+    traffic = None
+    if c.cfg == 4 and not reduced:
+        traffic = (FUSED_FETCH_KIB * 2.0 + FUSED_WRITE_KIB) * 1024.0 if fused else (39087769.4 * 2.0 + 42359959.7) * 1024.0
+    plain_ms = kern["prox_tile_kernel"]["avg_ms"]
+    roofline = {"kernel": dom, "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_VALU_LANE_OPS / 1e12,
                 "unit": "T lane-ops/s", "frac": achieved / PEAK_VALU_LANE_OPS, "traffic": traffic,
-                "traffic_source": "profiles/bench_cfg4_pmc_fetch_write.txt (L2-to-fabric bytes; output is 4*N*N)",
-                "ops_per_test": (P + 1) / 32.0, "avg_launch_ms": tile_ms,
+                "traffic_source": "profiles/bench_cfg4_pmc_fetch_write.txt (L2-to-fabric bytes; outputs are 4*N*N + 2*N*(N-1))",
+                "ops_per_test": ops_per_test, "avg_launch_ms": tile_ms,
+                # the plain compare-and-count kernel on its own (P + 1 ops per 32 trees), run outside the step
+                "plain_kernel": {"avg_launch_ms": plain_ms, "ops_per_test": (P + 1) / 32.0,
+                                 "frac": tests * (P + 1) / 32.0 / (plain_ms * 1e-3) / PEAK_VALU_LANE_OPS if plain_ms > 0 else 0.0},
                 "tests_per_s": tests / (tile_ms * 1e-3) if tile_ms > 0 else 0.0,
                 # the same rate against the roof of a plain compare-and-add loop (2 lane-ops per test: 19.7 T tests/s),
                 # which does not depend on this kernel's own op count (above 1 = faster than a perfect such loop),
@@ -247,7 +275,7 @@ def main():
         "phases_ms": phases,
         "mds": {"iterations": mds_iters, "ms_per_iteration": phases["mds3d"] / max(mds_iters, 1),
                 "factor_GBps": N * k * mds_iters / (phases["mds3d"] * 1e-3) / 1e9},
-        "dense_tests_per_s": tests / (phases["prox_dense"] * 1e-3),
+        "dense_tests_per_s": tests / (phases["prox_dense_oob" if fused else "prox_dense"] * 1e-3),
         "pv": pv,
         "leaf_assign": la,
         "kernels": kern,

@@ -179,6 +179,16 @@ int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_boun
 int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
                  int count_dtype, int layout, void* num, void* den, float* prox, void* stream);
 
+/* Plain and out-of-bag proximity in one pass over the trees (the two share the per-tree leaf
+ * comparison, so the fused pass does about 40 % less work than the two calls).  Outputs and their
+ * meaning exactly as rfx_prox_dense (counts, prox, in `layout`) and rfx_prox_oob (num, den,
+ * prox_oob, in `oob_layout`); at least one output of each kind must be given.  The three counts
+ * of a pair share one 32-bit counter, so B <= 1023, else RFX_ERR_UNSUPPORTED (use the two calls).
+ * Synchronous. */
+int rfx_prox_dense_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
+                       int count_dtype, int layout, void* counts, float* prox, int oob_layout, void* num, void* den,
+                       float* prox_oob, void* stream);
+
 /* Thresholded sparse proximity ("CPU TriBlock Proximity": only pairs i < j are kept, and only
  * those whose proximity reaches a threshold; values below it are implicit zeros).  The threshold is
  * given as a count, p >= tau <=> cnt >= min_count = ceil(tau B); min_count = 1 keeps every non-zero

@@ -25,7 +25,7 @@ ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
 
 EXPORTS = (
     "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_probe_valu", "rfx_probe_copy", "rfx_forest_grow", "rfx_grown_sizes", "rfx_grown_export", "rfx_grown_destroy", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
-    "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_sparse", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
+    "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_dense_oob", "rfx_prox_sparse", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
 )
@@ -71,6 +71,7 @@ def load():
             "rfx_leaf_assign": [vp, vp, i64, i32, vp, vp],
             "rfx_prox_dense": [vp, i64, i32, i32, ci, ci, vp, vp, vp],
             "rfx_prox_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp],
+            "rfx_prox_dense_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, ci, vp, vp, vp, vp],
             "rfx_prox_sparse": [vp, i64, i32, i32, i32, ci, i64, vp, vp, vp, vp, ctypes.POINTER(i64), vp],
             "rfx_prox_outlier": [vp, i64, i32, i32, vp, vp, vp, vp],
             "rfx_oob_vote": [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, ctypes.POINTER(i64), ctypes.POINTER(i64), vp],
@@ -248,6 +249,22 @@ def prox_oob(leaf, inbag, leaf_bound: int, count_dtype: int = U32, layout: int =
                                count_dtype, layout, num.data_ptr(), den.data_ptr(),
                                prox.data_ptr() if prox is not None else 0, _stream()))
     return num, den, prox
+
+
+def prox_dense_oob(leaf, inbag, leaf_bound: int, count_dtype: int = U32, layout: int = FULL, oob_layout: int = FULL,
+                   want_counts: bool = True, want_prox: bool = True, want_num_den: bool = True, want_prox_oob: bool = True):
+    """rfx_prox_dense_oob: returns (counts, prox, num, den, prox_oob); B <= 1023."""
+    import torch
+    B, N = leaf.shape
+    cdt = _count_dtype(count_dtype)
+    mk = lambda want, lay, dt: torch.empty(_sym_shape(N, lay), dtype=dt, device=leaf.device) if want else None
+    counts, prox = mk(want_counts, layout, cdt), mk(want_prox, layout, torch.float32)
+    num, den = mk(want_num_den, oob_layout, cdt), mk(want_num_den, oob_layout, cdt)
+    prox_oob = mk(want_prox_oob, oob_layout, torch.float32)
+    ptr = lambda t: t.data_ptr() if t is not None else 0
+    _check(load().rfx_prox_dense_oob(_dev(leaf, torch.int32), _dev(inbag, torch.int16, (B, N)), N, B, leaf_bound, count_dtype,
+                                     layout, ptr(counts), ptr(prox), oob_layout, ptr(num), ptr(den), ptr(prox_oob), _stream()))
+    return counts, prox, num, den, prox_oob
 
 
 def prox_sparse_count(leaf, leaf_bound: int, min_count: int = 1) -> int:

@@ -37,7 +37,7 @@ def _stale(target: Path, deps) -> bool:
 
 # sources that are compiled several times, once per set of kernel instantiations: (object stem, extra flags)
 VARIANTS = {
-    "prox_dense.hip": [(f"prox_dense_mode{m}", [f"-DRFX_TILE_MODE={m}"]) for m in range(4)],
+    "prox_dense.hip": [(f"prox_dense_mode{m}", [f"-DRFX_TILE_MODE={m}"]) for m in range(5)],
 }
 
 

@@ -132,7 +132,22 @@ __device__ __forceinline__ void store4_float(float* base, int64_t at, const floa
 // Writes one wave tile.  acc[r][j] belongs to the pair (a_tile + 4*lane + r, b0 + j): the mismatch
 // count (plain), or the out-of-bag numerator in bits 0..15 and denominator in bits 16..31.  `tr` is
 // this wave's LDS transposition buffer: 64 rows of J + 4 words.
-template <int J, bool kOob, bool kTab>
+// What a raw counter means.  kField 0: the mismatch count (plain), or out-of-bag numerator | denominator
+// << 16.  The fused kernel keeps three 10-bit fields in one counter (mismatches | numerator << 10 |
+// denominator << 20); kField 1 reads its plain part, kField 2 its out-of-bag part.
+template <bool kOob, int kField>
+__device__ __forceinline__ uint32_t count_of(uint32_t raw, uint32_t B) {
+    if (kField == 1) return B - (raw & 1023u);
+    if (kField == 2) return (raw >> 10) & 1023u;
+    return kOob ? (raw & 0xffffu) : B - raw;
+}
+template <bool kOob, int kField>
+__device__ __forceinline__ uint32_t den_of(uint32_t raw) {
+    if (kField == 2) return raw >> 20;
+    return kOob ? (raw >> 16) : 0u;
+}
+
+template <int J, bool kOob, bool kTab, int kField = 0>
 __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab, uint32_t* tr, int lane, int64_t a_tile,
                                            int64_t b0, const uint32_t (&acc)[kR][J]) {
     static_assert(kR == 4 && J % 4 == 0 && 256 % J == 0, "tile shape assumed by the vector stores");
@@ -156,8 +171,8 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
                 float p[kR];
 #pragma unroll
                 for (int r = 0; r < kR; ++r) {
-                    c[r] = kOob ? (acc[r][j] & 0xffffu) : (uint32_t)out.B - acc[r][j];
-                    d[r] = kOob ? (acc[r][j] >> 16) : 0u;
+                    c[r] = count_of<kOob, kField>(acc[r][j], (uint32_t)out.B);
+                    d[r] = den_of<kOob, kField>(acc[r][j]);
                     p[r] = kOob ? oob_quotient(c[r], d[r], a0 + r == b0 + j) : quotient(c[r]);
                 }
                 if (out.counts) store4_count(out.counts, out.u16, at, c);
@@ -192,8 +207,8 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
                     uint32_t c[4], d[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        c[e] = kOob ? (raw[e] & 0xffffu) : (uint32_t)out.B - raw[e];
-                        d[e] = kOob ? (raw[e] >> 16) : 0u;
+                        c[e] = count_of<kOob, kField>(raw[e], (uint32_t)out.B);
+                        d[e] = den_of<kOob, kField>(raw[e]);
                     }
                     if (out.counts) store4_count(out.counts, out.u16, mt, c);
                     if (kOob && out.den) store4_count(out.den, out.u16, mt, d);
@@ -227,8 +242,8 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
             float p[kR];
 #pragma unroll
             for (int r = 0; r < kR; ++r) {
-                c[r] = kOob ? (acc[r][j] & 0xffffu) : (uint32_t)out.B - acc[r][j];
-                d[r] = kOob ? (acc[r][j] >> 16) : 0u;
+                c[r] = count_of<kOob, kField>(acc[r][j], (uint32_t)out.B);
+                d[r] = den_of<kOob, kField>(acc[r][j]);
                 p[r] = kOob ? oob_quotient(c[r], d[r], false) : quotient(c[r]);
             }
             // w[e] = element at aligned position 4*lane + e of the run shifted right by phi
@@ -293,8 +308,8 @@ __device__ __forceinline__ void write_tile(const TileOut& out, const float* tab,
         for (int r = 0; r < kR; ++r) {
             const int64_t a = a0 + r;
             if (a >= N) continue;
-            uint32_t c = kOob ? (acc[r][j] & 0xffffu) : (uint32_t)out.B - acc[r][j];
-            uint32_t d = kOob ? (acc[r][j] >> 16) : (uint32_t)out.B;
+            uint32_t c = count_of<kOob, kField>(acc[r][j], (uint32_t)out.B);
+            uint32_t d = kOob ? den_of<kOob, kField>(acc[r][j]) : (uint32_t)out.B;
             float p;
             if (a == b)
                 p = 1.0f;
@@ -498,13 +513,14 @@ __global__ __launch_bounds__(256) void outlier_finalise_kernel(const double* __r
 #define RFX_MIN_WAVES(oob) RFX_PLAIN_WAVES
 
 // P = number of leaf-id bit planes, J = b samples per wave, kMode = what is counted and how it leaves.
-enum { kModePlain = 0, kModeOob = 1, kModeSparse = 2, kModeOutlier = 3 };
+enum { kModePlain = 0, kModeOob = 1, kModeSparse = 2, kModeOutlier = 3, kModeBoth = 4 };
 template <int P, int J, int kMode>
 __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kMode == kModeOob)) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
-                                                                 int32_t G, int32_t n_tile_rows, TileOut out) {
+                                                                 int32_t G, int32_t n_tile_rows, TileOut out, TileOut out2) {
     constexpr bool kOob = kMode == kModeOob;
+    constexpr bool kBoth = kMode == kModeBoth;  // plain and out-of-bag counts in one pass; out2 takes the latter
     constexpr int PS = plane_stride(P);
-    constexpr int PL = kOob ? P + 1 : P;     // words of a sample actually used
+    constexpr int PL = (kOob || kBoth) ? P + 1 : P;  // words of a sample actually used
     constexpr int PV = (PL + 3) / 4;         // 16-byte loads per a sample
     constexpr int kBTile = J * kWaves;
     constexpr int kRatio = kATile / kBTile;  // b tiles per a tile
@@ -572,7 +588,14 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kMode == kModeOob)) void
                 uint32_t t = xa[r][0] ^ xb[0];
 #pragma unroll
                 for (int p = 1; p < P; ++p) t = __builtin_amdgcn_bitop3_b32(t, xa[r][p], xb[p], 0xf6);  // t | (a ^ b)
-                if (kOob) {
+                if (kBoth) {
+                    // three 10-bit fields (B <= 1023): mismatches | numerator << 10 | denominator << 20
+                    const uint32_t both_same = __builtin_amdgcn_bitop3_b32(t, xa[r][P], xb[P], 0x08);
+                    const uint32_t both = xa[r][P] & xb[P];
+                    acc[r][j] += __builtin_popcount(t);
+                    acc[r][j] += (uint32_t)__builtin_popcount(both_same) << 10;
+                    acc[r][j] += (uint32_t)__builtin_popcount(both) << 20;
+                } else if (kOob) {
                     // trees where both are out-of-bag and the leaves agree: ~t & oa & ob
                     const uint32_t both_same = __builtin_amdgcn_bitop3_b32(t, xa[r][P], xb[P], 0x08);
                     const uint32_t both = xa[r][P] & xb[P];
@@ -585,7 +608,14 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kMode == kModeOob)) void
         }
     }
 
-    if (kMode == kModeSparse)
+    if (kBoth) {
+        if (out.use_tab)
+            write_tile<J, false, true, 1>(out, tab, tr, lane, ta * kATile, b0, acc);
+        else
+            write_tile<J, false, false, 1>(out, tab, tr, lane, ta * kATile, b0, acc);
+        __builtin_amdgcn_wave_barrier();
+        write_tile<J, true, false, 2>(out2, tab, tr, lane, ta * kATile, b0, acc);
+    } else if (kMode == kModeSparse)
         emit_tile<J>(out, tr, lane, ta * kATile, b0, acc);
     else if (kMode == kModeOutlier)
         outlier_tile<J>(out, lds, lane, wave, ta * kATile, b0, acc);
@@ -596,7 +626,7 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kMode == kModeOob)) void
 }
 
 template <int P, int J, int kMode>
-int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, hipStream_t st) {
+int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, const TileOut& out2, hipStream_t st) {
     constexpr int kRatio = kATile / (J * kWaves);
     const int64_t rows = Npad / kATile;
     // XCD x works through tile rows x, x+8, ...; the last XCD that has `cnt` rows has the longest list
@@ -609,19 +639,20 @@ int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut&
     if (blocks > 0x7fffffffLL) return rfx::fail(RFX_ERR_INVALID_ARG, "proximity: N too large for one launch");
     constexpr bool kOob = kMode == kModeOob;
     TileOut o = out;
-    o.use_tab = (kMode == kModePlain && out.prox && out.B < 8192) ? 1 : 0;
+    o.use_tab = ((kMode == kModePlain || kMode == kModeBoth) && out.prox && out.B < 8192) ? 1 : 0;
     static_assert(sizeof(uint32_t) * kWaves * 64 * (J + 4) >= 16 * kWaves * kATile, "outlier sums reuse the transposition buffers");
     const size_t lds = sizeof(uint32_t) * kWaves * 64 * (J + 4) +
                        (o.use_tab ? sizeof(float) * (size_t)(out.B + 1) : 0);
-    rfx::TimedLaunch timed(kOob ? "prox_tile_kernel_oob" : (kMode == kModeSparse ? "prox_tile_kernel_sparse" : (kMode == kModeOutlier ? "prox_tile_kernel_outlier" : "prox_tile_kernel")), st);
+    rfx::TimedLaunch timed(kMode == kModeBoth ? "prox_tile_kernel_both" : kOob ? "prox_tile_kernel_oob" : (kMode == kModeSparse ? "prox_tile_kernel_sparse" : (kMode == kModeOutlier ? "prox_tile_kernel_outlier" : "prox_tile_kernel")), st);
     hipLaunchKernelGGL((prox_tile_kernel<P, J, kMode>), dim3((unsigned)blocks), dim3(64 * kWaves), lds, st, planes, Npad, G,
-                       (int32_t)rows, o);
+                       (int32_t)rows, o, out2);
     RFX_LAUNCH_CHECK("prox_tile_kernel");
     return RFX_OK;
 }
 
 template <int kMode>
-int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, hipStream_t st) {
+int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, const TileOut& out2,
+                    hipStream_t st) {
 #ifndef RFX_J_PLAIN
 #define RFX_J_PLAIN 16
 #endif
@@ -629,7 +660,7 @@ int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, cons
     switch (P) {
 #define RFX_CASE(p) \
     case p:         \
-        return launch_tiles<p, J, kMode>(planes, Npad, G, out, st);
+        return launch_tiles<p, J, kMode>(planes, Npad, G, out, out2, st);
 #ifdef RFX_ONLY_P  // development builds: a single plane count compiles in seconds
         RFX_CASE(RFX_ONLY_P)
 #else
@@ -668,7 +699,7 @@ int planes_for(int32_t leaf_bound) {
 
 template <int kMode>
 int run(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound, const TileOut& out,
-        hipStream_t st) {
+        hipStream_t st, const TileOut& out2 = TileOut{}) {
     const int P = planes_for(leaf_bound);
     const int PS = plane_stride(P);
     const int32_t G = (B + 31) / 32;
@@ -678,7 +709,7 @@ int run(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32
     hipLaunchKernelGGL(pack_planes_kernel, dim3((unsigned)rfx::ceil_div(Npad, 256), (unsigned)G), dim3(256), 0, st, leaf,
                        inbag, N, B, Npad, P, PS, planes.as<uint32_t>());
     RFX_LAUNCH_CHECK("pack_planes_kernel");
-    int rc = dispatch_planes<kMode>(P, planes.as<uint32_t>(), Npad, G, out, st);
+    int rc = dispatch_planes<kMode>(P, planes.as<uint32_t>(), Npad, G, out, out2, st);
     // the scratch is freed on return, so wait for the kernels that read it
     hipError_t e = hipStreamSynchronize(st);
     if (rc != RFX_OK) return rc;
@@ -690,7 +721,7 @@ int run(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32
 
 extern "C" {
 
-// RFX_TILE_MODE (0..3), when defined, compiles the entry point of one mode only, so that the build can
+// RFX_TILE_MODE (0..4), when defined, compiles the entry point of one mode only, so that the build can
 // compile the four sets of kernel instantiations side by side.
 #if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 0
 int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
@@ -746,6 +777,24 @@ int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
     return RFX_OK;
 }
 
+#endif
+
+#if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 4
+int rfx_prox_dense_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
+                       int count_dtype, int layout, void* counts, float* prox, int oob_layout, void* num, void* den,
+                       float* prox_oob, void* stream) {
+    int rc = check_common("rfx_prox_dense_oob", leaf, N, B, leaf_bound, count_dtype, layout);
+    if (rc != RFX_OK) return rc;
+    if (oob_layout != RFX_FULL && oob_layout != RFX_UPPER_PACKED)
+        return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_dense_oob: oob_layout=%d", oob_layout);
+    if (!inbag) return rfx::fail(RFX_ERR_NULL, "rfx_prox_dense_oob: inbag is null");
+    if (B > 1023) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_dense_oob: more than 1023 trees");
+    if ((!counts && !prox) || (!num && !den && !prox_oob))
+        return rfx::fail(RFX_ERR_NULL, "rfx_prox_dense_oob: an output of each kind is required");
+    TileOut plain{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
+    TileOut oob{num, den, prox_oob, N, B, count_dtype == RFX_U16, oob_layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
+    return run<kModeBoth>(leaf, inbag, N, B, leaf_bound, plain, rfx::as_stream(stream), oob);
+}
 #endif
 
 #if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 3
