@@ -130,6 +130,32 @@ def _check_dense(d, n_rows):
     return prox
 
 
+def _check_fused(d, n_rows):
+    """The fused plain + out-of-bag pass in the configuration bench.py times: full float32 plain output,
+    packed float32 out-of-bag output; sampled rows of both against the oracle."""
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    B, N = d["ref_leaf"].shape
+    inbag = d["F"].inbag
+    prox = torch.empty((N, N), dtype=torch.float32, device="cuda")
+    poob = torch.empty((N * (N - 1) // 2,), dtype=torch.float32, device="cuda")
+    rfx._check(rfx.load().rfx_prox_dense_oob(d["leaf"].data_ptr(), torch.from_numpy(inbag.view(np.int16)).cuda().data_ptr(), N, B,
+                                             d["Lb"], rfx.U32, rfx.FULL, 0, prox.data_ptr(), rfx.UPPER_PACKED, 0, 0,
+                                             poob.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    rows = [i for i in _sample_rows(N, n_rows, 17) if i < N - 1]
+    for i in rows:
+        ref = oracle.normalise(oracle.counts_rows(d["ref_leaf"], i, i + 1)[0], B)
+        np.testing.assert_array_equal(prox[i].cpu().numpy(), ref, err_msg=f"row {i}")
+        np.testing.assert_array_equal(prox[:, i].cpu().numpy(), ref, err_msg=f"column {i}")
+        rn, rd = oracle.oob_rows(d["ref_leaf"], inbag, i, i + 1)
+        ref = oracle.prox_oob_rows(rn, rd, i)[0, i + 1:]
+        st = i * N - i * (i + 1) // 2
+        np.testing.assert_array_equal(poob[st:st + N - i - 1].cpu().numpy(), ref, err_msg=f"out-of-bag row {i}")
+    say(f"fused pass: {len(rows)} sampled rows of both outputs bit-exact")
+
+
 def _check_oob(d, n_rows):
     import torch
     import oracle
@@ -332,6 +358,7 @@ def test_cfg3_dense_and_rank32(w3):
     prox = _check_dense(w3, 24)
     _check_matvec(w3, 32, 24, prox)
     del prox
+    _check_fused(w3, 12)
     _check_sparse(w3, 16)
     _check_consumers(w3, 12)
     _check_oob(w3, 12)
@@ -344,6 +371,7 @@ def test_cfg4_leaf_and_dense(w4):
     prox = _check_dense(w4, 24)
     _check_matvec(w4, 64, 16, prox)
     del prox
+    _check_fused(w4, 10)
     _check_sparse(w4, 12)
     _check_consumers(w4, 8)
     _check_oob(w4, 12)
