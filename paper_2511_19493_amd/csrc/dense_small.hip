@@ -109,10 +109,11 @@ __global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restr
         const double piv = R[j * k + j];
         for (int c = j + 1 + threadIdx.x; c < k; c += 256) R[j * k + c] /= piv;
         __syncthreads();
-        const int m = k - 1 - j;  // trailing block (j+1..k-1)^2, upper part
-        for (int e = threadIdx.x; e < m * m; e += 256) {
-            const int r = j + 1 + e / m, c = j + 1 + e % m;
-            if (c >= r) R[r * k + c] -= R[j * k + r] * R[j * k + c];
+        // trailing block (j+1..k-1)^2, upper part: a 16 x 16 arrangement of the threads walks it in squares
+        for (int r = j + 1 + (int)(threadIdx.x >> 4); r < k; r += 16) {
+            const double rj = R[j * k + r];
+            for (int c = j + 1 + (int)(threadIdx.x & 15); c < k; c += 16)
+                if (c >= r) R[r * k + c] -= rj * R[j * k + c];
         }
         __syncthreads();
     }

@@ -48,3 +48,20 @@ def test_host_side_argument_checks():
     assert lib.rfx_prox_lowrank(fake, 10, 4, 8, 300, 5, fake, fake, fake, None, None, None) == -1
     assert lib.rfx_prox_lowrank(fake, 10, 4, 8, 4, 0, fake, fake, fake, None, None, None) == -1
     assert lib.rfx_forest_create(None, None) == -2
+    # fused pass, consumers, growth
+    assert lib.rfx_prox_dense_oob(fake, fake, 10, 1024, 8, rfx.U32, rfx.FULL, fake, None, rfx.FULL, fake, None, None, None) == rfx.ERR_UNSUPPORTED
+    assert lib.rfx_prox_dense_oob(fake, fake, 10, 4, 8, rfx.U32, rfx.FULL, fake, None, rfx.FULL, None, None, None, None) == rfx.ERR_NULL
+    assert lib.rfx_prox_dense_oob(fake, fake, 10, 4, 8, rfx.U32, rfx.FULL, fake, None, 9, fake, None, None, None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_prox_outlier(fake, 1, 4, 8, None, fake, None, None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_prox_outlier(fake, 10, 4, 8, None, None, None, None) == rfx.ERR_NULL
+    assert lib.rfx_oob_vote(fake, fake, fake, 10, 4, 8, 200, None, None, fake, None, None, None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_oob_vote(fake, fake, fake, 10, 4, 8, 3, None, None, fake, ctypes.byref(nnz), None, None) == rfx.ERR_NULL
+    h = ctypes.c_void_p()
+    assert lib.rfx_forest_grow(fake, fake, 1 << 20, 4, 2, 0, 1, 2, 7, ctypes.byref(h), None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_forest_grow(fake, fake, 100, 4, 2, 0, 1, 5, 7, ctypes.byref(h), None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_forest_grow(fake, fake, 100, 4, 65, 0, 1, 2, 7, ctypes.byref(h), None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_forest_grow(fake, None, 100, 4, 2, 0, 1, 2, 7, ctypes.byref(h), None) == rfx.ERR_NULL
+    assert lib.rfx_grown_sizes(None, None, None, None, None) == rfx.ERR_NULL
+    out = ctypes.c_double(0)
+    assert lib.rfx_probe_valu(0, ctypes.byref(out), None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_probe_copy(5, ctypes.byref(out), None) == rfx.ERR_INVALID_ARG
