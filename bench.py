@@ -60,10 +60,22 @@ def main():
     k, T = c.k, c.T
     reduced = bool(args.rows or args.trees)
 
+    # Workloads whose dense float32 output does not fit the GPU (workload 5: 1 TB) take the exact sparse list instead of
+    # the dense passes, and their forest is grown on the GPU (the CPU input generator needs tens of minutes there).
+    large = 4.0 * N * N > 120e9
     t0 = time.time()
-    X, y, F = ri.load_or_grow(c, N=N if args.rows else None, B=B if args.trees else None)
+    if large:
+        X, y = ri.gaussian_mixture(c, N if args.rows else None)
+        grown = rfx.forest_grow(torch.from_numpy(X).to(dev), torch.from_numpy(y.astype(np.int32)).to(dev), c.C, B, c.mtry,
+                                ri.mixture.FOREST_ISEED)
+        F = ri.Forest(B, c.M, grown["node_offset"], grown["feature"], grown["threshold"], grown["left"], grown["right"],
+                      grown["leaf_id"], grown["depth"], grown["n_leaves"], grown["inbag"], np.zeros((B, 0), np.int32))
+        large_leaf_class = grown["leaf_class"]
+        del grown
+    else:
+        X, y, F = ri.load_or_grow(c, N=N if args.rows else None, B=B if args.trees else None)
     log(f"workload cfg{c.cfg}: N={N} M={c.M} B={B} k={k} T={T}; inputs ready in {time.time() - t0:.1f}s "
-        f"(nodes={F.total_nodes}, max leaves/tree={int(F.n_leaves.max())})")
+        f"(nodes={F.total_nodes}, max leaves/tree={int(F.n_leaves.max())}" + (", forest grown on the GPU)" if large else ")"))
     t0 = time.perf_counter()
     gf = rfx.Forest(F.n_features, F.node_offset, F.feature, F.threshold, F.left, F.right, F.leaf_id, F.n_leaves)
     forest_create_ms = (time.perf_counter() - t0) * 1e3     # host validation + re-layout + upload, once per forest
@@ -74,9 +86,18 @@ def main():
     m = args.mds_block
     dx0 = torch.from_numpy(ri.start_block(N, m, seed=ri.mixture.START_SEED + 1)).to(dev)
     leaf = torch.empty((B, N), dtype=torch.int32, device=dev)
-    prox = torch.empty((N, N), dtype=torch.float32, device=dev)
     n_ut = N * (N - 1) // 2
-    prox_oob = torch.empty((n_ut,), dtype=torch.float32, device=dev)
+    if large:
+        # capacity of the sparse list: one counting call on the leaf ids of this forest
+        rfx.leaf_assign(gf, dX, leaf)
+        sp_cap = max(rfx.prox_sparse_count(leaf, Lb, 1), 1)
+        sp_rows = torch.empty(sp_cap, dtype=torch.int32, device=dev)
+        sp_cols = torch.empty_like(sp_rows)
+        sp_cnt = torch.empty(sp_cap, dtype=torch.int16, device=dev)
+        sp_got = ctypes.c_int64(0)
+    else:
+        prox = torch.empty((N, N), dtype=torch.float32, device=dev)
+        prox_oob = torch.empty((n_ut,), dtype=torch.float32, device=dev)
 
     lib = rfx.load()
     st = torch.cuda.current_stream().cuda_stream
@@ -90,7 +111,7 @@ def main():
         phase_ms.setdefault(name, []).append((e0, e1))
         return out
 
-    fused = B <= 1023   # plain and out-of-bag proximities from one pass over the trees
+    fused = B <= 1023 and not large   # plain and out-of-bag proximities from one pass over the trees
 
     def dense_and_oob_separately():
         timed("prox_dense", lambda: rfx.prox_dense(leaf, Lb, rfx.U32, rfx.FULL, prox=prox, want_counts=False))
@@ -99,7 +120,11 @@ def main():
 
     def step():
         timed("leaf_assign", lambda: rfx.leaf_assign(gf, dX, leaf))
-        if fused:
+        if large:
+            timed("prox_sparse", lambda: rfx._check(lib.rfx_prox_sparse(leaf.data_ptr(), N, B, Lb, 1, rfx.U16, sp_cap,
+                                                                         sp_rows.data_ptr(), sp_cols.data_ptr(), sp_cnt.data_ptr(),
+                                                                         0, ctypes.byref(sp_got), st)))
+        elif fused:
             timed("prox_dense_oob", lambda: rfx._check(lib.rfx_prox_dense_oob(
                 leaf.data_ptr(), d_inbag.data_ptr(), N, B, Lb, rfx.U32, rfx.FULL, 0, prox.data_ptr(), rfx.UPPER_PACKED, 0, 0,
                 prox_oob.data_ptr(), st)))
@@ -141,26 +166,31 @@ def main():
         phases["separate_prox_dense"] = float(np.mean([a.elapsed_time(b) for a, b in phase_ms.pop("prox_dense")]))
         phases["separate_prox_oob"] = float(np.mean([a.elapsed_time(b) for a, b in phase_ms.pop("prox_oob")]))
     kern = {}
-    for name in ("leaf_assign_kernel", "prox_tile_kernel_both", "prox_tile_kernel", "prox_tile_kernel_oob", "pv_leaf_sum_kernel",
-                 "pv_gather_kernel"):
+    for name in ("leaf_assign_kernel", "prox_tile_kernel_both", "prox_tile_kernel", "prox_tile_kernel_oob",
+                 "prox_tile_kernel_sparse", "pv_leaf_sum_kernel", "pv_gather_kernel"):
         ms, n = rfx.timing_get(name)
         kern[name] = {"avg_ms": ms / max(n, 1), "launches": n}
     # outside the timed step: the thresholded sparse form of the same counts (every non-zero pair)
-    nnz = rfx.prox_sparse_count(leaf, Lb, 1)
-    sp_rows = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
-    sp_cols = torch.empty_like(sp_rows)
-    sp_cnt = torch.empty(max(nnz, 1), dtype=torch.int16, device=dev)
-    got = ctypes.c_int64(0)
-    rfx.timing_enable(True)
-    for _ in range(2):
-        rfx._check(lib.rfx_prox_sparse(leaf.data_ptr(), N, B, Lb, 1, rfx.U16, max(nnz, 1), sp_rows.data_ptr(),
-                                       sp_cols.data_ptr(), sp_cnt.data_ptr(), 0, ctypes.byref(got), st))
-    sp_ms, sp_n = rfx.timing_get("prox_tile_kernel_sparse")
-    sp_ms /= max(sp_n, 1)
+    if large:
+        nnz = sp_cap
+        sp_ms = kern["prox_tile_kernel_sparse"]["avg_ms"]
+        rfx.timing_enable(True)
+    else:
+        nnz = rfx.prox_sparse_count(leaf, Lb, 1)
+        sp_rows = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+        sp_cols = torch.empty_like(sp_rows)
+        sp_cnt = torch.empty(max(nnz, 1), dtype=torch.int16, device=dev)
+        got = ctypes.c_int64(0)
+        rfx.timing_enable(True)
+        for _ in range(2):
+            rfx._check(lib.rfx_prox_sparse(leaf.data_ptr(), N, B, Lb, 1, rfx.U16, max(nnz, 1), sp_rows.data_ptr(),
+                                           sp_cols.data_ptr(), sp_cnt.data_ptr(), 0, ctypes.byref(got), st))
+        sp_ms, sp_n = rfx.timing_get("prox_tile_kernel_sparse")
+        sp_ms /= max(sp_n, 1)
     del sp_rows, sp_cols, sp_cnt
     # consumers of the proximity rows, also outside the step
     d_y = torch.from_numpy(y.astype(np.int32)).to(dev)
-    d_lc = torch.from_numpy(ri.leaf_classes(F, y, c.C)).to(dev)
+    d_lc = torch.from_numpy(large_leaf_class if large else ri.leaf_classes(F, y, c.C)).to(dev)
     for _ in range(2):
         rfx.prox_outlier(leaf, Lb, d_y)
         _, _, oob_wrong, oob_voted = rfx.oob_vote(leaf, d_inbag, d_lc, c.C, d_y, want_votes=False)
@@ -182,9 +212,10 @@ def main():
     torch.cuda.synchronize()
     rfx.forest_grow(dX, d_y, c.C, min(B, 8), c.mtry, 1)                      # warm-up
     t0 = time.perf_counter()
-    grown = rfx.forest_grow(dX, d_y, c.C, B, c.mtry, ri.mixture.FOREST_ISEED)
+    grown = rfx.forest_grow(dX, d_y, c.C, B if not large else min(B, 128), c.mtry, ri.mixture.FOREST_ISEED)
     grow_s = time.perf_counter() - t0
-    growth = {"note": "not part of the step", "trees": B, "seconds": grow_s, "trees_per_s": B / grow_s,
+    grown_trees = B if not large else min(B, 128)
+    growth = {"note": "not part of the step", "trees": grown_trees, "seconds": grow_s, "trees_per_s": grown_trees / grow_s,
               "nodes": int(grown["node_offset"][-1]), "level_passes": grown["levels"], "sorted_pairs": grown["sorted_pairs"],
               "pairs_per_s": grown["sorted_pairs"] / grow_s}
     del grown
@@ -198,7 +229,7 @@ def main():
     # dominant kernel: bit-plane compare-and-count.  One launch covers the tile pairs on and below the
     # diagonal of the (padded) N x N grid; per 32 trees and pair, P + 1 vector ops for the plain count, P + 7 for the
     # fused pass that also yields the out-of-bag numerator and denominator: algorithmic lane-ops per launch
-    dom = "prox_tile_kernel_both" if fused else "prox_tile_kernel"
+    dom = "prox_tile_kernel_sparse" if large else ("prox_tile_kernel_both" if fused else "prox_tile_kernel")
     ops_per_test = (P + 7) / 32.0 if fused else (P + 1) / 32.0
     ops_per_launch = tests * ops_per_test
     tile_ms = kern[dom]["avg_ms"]
@@ -215,7 +246,7 @@ def main():
                 "ops_per_test": ops_per_test, "avg_launch_ms": tile_ms,
                 # the plain compare-and-count kernel on its own (P + 1 ops per 32 trees), run outside the step
                 "plain_kernel": {"avg_launch_ms": plain_ms, "ops_per_test": (P + 1) / 32.0,
-                                 "frac": tests * (P + 1) / 32.0 / (plain_ms * 1e-3) / PEAK_VALU_LANE_OPS if plain_ms > 0 else 0.0},
+                                 "frac": tests * (P + 1) / 32.0 / (plain_ms * 1e-3) / PEAK_VALU_LANE_OPS} if plain_ms > 0 else None,
                 "tests_per_s": tests / (tile_ms * 1e-3) if tile_ms > 0 else 0.0,
                 # the same rate against the roof of a plain compare-and-add loop (2 lane-ops per test: 19.7 T tests/s),
                 # which does not depend on this kernel's own op count (above 1 = faster than a perfect such loop),
@@ -270,12 +301,13 @@ def main():
         "dtype": "u32",
         "data": "synthetic",
         "config": {"workload": f"cfg{c.cfg}: N={N} M={c.M} B={B} trees to purity, mtry={c.mtry}, k={k}, T={T}"
-                               + (" (REDUCED, debugging)" if reduced else ""),
+                               + (" (REDUCED, debugging)" if reduced else "")
+                               + (" (dense outputs do not fit: exact sparse list instead; forest grown by rfx_forest_grow)" if large else ""),
                    "leaf_bound": Lb, "bit_planes": P, "mds_block": m, "mds_iters": mds_iters},
         "phases_ms": phases,
         "mds": {"iterations": mds_iters, "ms_per_iteration": phases["mds3d"] / max(mds_iters, 1),
                 "factor_GBps": N * k * mds_iters / (phases["mds3d"] * 1e-3) / 1e9},
-        "dense_tests_per_s": tests / (phases["prox_dense_oob" if fused else "prox_dense"] * 1e-3),
+        "dense_tests_per_s": tests / (phases["prox_sparse" if large else ("prox_dense_oob" if fused else "prox_dense")] * 1e-3),
         "pv": pv,
         "leaf_assign": la,
         "kernels": kern,
