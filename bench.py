@@ -172,6 +172,7 @@ def main():
         kern[name] = {"avg_ms": ms / max(n, 1), "launches": n}
     # outside the timed step: the thresholded sparse form of the same counts (every non-zero pair)
     if large:
+        assert sp_got.value == sp_cap, "the sparse pass found a different number of pairs than the counting call"
         nnz = sp_cap
         sp_ms = kern["prox_tile_kernel_sparse"]["avg_ms"]
         rfx.timing_enable(True)
