@@ -623,6 +623,21 @@ __global__ __launch_bounds__(64) void leaf_ids_kernel(int64_t cap, const int32_t
     if (lane == 0) n_leaves[tb] = run;
 }
 
+// the seven 4-byte fields of a node record (the threshold travels as its bit pattern)
+struct NodeFields {
+    const int32_t* f[7];
+};
+
+// [Tb][cap] per field -> the trees' first n_nodes records, tree after tree, field after field
+__global__ __launch_bounds__(256) void pack_nodes_kernel(int64_t cap, const int64_t* __restrict__ off, int64_t n_batch,
+                                                        NodeFields src, int32_t* __restrict__ packed) {
+    const int64_t tb = blockIdx.y;
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= off[tb + 1] - off[tb]) return;
+#pragma unroll
+    for (int f = 0; f < 7; ++f) packed[(int64_t)f * n_batch + off[tb] + v] = src.f[f][tb * cap + v];
+}
+
 // scratch of the library primitives; it only grows, and before it is replaced the stream is drained
 // because earlier work may still be using the old block
 struct Scratch {
@@ -678,13 +693,6 @@ namespace {
 template <class T>
 hipError_t alloc_n(rfx::DevBuf& b, size_t n) {
     return b.alloc(sizeof(T) * std::max<size_t>(n, 1));
-}
-
-// appends the first n records of tree t of a [Tb][cap] device array to a host vector
-template <class T>
-hipError_t pull(std::vector<T>& vec, const rfx::DevBuf& src, size_t off, size_t n, size_t t, size_t cap, hipStream_t st) {
-    vec.resize(off + n);
-    return hipMemcpyAsync(vec.data() + off, static_cast<const T*>(src.p) + t * cap, sizeof(T) * n, hipMemcpyDeviceToHost, st);
 }
 
 // Grows trees [first, first + Tb) and appends them to g.
@@ -919,17 +927,34 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
     RFX_HIP(hipMemcpyAsync(h_nodes.data(), next_id.p, sizeof(int32_t) * Tb, hipMemcpyDeviceToHost, st));
     RFX_HIP(hipMemcpyAsync(h_leaves.data(), n_leaves.p, sizeof(int32_t) * Tb, hipMemcpyDeviceToHost, st));
     RFX_HIP(hipStreamSynchronize(st));
+    // the batch's records, packed tree after tree on the device and copied with one transfer per field
+    std::vector<int64_t> h_off(Tb + 1, 0);
+    for (int32_t t = 0; t < Tb; ++t) h_off[t + 1] = h_off[t] + h_nodes[t];
+    const size_t n_batch = (size_t)h_off[Tb], base = g.feature.size();
+    rfx::DevBuf d_off, packed;
+    RFX_HIP(alloc_n<int64_t>(d_off, Tb + 1));
+    RFX_HIP(alloc_n<int32_t>(packed, 7 * n_batch));
+    RFX_HIP(hipMemcpyAsync(d_off.p, h_off.data(), sizeof(int64_t) * (Tb + 1), hipMemcpyHostToDevice, st));
+    NodeFields src{nd_feature.as<int32_t>(), reinterpret_cast<const int32_t*>(nd_thr.p), nd_left.as<int32_t>(), nd_right.as<int32_t>(),
+                   nd_leaf.as<int32_t>(), nd_depth.as<int32_t>(), nd_class.as<int32_t>()};
+    hipLaunchKernelGGL(pack_nodes_kernel, dim3((unsigned)rfx::ceil_div(cap, 256), (unsigned)Tb), dim3(256), 0, st, cap,
+                       d_off.as<int64_t>(), (int64_t)n_batch, src, packed.as<int32_t>());
+    RFX_LAUNCH_CHECK("pack_nodes_kernel");
+    g.feature.resize(base + n_batch);
+    g.threshold.resize(base + n_batch);
+    g.left.resize(base + n_batch);
+    g.right.resize(base + n_batch);
+    g.leaf_id.resize(base + n_batch);
+    g.depth.resize(base + n_batch);
+    g.node_class.resize(base + n_batch);
+    void* dst[7] = {g.feature.data() + base, g.threshold.data() + base, g.left.data() + base, g.right.data() + base,
+                    g.leaf_id.data() + base, g.depth.data() + base, g.node_class.data() + base};
+    for (int f = 0; f < 7; ++f)
+        RFX_HIP(hipMemcpyAsync(dst[f], packed.as<int32_t>() + (size_t)f * n_batch, sizeof(int32_t) * n_batch,
+                               hipMemcpyDeviceToHost, st));
     for (int32_t t = 0; t < Tb; ++t) {
-        const size_t off = g.feature.size(), n = (size_t)h_nodes[t];
-        g.node_offset.push_back((int64_t)(off + n));
+        g.node_offset.push_back((int64_t)base + h_off[t + 1]);
         g.n_leaves.push_back(h_leaves[t]);
-        RFX_HIP(pull(g.feature, nd_feature, off, n, (size_t)t, (size_t)cap, st));
-        RFX_HIP(pull(g.threshold, nd_thr, off, n, (size_t)t, (size_t)cap, st));
-        RFX_HIP(pull(g.left, nd_left, off, n, (size_t)t, (size_t)cap, st));
-        RFX_HIP(pull(g.right, nd_right, off, n, (size_t)t, (size_t)cap, st));
-        RFX_HIP(pull(g.leaf_id, nd_leaf, off, n, (size_t)t, (size_t)cap, st));
-        RFX_HIP(pull(g.depth, nd_depth, off, n, (size_t)t, (size_t)cap, st));
-        RFX_HIP(pull(g.node_class, nd_class, off, n, (size_t)t, (size_t)cap, st));
     }
     const size_t ib = g.inbag.size();
     g.inbag.resize(ib + (size_t)TN);
