@@ -284,13 +284,18 @@ __global__ __launch_bounds__(64 * kEvalWaves) void eval_segments_kernel(
         const uint32_t row = in ? vals[base + p] : 0u;
         const int32_t cls = in ? y[row] : 0;
         const uint32_t w = in ? (uint32_t)w_of[row] : 0u;
+        // one prefix sum per class that occurs in the tile (deep nodes hold two or three classes, not all C)
         uint32_t own_prefix = 0, add = 0;
-        for (int32_t c = 0; c < C; ++c) {
-            const uint32_t v = (in && cls == c) ? w : 0u;
+        u64 todo = __ballot(in);
+        while (todo) {
+            const int c = __shfl(cls, __ffsll((unsigned long long)todo) - 1);  // wave-uniform
+            const bool mine = in && cls == c;
+            const uint32_t v = mine ? w : 0u;
             const uint32_t incl = wave_incl_scan(v, lane);
-            if (cls == c) own_prefix = incl - v;
+            if (mine) own_prefix = incl - v;
             const uint32_t tile_tot = __shfl(incl, 63);
             if (lane == c) add = tile_tot;
+            todo &= ~__ballot(mine);
         }
         const uint32_t wl_own = (uint32_t)__shfl((int)wl, cls) + own_prefix;
         const uint32_t tot_own = (uint32_t)__shfl((int)tot, cls);
@@ -478,11 +483,14 @@ __global__ __launch_bounds__(256) void child_stats_kernel(uint32_t A, int32_t C,
         const uint32_t r = p < hi ? rows_tmp[p] : 0u;
         const int32_t cls = p < hi ? y[r] : -1;
         const uint32_t w = p < hi ? (uint32_t)w_of[r] : 0u;
-        for (int32_t c = 0; c < C; ++c) {
+        u64 todo = __ballot(p < hi);
+        while (todo) {  // the classes that occur in this tile
+            const int c = __shfl(cls, __ffsll((unsigned long long)todo) - 1);
             uint32_t v = cls == c ? w : 0u;
 #pragma unroll
             for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
             if (lane == c) mine += v;
+            todo &= ~__ballot(cls == c);
         }
     }
     if (lane < C) child_tot[(int64_t)ch * C + lane] = mine;
