@@ -992,9 +992,10 @@ int rfx_forest_grow(const float* X, const int32_t* y, int64_t N, int32_t M, int3
     g->n_classes = n_classes;
     g->N = N;
     g->node_offset.push_back(0);
-    // trees per batch: about 1.2e8 (key, row) pairs per level at most, 256 trees at most
+    // trees per batch: about 5e8 (key, row) pairs per level at most (some 20 GB of level buffers), 256 trees at most;
+    // few trees per batch leave the first levels, whose segments are whole trees, with too few waves
     const double per_tree = 0.64 * (double)N * mtry;
-    const int32_t batch = (int32_t)std::max(1.0, std::min(256.0, 1.2e8 / per_tree));
+    const int32_t batch = (int32_t)std::max(1.0, std::min(256.0, 5.0e8 / per_tree));
     int rc = RFX_OK;
     try {
         for (int32_t t0 = 0; t0 < n_trees && rc == RFX_OK; t0 += batch)
