@@ -134,6 +134,9 @@ int rfx_grown_export(const rfx_grown* grown, int64_t* node_offset, int32_t* feat
                      int32_t* right, int32_t* leaf_id, int32_t* depth, int32_t* n_leaves, uint16_t* inbag,
                      int32_t* leaf_class);
 int rfx_grown_destroy(rfx_grown* grown);
+/* The counter-based 64-bit draw defined above, evaluated on the host (the same function the
+ * kernels call); lets a caller reproduce the bootstrap samples and feature draws of a tree. */
+uint64_t rfx_growth_draw(uint64_t seed, uint64_t tree, uint64_t a, uint64_t b);
 
 /* Leaf assignment: leaf[b*N + i] = dense leaf index of sample i in tree b, for every tree and
  * every sample, in-bag or not ("for each tree, terminal node assignments are computed for all

@@ -24,7 +24,7 @@ MDS_SQUARED, MDS_LINEAR = 0, 1
 ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
 
 EXPORTS = (
-    "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_probe_valu", "rfx_probe_copy", "rfx_forest_grow", "rfx_grown_sizes", "rfx_grown_export", "rfx_grown_destroy", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
+    "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_probe_valu", "rfx_probe_copy", "rfx_forest_grow", "rfx_grown_sizes", "rfx_grown_export", "rfx_grown_destroy", "rfx_growth_draw", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
     "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_dense_oob", "rfx_prox_sparse", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
@@ -91,6 +91,8 @@ def load():
             fn = getattr(lib, name)
             fn.restype = ctypes.c_int
             fn.argtypes = args
+        lib.rfx_growth_draw.restype = ctypes.c_uint64
+        lib.rfx_growth_draw.argtypes = [ctypes.c_uint64] * 4
         lib.rfx_forest_leaf_bound.restype = ctypes.c_int32
         lib.rfx_forest_leaf_bound.argtypes = [vp]
         _lib = lib
@@ -142,6 +144,11 @@ def probe_copy(nbytes: int = 1 << 32) -> float:
     r = ctypes.c_double(0.0)
     _check(load().rfx_probe_copy(nbytes, ctypes.byref(r), _stream()))
     return r.value
+
+
+def growth_draw(seed: int, tree: int, a: int, b: int) -> int:
+    """rfx_growth_draw: the counter-based draw of the grower, on the host."""
+    return int(load().rfx_growth_draw(seed, tree, a, b))
 
 
 def forest_grow(X, y, n_classes: int, n_trees: int, mtry: int, seed: int, first_tree: int = 0) -> dict:

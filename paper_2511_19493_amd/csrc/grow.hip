@@ -1046,6 +1046,8 @@ int rfx_grown_export(const rfx_grown* g, int64_t* node_offset, int32_t* feature,
     return RFX_OK;
 }
 
+uint64_t rfx_growth_draw(uint64_t seed, uint64_t tree, uint64_t a, uint64_t b) { return draw(seed, tree, a, b); }
+
 int rfx_grown_destroy(rfx_grown* g) {
     delete g;
     return RFX_OK;

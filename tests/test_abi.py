@@ -65,3 +65,20 @@ def test_host_side_argument_checks():
     out = ctypes.c_double(0)
     assert lib.rfx_probe_valu(0, ctypes.byref(out), None) == rfx.ERR_INVALID_ARG
     assert lib.rfx_probe_copy(5, ctypes.byref(out), None) == rfx.ERR_INVALID_ARG
+
+
+def test_growth_draw_follows_the_published_generator():
+    """The library's counter-based draw (host side of the function the kernels call) against splitmix64's
+    published first outputs and a restatement of the composition; the oracle is not involved."""
+    mask, K = (1 << 64) - 1, 0x9E3779B97F4A7C15
+
+    def mix(z):
+        z = (z + K) & mask
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & mask
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
+        return z ^ (z >> 31)
+
+    assert mix(0) == 0xE220A8397B1DCDAF and mix(K) == 0x6E789E6AA1B965F4
+    for seed, tree, a, b in ((0, 0, 0, 0), (12345, 7, 0, 99), (2 ** 63 + 5, 999, 1 + 4021, 9), (1, 2, 3, 4)):
+        want = mix(mix(mix(seed ^ (((tree + 1) * K) & mask)) ^ a) ^ b)
+        assert rfx.growth_draw(seed, tree, a, b) == want
