@@ -128,6 +128,46 @@ __global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restr
     }
 }
 
+// The same factorisation with one barrier per column, for blocks small enough to hold two k x k arrays in
+// LDS: the Schur complement A is updated in place from its unscaled row j (A[r][c] -= A[j][r] A[j][c] / d),
+// while the scaled row goes to a separate array R, so the update and the scaling of a column do not have to
+// be separated by barriers, and every thread forms 1 / d itself instead of waiting for one thread's square root.
+__global__ __launch_bounds__(256) void chol_inverse_fast_kernel(const double* __restrict__ G, int k, double* __restrict__ T,
+                                                               int* __restrict__ flag) {
+    extern __shared__ double chol_sm[];
+    double* A = chol_sm;      // [k][k]
+    double* R = A + k * k;    // [k][k] upper factor
+    for (int e = threadIdx.x; e < k * k; e += 256) A[e] = G[e];
+    __syncthreads();
+    double scale = 0.0;
+    for (int j = 0; j < k; ++j) scale = fmax(scale, A[j * k + j]);
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    for (int j = 0; j < k; ++j) {
+        double d = A[j * k + j];
+        if (!(d > scale * 1e-28)) {
+            if (threadIdx.x == 0) *flag = 1;  // numerically rank-deficient block
+            d = scale > 0.0 ? scale * 1e-28 : 1.0;
+        }
+        const double inv = 1.0 / d, rs = sqrt(inv);
+        for (int c = j + (int)threadIdx.x; c < k; c += 256) R[j * k + c] = (c == j) ? d * rs : A[j * k + c] * rs;
+        for (int r = j + 1 + ty; r < k; r += 16) {
+            const double f = A[j * k + r] * inv;
+            for (int c = j + 1 + tx; c < k; c += 16)
+                if (c >= r) A[r * k + c] -= f * A[j * k + c];
+        }
+        __syncthreads();
+    }
+    for (int c = threadIdx.x; c < k; c += 256) {
+        for (int r = k - 1; r > c; --r) T[r * k + c] = 0.0;
+        T[c * k + c] = 1.0 / R[c * k + c];
+        for (int r = c - 1; r >= 0; --r) {
+            double s = 0.0;
+            for (int p = r + 1; p <= c; ++p) s += R[r * k + p] * T[p * k + c];
+            T[r * k + c] = -s / R[r * k + r];
+        }
+    }
+}
+
 // One workgroup: cyclic Jacobi on a symmetric k x k matrix held in LDS; rotations of one
 // round-robin step act on disjoint index pairs and are applied together (rows, then columns).
 // The accumulated rotations Wk live in global memory.  theta is sorted descending and the
@@ -350,8 +390,13 @@ int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& w
 
 int chol_inverse(const double* G, int k, SmallWs& ws, double* T, hipStream_t st) {
     const size_t lds = sizeof(double) * (size_t)k * k;
-    RFX_HIP(allow_lds(chol_inverse_kernel, lds));
-    hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(256), lds, st, G, k, T, ws.flag);
+    if (2 * lds <= 128 * 1024) {
+        RFX_HIP(allow_lds(chol_inverse_fast_kernel, 2 * lds));
+        hipLaunchKernelGGL(chol_inverse_fast_kernel, dim3(1), dim3(256), 2 * lds, st, G, k, T, ws.flag);
+    } else {
+        RFX_HIP(allow_lds(chol_inverse_kernel, lds));
+        hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(256), lds, st, G, k, T, ws.flag);
+    }
     RFX_LAUNCH_CHECK("chol_inverse_kernel");
     return RFX_OK;
 }
