@@ -64,6 +64,15 @@ def test_growth_on_degenerate_inputs(torch_cuda):
     _compare(torch_cuda, X, y, 64, 8, 2, 80)
 
 
+def test_growth_with_the_largest_feature_subsets(torch_cuda):
+    rng = np.random.default_rng(11)
+    for M, mtry in ((64, 64), (70, 64), (200, 64), (1000, 31)):
+        X = rng.standard_normal((400, M)).astype(np.float32)
+        X[:, ::3] = np.round(X[:, ::3])                   # many ties inside a third of the features
+        y = rng.integers(0, 4, 400).astype(np.int32)
+        _compare(torch_cuda, X, y, 4, 6, mtry, 1000 + M)
+
+
 def test_growth_medium(torch_cuda):
     import rfx_inputs as ri
     c = ri.CONFIGS[2]
