@@ -118,6 +118,86 @@ __global__ __launch_bounds__(256) void mds_moments_kernel(const float* __restric
     }
 }
 
+// The same moments on the matrix cores (SQUARED, k <= 64): M_c = sum_i a_i (u_i a_i)^T is a Gram product with
+// the sample index as the contraction, 4 samples per v_mfma_f64_16x16x4_f64.  Lane l of a wave supplies element
+// (row i0 + l / 16, column 16 tile + l % 16) of A for the left operand and of diag(u) A for the right one; result
+// register v of lane l is entry (16 tile_p + l / 16 + 4 v, 16 tile_q + l % 16).  The four waves of a workgroup take
+// a quarter of its rows each and add their tiles up in LDS in wave order, so the sums do not depend on timing.
+typedef double mds_double4_t __attribute__((ext_vector_type(4)));
+
+template <int NB>
+__global__ __launch_bounds__(256) void mds_moments_mfma_kernel(const float* __restrict__ A, const float* __restrict__ X,
+                                                              const double* __restrict__ colsum, int64_t N, int k, int m,
+                                                              int64_t rows_per_block, double* __restrict__ partialM,
+                                                              double* __restrict__ partialT) {
+    extern __shared__ double mfma_sm[];  // [k][k] tiles of M, then [k] of T
+    const int c = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane >> 4, c16 = lane & 15;
+    const double mean = colsum[c] / (double)N;
+    const int64_t b_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t b_end = min(N, b_begin + rows_per_block);
+    const int64_t per_wave = ((b_end - b_begin + 3) / 4 + 3) / 4 * 4;  // whole groups of 4 rows
+    const int64_t i_begin = min(b_end, b_begin + wave * per_wave), i_end = min(b_end, i_begin + per_wave);
+    mds_double4_t acc[NB][NB];
+    double tacc[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+        tacc[u] = 0.0;
+#pragma unroll
+        for (int w = 0; w < NB; ++w) acc[u][w] = mds_double4_t{0.0, 0.0, 0.0, 0.0};
+    }
+    for (int64_t i0 = i_begin; i0 < i_end; i0 += 4) {
+        const int64_t row = i0 + r;
+        const bool live = row < i_end;
+        const double u_i = live ? (double)X[row * m + c] - mean : 0.0;
+        double a[NB], b[NB];
+#pragma unroll
+        for (int w = 0; w < NB; ++w) {
+            const int col = 16 * w + c16;
+            a[w] = (live && col < k) ? (double)A[row * k + col] : 0.0;
+            b[w] = u_i * a[w];
+            tacc[w] += b[w];
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
+#pragma unroll
+            for (int w = 0; w < NB; ++w) acc[u][w] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[w], acc[u][w], 0, 0, 0);
+    }
+    // T: the four row groups of a wave (lanes c16, c16 + 16, ...) hold partial sums of the same columns
+#pragma unroll
+    for (int w = 0; w < NB; ++w) {
+        tacc[w] += __shfl_xor(tacc[w], 16);
+        tacc[w] += __shfl_xor(tacc[w], 32);
+    }
+    double* Ms = mfma_sm;
+    double* Ts = mfma_sm + k * k;
+    for (int w4 = 0; w4 < 4; ++w4) {
+        if (wave == w4) {
+#pragma unroll
+            for (int u = 0; u < NB; ++u)
+#pragma unroll
+                for (int w = 0; w < NB; ++w)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int p = 16 * u + r + 4 * v, q = 16 * w + c16;
+                        if (p < k && q < k) Ms[p * k + q] = (w4 == 0 ? 0.0 : Ms[p * k + q]) + acc[u][w][v];
+                    }
+            if (r == 0) {
+#pragma unroll
+                for (int w = 0; w < NB; ++w) {
+                    const int q = 16 * w + c16;
+                    if (q < k) Ts[q] = (w4 == 0 ? 0.0 : Ts[q]) + tacc[w];
+                }
+            }
+        }
+        __syncthreads();
+    }
+    const int64_t slot = (int64_t)blockIdx.x * m + c;
+    for (int e = threadIdx.x; e < k * k; e += 256) partialM[slot * k * k + e] = Ms[e];
+    for (int e = threadIdx.x; e < k; e += 256) partialT[slot * k + e] = Ts[e];
+}
+
 // M[c][e] = sum_block partialM[block][c][e];  T[c][q] likewise.  len = k*k or k.
 __global__ __launch_bounds__(256) void moments_reduce_kernel(const double* __restrict__ partial, int blocks, int m,
                                                             int len, double* __restrict__ out) {
@@ -236,15 +316,26 @@ int apply_gram_nb(const float* A, int64_t N, int k, int m, int squared, const fl
     int rc;
     if ((rc = col_sums(X, N, m, w, st)) != RFX_OK) return rc;
     {
-        const size_t lds = sizeof(float) * kRowsStage * (size_t)k + sizeof(double) * kRowsStage;
-        hipLaunchKernelGGL(mds_moments_kernel<NB>, dim3(w.blocks, m), dim3(256), lds, st, A, X, w.colsum, N, k, m,
-                           w.rows_per_block, squared, w.partialM, w.partialT);
+        int mom_blocks = w.blocks;
+        if (squared && NB <= 4) {
+            // few, long row ranges: the tiles are added up and written once per workgroup
+            mom_blocks = std::min(w.blocks, 64);
+            const int64_t rows_per = rfx::ceil_div(rfx::ceil_div(N, mom_blocks), 16) * 16;
+            mom_blocks = (int)rfx::ceil_div(N, rows_per);
+            const size_t lds = sizeof(double) * ((size_t)k * k + k);
+            hipLaunchKernelGGL(mds_moments_mfma_kernel<(NB <= 4 ? NB : 1)>, dim3(mom_blocks, m), dim3(256), lds, st, A, X,
+                               w.colsum, N, k, m, rows_per, w.partialM, w.partialT);
+        } else {
+            const size_t lds = sizeof(float) * kRowsStage * (size_t)k + sizeof(double) * kRowsStage;
+            hipLaunchKernelGGL(mds_moments_kernel<NB>, dim3(w.blocks, m), dim3(256), lds, st, A, X, w.colsum, N, k, m,
+                               w.rows_per_block, squared, w.partialM, w.partialT);
+        }
         RFX_LAUNCH_CHECK("mds_moments_kernel");
         if (squared)
             hipLaunchKernelGGL(moments_reduce_kernel, dim3((unsigned)rfx::ceil_div(k * k, 256), m), dim3(256), 0, st,
-                               w.partialM, w.blocks, m, k * k, w.M);
+                               w.partialM, mom_blocks, m, k * k, w.M);
         hipLaunchKernelGGL(moments_reduce_kernel, dim3((unsigned)rfx::ceil_div(k, 256), m), dim3(256), 0, st, w.partialT,
-                           w.blocks, m, k, w.T);
+                           mom_blocks, m, k, w.T);
         RFX_LAUNCH_CHECK("moments_reduce_kernel");
     }
     {
