@@ -123,6 +123,7 @@ __global__ __launch_bounds__(256) void mds_moments_kernel(const float* __restric
 // (row i0 + l / 16, column 16 tile + l % 16) of A for the left operand and of diag(u) A for the right one; result
 // register v of lane l is entry (16 tile_p + l / 16 + 4 v, 16 tile_q + l % 16).  The four waves of a workgroup take
 // a quarter of its rows each and add their tiles up in LDS in wave order, so the sums do not depend on timing.
+// Tiles below the diagonal are copies of their mirror images.
 typedef double mds_double4_t __attribute__((ext_vector_type(4)));
 
 template <int NB>
@@ -159,10 +160,11 @@ __global__ __launch_bounds__(256) void mds_moments_mfma_kernel(const float* __re
             b[w] = u_i * a[w];
             tacc[w] += b[w];
         }
+        // M_c is symmetric: only the tiles on and above the diagonal are accumulated
 #pragma unroll
         for (int u = 0; u < NB; ++u)
 #pragma unroll
-            for (int w = 0; w < NB; ++w) acc[u][w] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[w], acc[u][w], 0, 0, 0);
+            for (int w = u; w < NB; ++w) acc[u][w] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[w], acc[u][w], 0, 0, 0);
     }
     // T: the four row groups of a wave (lanes c16, c16 + 16, ...) hold partial sums of the same columns
 #pragma unroll
@@ -177,11 +179,15 @@ __global__ __launch_bounds__(256) void mds_moments_mfma_kernel(const float* __re
 #pragma unroll
             for (int u = 0; u < NB; ++u)
 #pragma unroll
-                for (int w = 0; w < NB; ++w)
+                for (int w = u; w < NB; ++w)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int p = 16 * u + r + 4 * v, q = 16 * w + c16;
-                        if (p < k && q < k) Ms[p * k + q] = (w4 == 0 ? 0.0 : Ms[p * k + q]) + acc[u][w][v];
+                        if (p < k && q < k) {
+                            const double sum = (w4 == 0 ? 0.0 : Ms[p * k + q]) + acc[u][w][v];
+                            Ms[p * k + q] = sum;
+                            if (w > u) Ms[q * k + p] = sum;  // the mirrored tile below the diagonal
+                        }
                     }
             if (r == 0) {
 #pragma unroll
