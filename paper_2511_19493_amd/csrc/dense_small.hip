@@ -136,7 +136,7 @@ __global__ __launch_bounds__(256) void chol_inverse_fast_kernel(const double* __
                                                                int* __restrict__ flag) {
     extern __shared__ double chol_sm[];
     double* A = chol_sm;      // [k][k]
-    double* R = A + k * k;    // [k][k] upper factor
+    double* R = A + k * k;    // [k][k] upper factor, then [k] reciprocals of its diagonal
     for (int e = threadIdx.x; e < k * k; e += 256) A[e] = G[e];
     __syncthreads();
     double scale = 0.0;
@@ -157,16 +157,35 @@ __global__ __launch_bounds__(256) void chol_inverse_fast_kernel(const double* __
         }
         __syncthreads();
     }
-    for (int c = threadIdx.x; c < k; c += 256) {
-        for (int r = k - 1; r > c; --r) T[r * k + c] = 0.0;
-        T[c * k + c] = 1.0 / R[c * k + c];
-        for (int r = c - 1; r >= 0; --r) {
-            double s = 0.0;
-            for (int p = r + 1; p <= c; ++p) s += R[r * k + p] * T[p * k + c];
-            T[r * k + c] = -s / R[r * k + r];
+    // Inverse of the upper factor by back substitution, built in the array the Schur complement no longer needs.
+    // Lane c of the first wave owns column c (columns are independent); the loops over r and p are the same for
+    // every lane, so R[r][p] is one broadcast read and Ti[p][c] a conflict-free one; entries below the diagonal
+    // are written as zeros before they are read.
+    double* Ti = A;
+    double* dinv = R + k * k;  // [k] reciprocals of the diagonal of R
+    for (int c = threadIdx.x; c < k; c += 256) dinv[c] = 1.0 / R[c * k + c];
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        for (int c0 = 0; c0 < k; c0 += 64) {
+            const int c = c0 + (int)threadIdx.x;
+            const bool on = c < k;
+            const int cc = on ? c : k - 1;  // lanes without a column read a valid one and store nothing
+            const int cmax = min(k - 1, c0 + 63);
+            for (int r = k - 1; r > cmax; --r)
+                if (on) Ti[r * k + c] = 0.0;
+            for (int r = cmax; r >= 0; --r) {
+                double s = 0.0;
+#pragma unroll 4
+                for (int p = r + 1; p <= cmax; ++p) s += R[r * k + p] * Ti[p * k + cc];
+                const double t = r > c ? 0.0 : (r == c ? dinv[r] : -s * dinv[r]);
+                if (on) Ti[r * k + c] = t;
+            }
         }
     }
+    __syncthreads();
+    for (int e = threadIdx.x; e < k * k; e += 256) T[e] = Ti[e];
 }
+
 
 // One workgroup: cyclic Jacobi on a symmetric k x k matrix held in LDS; rotations of one
 // round-robin step act on disjoint index pairs and are applied together (rows, then columns).
@@ -391,8 +410,9 @@ int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& w
 int chol_inverse(const double* G, int k, SmallWs& ws, double* T, hipStream_t st) {
     const size_t lds = sizeof(double) * (size_t)k * k;
     if (2 * lds <= 128 * 1024) {
-        RFX_HIP(allow_lds(chol_inverse_fast_kernel, 2 * lds));
-        hipLaunchKernelGGL(chol_inverse_fast_kernel, dim3(1), dim3(256), 2 * lds, st, G, k, T, ws.flag);
+        const size_t fast_lds = 2 * lds + sizeof(double) * (size_t)k;  // Schur complement / inverse, factor, 1 / diagonal
+        RFX_HIP(allow_lds(chol_inverse_fast_kernel, fast_lds));
+        hipLaunchKernelGGL(chol_inverse_fast_kernel, dim3(1), dim3(256), fast_lds, st, G, k, T, ws.flag);
     } else {
         RFX_HIP(allow_lds(chol_inverse_kernel, lds));
         hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(256), lds, st, G, k, T, ws.flag);
