@@ -18,6 +18,8 @@ struct SmallWs {
     double* theta = nullptr;    // [k]
     double* W = nullptr;        // [k][k]
     int* flag = nullptr;        // device status word (non-positive Cholesky pivot)
+    long long* sign_row = nullptr;  // [256][k] per row range and column: row of the largest-magnitude entry
+    float* sign_val = nullptr;      // [256][k] and its value
     int gram_blocks = 0;
     DevBuf buf;
     hipError_t alloc(int64_t N, int k);
@@ -37,6 +39,6 @@ int apply_small(const float* A, int64_t N, int k, const double* T, int kout, flo
 // orthonormal block); passes = 2 repeats the step for blocks of unknown conditioning (start blocks).
 int orthonormalise(const float* Y, int64_t N, int k, SmallWs& ws, float* Z, float* V, hipStream_t st, int passes);
 // Flips every column of V [N][kc] so that its largest-magnitude entry (first one on ties) is positive.
-int fix_signs(float* V, int64_t N, int kc, hipStream_t st);
+int fix_signs(float* V, int64_t N, int kc, SmallWs& ws, hipStream_t st);  // kc <= the width ws was sized for
 
 }  // namespace rfx

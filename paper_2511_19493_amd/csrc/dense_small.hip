@@ -187,26 +187,33 @@ __global__ __launch_bounds__(256) void chol_inverse_fast_kernel(const double* __
 }
 
 
-// One workgroup: cyclic Jacobi on a symmetric k x k matrix held in LDS; rotations of one
-// round-robin step act on disjoint index pairs and are applied together (rows, then columns).
-// The accumulated rotations Wk live in global memory.  theta is sorted descending and the
+// One workgroup: cyclic Jacobi on a symmetric k x k matrix held in LDS.  The rotations of one round-robin step
+// act on disjoint index pairs; with pair a = (p_a, q_a) and pair b = (p_b, q_b), the update J^T A J changes the
+// 2 x 2 block A[{p_a, q_a}][{p_b, q_b}] using nothing but that block and the two rotations, so every block is
+// read, rotated by rows, then by columns, and written by one thread: two barriers per step (rotations known;
+// blocks written).  The accumulated rotations are kept transposed (Wt[p][row], contiguous per rotated column),
+// in LDS when both arrays fit (kLdsW) and in global memory otherwise.  theta is sorted descending and the
 // columns of W follow.
+template <bool kLdsW>
 __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ H, int k, int sweeps,
                                                     double* __restrict__ Wk, double* __restrict__ theta,
                                                     double* __restrict__ W) {
     extern __shared__ double jac_sm[];
     const int K = (k + 1) & ~1;  // even number of players; index k (if any) is a dummy
+    const int half = K / 2;
     double* A = jac_sm;          // [k][k]
     double* cs = A + k * k;      // [K/2] cos, [K/2] sin
-    double* sn = cs + K / 2;
-    int* pp = (int*)(sn + K / 2);  // [K/2] p, [K/2] q
-    int* qq = pp + K / 2;
+    double* sn = cs + half;
+    int* pp = (int*)(sn + half);  // [K/2] p, [K/2] q
+    int* qq = pp + half;
+    double* Wt = kLdsW ? (double*)(qq + half) : Wk;  // [k][k], transposed
     for (int e = threadIdx.x; e < k * k; e += 256) {
         A[e] = H[e];
-        Wk[e] = (e / k == e % k) ? 1.0 : 0.0;
+        Wt[e] = (e / k == e % k) ? 1.0 : 0.0;
     }
     __syncthreads();
     __shared__ double red_off[256], red_diag[256];
+    const int ta = threadIdx.x >> 4, tb = threadIdx.x & 15;
     for (int sw = 0; sw < sweeps; ++sw) {
         // converged when the off-diagonal mass is negligible against the diagonal
         double off = 0.0, dg = 0.0;
@@ -231,7 +238,7 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
         __syncthreads();
         if (done) break;
         for (int step = 0; step < K - 1; ++step) {
-            for (int pr = threadIdx.x; pr < K / 2; pr += 256) {
+            for (int pr = threadIdx.x; pr < half; pr += 256) {
                 int p = (step + pr) % (K - 1);
                 int q = (pr == 0) ? K - 1 : (step + K - 1 - pr) % (K - 1);
                 if (p > q) {
@@ -249,7 +256,7 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
                         s = t * c;
                     }
                 } else {
-                    q = -1;  // pair with the dummy: nothing to rotate
+                    q = -1;  // pair with the dummy: index p rests in this step (identity rotation, no second row)
                 }
                 cs[pr] = c;
                 sn[pr] = s;
@@ -257,28 +264,32 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
                 qq[pr] = q;
             }
             __syncthreads();
-            for (int e = threadIdx.x; e < (K / 2) * k; e += 256) {  // rows p, q of A
-                const int pr = e / k, col = e - pr * k;
-                const int p = pp[pr], q = qq[pr];
-                if (q >= 0) {
-                    const double c = cs[pr], s = sn[pr];
-                    const double ap = A[p * k + col], aq = A[q * k + col];
-                    A[p * k + col] = c * ap - s * aq;
-                    A[q * k + col] = s * ap + c * aq;
+            for (int a = ta; a < half; a += 16) {
+                const int pa = pp[a], qa = qq[a];
+                const double ca = cs[a], sa = sn[a];
+                for (int b = tb; b < half; b += 16) {
+                    const int pb = pp[b], qb = qq[b];
+                    const double cb = cs[b], sb = sn[b];
+                    const double xpp = A[pa * k + pb];
+                    const double xpq = qb >= 0 ? A[pa * k + qb] : 0.0;
+                    const double xqp = qa >= 0 ? A[qa * k + pb] : 0.0;
+                    const double xqq = (qa >= 0 && qb >= 0) ? A[qa * k + qb] : 0.0;
+                    // rows p_a, q_a
+                    const double rpp = ca * xpp - sa * xqp, rpq = ca * xpq - sa * xqq;
+                    const double rqp = sa * xpp + ca * xqp, rqq = sa * xpq + ca * xqq;
+                    // columns p_b, q_b
+                    A[pa * k + pb] = cb * rpp - sb * rpq;
+                    if (qb >= 0) A[pa * k + qb] = sb * rpp + cb * rpq;
+                    if (qa >= 0) A[qa * k + pb] = cb * rqp - sb * rqq;
+                    if (qa >= 0 && qb >= 0) A[qa * k + qb] = sb * rqp + cb * rqq;
                 }
-            }
-            __syncthreads();
-            for (int e = threadIdx.x; e < (K / 2) * k; e += 256) {  // columns p, q of A and of Wk
-                const int pr = e / k, row = e - pr * k;
-                const int p = pp[pr], q = qq[pr];
-                if (q >= 0) {
-                    const double c = cs[pr], s = sn[pr];
-                    const double ap = A[row * k + p], aq = A[row * k + q];
-                    A[row * k + p] = c * ap - s * aq;
-                    A[row * k + q] = s * ap + c * aq;
-                    const double wp = Wk[row * k + p], wq = Wk[row * k + q];
-                    Wk[row * k + p] = c * wp - s * wq;
-                    Wk[row * k + q] = s * wp + c * wq;
+                // columns p_a, q_a of the accumulated rotations
+                if (qa >= 0) {
+                    for (int row = tb; row < k; row += 16) {
+                        const double wp = Wt[pa * k + row], wq = Wt[qa * k + row];
+                        Wt[pa * k + row] = ca * wp - sa * wq;
+                        Wt[qa * k + row] = sa * wp + ca * wq;
+                    }
                 }
             }
             __syncthreads();
@@ -293,7 +304,7 @@ __global__ __launch_bounds__(256) void jacobi_kernel(const double* __restrict__ 
             rank += (tj > ti) || (tj == ti && j < i);
         }
         theta[rank] = ti;
-        for (int r = 0; r < k; ++r) W[r * k + rank] = Wk[r * k + i];
+        for (int r = 0; r < k; ++r) W[r * k + rank] = Wt[i * k + r];
     }
 }
 
@@ -319,39 +330,129 @@ __global__ __launch_bounds__(256) void apply_small_kernel(const float* __restric
     }
 }
 
-// One workgroup per column: find the largest-magnitude entry (first on ties), flip if negative.
-__global__ __launch_bounds__(256) void fix_signs_kernel(float* __restrict__ V, int64_t N, int kc) {
-    __shared__ float s_abs[256];
-    __shared__ long long s_idx[256];
-    __shared__ float s_sign;
-    const int c = blockIdx.x;
-    float best = -1.0f;
-    long long bi = 0;
-    for (int64_t i = threadIdx.x; i < N; i += 256) {
-        const float a = fabsf(V[i * kc + c]);
-        if (a > best) {
-            best = a;
-            bi = i;
-        }
+// The same product on the matrix cores for k a multiple of 16, k <= 64, kout <= 64, rows of A 16-byte aligned: a wave
+// takes tiles of 16 rows; v_mfma_f64_16x16x4_f64 contracts 4 columns of A per instruction.  Lane l = (g = l / 16,
+// r = l % 16) loads A[i0 + r][16 jj + 4 g .. + 3] as one 16-byte load per jj, which fixes the order in which the
+// columns are contracted: instruction j = 4 jj + t handles columns 16 jj + 4 g' + t (g' = 0..3).  The matching
+// entries of T (one per instruction and 16-column output tile) stay in registers for all tiles of the wave.
+// Result register v of lane l is Out[i0 + g + 4 v][16 w + r].
+template <int KB, int NBO>
+__global__ __launch_bounds__(256) void apply_small_mfma_kernel(const float* __restrict__ A, int64_t N,
+                                                              const double* __restrict__ T, int kout,
+                                                              float* __restrict__ Out) {
+    constexpr int k = 16 * KB, KO = 16 * NBO;
+    extern __shared__ double app_sm[];  // [k][KO], columns beyond kout are zero
+    for (int e = threadIdx.x; e < k * KO; e += 256) {
+        const int p = e / KO, c = e - p * KO;
+        app_sm[e] = c < kout ? T[p * k + c] : 0.0;
     }
-    s_abs[threadIdx.x] = best;
-    s_idx[threadIdx.x] = bi;
     __syncthreads();
-    for (int off = 128; off > 0; off >>= 1) {
-        if (threadIdx.x < off) {
-            const float oa = s_abs[threadIdx.x + off];
-            const long long oi = s_idx[threadIdx.x + off];
-            if (oa > s_abs[threadIdx.x] || (oa == s_abs[threadIdx.x] && oi < s_idx[threadIdx.x])) {
-                s_abs[threadIdx.x] = oa;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane >> 4, r = lane & 15;
+    double tb[4 * KB][NBO];
+#pragma unroll
+    for (int j = 0; j < 4 * KB; ++j)
+#pragma unroll
+        for (int w = 0; w < NBO; ++w) tb[j][w] = app_sm[(16 * (j / 4) + 4 * g + (j % 4)) * KO + 16 * w + r];
+    const int64_t tiles = (N + 15) / 16;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < tiles; tile += (int64_t)gridDim.x * 4) {
+        const int64_t i0 = tile * 16;
+        const bool live = i0 + r < N;
+        float4 av[KB];
+#pragma unroll
+        for (int jj = 0; jj < KB; ++jj)
+            av[jj] = live ? *reinterpret_cast<const float4*>(A + (i0 + r) * k + 16 * jj + 4 * g) : float4{0.f, 0.f, 0.f, 0.f};
+        double4_t acc[NBO];
+#pragma unroll
+        for (int w = 0; w < NBO; ++w) acc[w] = double4_t{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int jj = 0; jj < KB; ++jj) {
+            const double a4[4] = {(double)av[jj].x, (double)av[jj].y, (double)av[jj].z, (double)av[jj].w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int w = 0; w < NBO; ++w)
+                    acc[w] = __builtin_amdgcn_mfma_f64_16x16x4f64(a4[t], tb[4 * jj + t][w], acc[w], 0, 0, 0);
+        }
+#pragma unroll
+        for (int w = 0; w < NBO; ++w)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int64_t row = i0 + g + 4 * v;
+                const int col = 16 * w + r;
+                if (row < N && col < kout) Out[row * kout + col] = (float)acc[w][v];
+            }
+    }
+}
+
+// Sign convention, step 1: per workgroup (a range of rows) and column, the entry of largest magnitude (the first
+// one on ties) with its row.  Thread t takes column t % kpad of rows g, g + 256 / kpad, ... (kpad = kc rounded
+// up to a power of two), so a wave reads whole rows.
+constexpr int kSignBlocks = 256;
+
+__global__ __launch_bounds__(256) void sign_partial_kernel(const float* __restrict__ V, int64_t N, int kc, int kpad,
+                                                          int64_t rows_per_block, float* __restrict__ best_val,
+                                                          long long* __restrict__ best_row) {
+    __shared__ float s_val[256];
+    __shared__ long long s_idx[256];
+    const int c = threadIdx.x & (kpad - 1), g = threadIdx.x / kpad, G = 256 / kpad;
+    const int64_t i_begin = (int64_t)blockIdx.x * rows_per_block, i_end = min(N, i_begin + rows_per_block);
+    float best = 0.0f, best_abs = -1.0f;
+    long long bi = i_begin;
+    if (c < kc)
+        for (int64_t i = i_begin + g; i < i_end; i += G) {
+            const float v = V[i * kc + c], a = fabsf(v);
+            if (a > best_abs) {
+                best_abs = a;
+                best = v;
+                bi = i;
+            }
+        }
+    s_val[threadIdx.x] = best;
+    s_idx[threadIdx.x] = best_abs < 0.0f ? -1 : bi;   // -1: nothing seen
+    __syncthreads();
+    for (int off = G >> 1; off > 0; off >>= 1) {
+        if (g < off) {
+            const int o = threadIdx.x + off * kpad;
+            const float ov = s_val[o], mv = s_val[threadIdx.x];
+            const long long oi = s_idx[o], mi = s_idx[threadIdx.x];
+            if (oi >= 0 && (mi < 0 || fabsf(ov) > fabsf(mv) || (fabsf(ov) == fabsf(mv) && oi < mi))) {
+                s_val[threadIdx.x] = ov;
                 s_idx[threadIdx.x] = oi;
             }
         }
         __syncthreads();
     }
-    if (threadIdx.x == 0) s_sign = V[s_idx[0] * kc + c] < 0.0f ? -1.0f : 1.0f;
+    if (g == 0 && c < kc) {
+        best_val[(int64_t)blockIdx.x * kc + c] = s_val[threadIdx.x];
+        best_row[(int64_t)blockIdx.x * kc + c] = s_idx[threadIdx.x];
+    }
+}
+
+// Step 2: every workgroup picks each column's winner among the partial results (ranges are in ascending row
+// order, so a strict comparison keeps the first on ties) and negates its rows of the columns whose winner is
+// negative.  The decision uses the values recorded in step 1, never V itself, which other workgroups are changing.
+__global__ __launch_bounds__(256) void sign_apply_kernel(float* __restrict__ V, int64_t N, int kc, int kpad,
+                                                        int64_t rows_per_block, int blocks,
+                                                        const float* __restrict__ best_val,
+                                                        const long long* __restrict__ best_row) {
+    __shared__ float s_sign[256];
+    if ((int)threadIdx.x < kc) {
+        float best = 0.0f, best_abs = -1.0f;
+        for (int b = 0; b < blocks; ++b) {
+            const float v = best_val[(int64_t)b * kc + threadIdx.x];
+            if (best_row[(int64_t)b * kc + threadIdx.x] >= 0 && fabsf(v) > best_abs) {
+                best_abs = fabsf(v);
+                best = v;
+            }
+        }
+        s_sign[threadIdx.x] = best < 0.0f ? -1.0f : 1.0f;
+    }
     __syncthreads();
-    if (s_sign < 0.0f)
-        for (int64_t i = threadIdx.x; i < N; i += 256) V[i * kc + c] = -V[i * kc + c];
+    const int c = threadIdx.x & (kpad - 1), g = threadIdx.x / kpad, G = 256 / kpad;
+    if (c >= kc || s_sign[c] > 0.0f) return;
+    const int64_t i_begin = (int64_t)blockIdx.x * rows_per_block, i_end = min(N, i_begin + rows_per_block);
+    for (int64_t i = i_begin + g; i < i_end; i += G) V[i * kc + c] = -V[i * kc + c];
 }
 
 template <class K>
@@ -366,7 +467,8 @@ hipError_t SmallWs::alloc(int64_t N, int k) {
     gram_blocks = (int)std::min<int64_t>(512, ceil_div(ceil_div(N, 64), kGramWaves) * kGramWaves);  // wave slots
     const size_t kk = (size_t)k * k;
     const size_t doubles = (size_t)gram_blocks * kk + 3 * kk + (size_t)k + kk /*jacobi work*/;
-    hipError_t e = buf.alloc(doubles * sizeof(double) + 64);
+    const size_t sign_entries = (size_t)kSignBlocks * k;
+    hipError_t e = buf.alloc(doubles * sizeof(double) + 64 + sign_entries * (sizeof(long long) + sizeof(float)));
     if (e != hipSuccess) return e;
     double* p = buf.as<double>();
     partial = p;
@@ -381,6 +483,9 @@ hipError_t SmallWs::alloc(int64_t N, int k) {
     p += k;
     p += kk;  // jacobi work matrix sits at theta + k
     flag = (int*)p;
+    p += 8;  // 64 bytes for the status word
+    sign_row = (long long*)p;
+    sign_val = (float*)(sign_row + sign_entries);
     return hipMemset(flag, 0, sizeof(int));
 }
 
@@ -424,15 +529,43 @@ int chol_inverse(const double* G, int k, SmallWs& ws, double* T, hipStream_t st)
 int jacobi_eigh(const double* H, int k, SmallWs& ws, double* theta, double* W, hipStream_t st) {
     const int K = (k + 1) & ~1;
     const size_t lds = sizeof(double) * ((size_t)k * k + K) + sizeof(int) * K;
-    RFX_HIP(allow_lds(jacobi_kernel, lds));
-    double* work = ws.theta + k;  // [k][k] accumulated rotations
+    const size_t lds_w = lds + sizeof(double) * (size_t)k * k;   // with the accumulated rotations in LDS as well
+    double* work = ws.theta + k;  // [k][k] accumulated rotations when they do not fit LDS
     const int sweeps = 16;  // upper bound; the kernel stops when the off-diagonal mass is below 1e-30 of the diagonal
-    hipLaunchKernelGGL(jacobi_kernel, dim3(1), dim3(256), lds, st, H, k, sweeps, work, theta, W);
+    if (lds_w <= 144 * 1024) {
+        RFX_HIP(allow_lds(jacobi_kernel<true>, lds_w));
+        hipLaunchKernelGGL(jacobi_kernel<true>, dim3(1), dim3(256), lds_w, st, H, k, sweeps, work, theta, W);
+    } else {
+        RFX_HIP(allow_lds(jacobi_kernel<false>, lds));
+        hipLaunchKernelGGL(jacobi_kernel<false>, dim3(1), dim3(256), lds, st, H, k, sweeps, work, theta, W);
+    }
     RFX_LAUNCH_CHECK("jacobi_kernel");
     return RFX_OK;
 }
 
+template <int KB, int NBO>
+int launch_apply_mfma(const float* A, int64_t N, const double* T, int kout, float* Out, hipStream_t st) {
+    const size_t lds = sizeof(double) * (size_t)(16 * KB) * (16 * NBO);
+    const unsigned blocks = (unsigned)std::min<int64_t>(ceil_div(ceil_div(N, 16), 4), 512);
+    hipLaunchKernelGGL((apply_small_mfma_kernel<KB, NBO>), dim3(blocks), dim3(256), lds, st, A, N, T, kout, Out);
+    RFX_LAUNCH_CHECK("apply_small_mfma_kernel");
+    return RFX_OK;
+}
+
 int apply_small(const float* A, int64_t N, int k, const double* T, int kout, float* Out, hipStream_t st) {
+    if (k % 16 == 0 && k <= 64 && kout >= 1 && kout <= 64 && reinterpret_cast<uintptr_t>(A) % 16 == 0) {
+        const int code = (k / 16) * 10 + (kout + 15) / 16;
+        switch (code) {
+#define RFX_APPLY(kb, nbo) \
+    case kb * 10 + nbo:    \
+        return launch_apply_mfma<kb, nbo>(A, N, T, kout, Out, st);
+            RFX_APPLY(1, 1) RFX_APPLY(2, 1) RFX_APPLY(2, 2) RFX_APPLY(3, 1) RFX_APPLY(3, 2) RFX_APPLY(3, 3)
+            RFX_APPLY(4, 1) RFX_APPLY(4, 2) RFX_APPLY(4, 3) RFX_APPLY(4, 4)
+#undef RFX_APPLY
+            default:
+                break;  // kout > k does not occur; the general kernel takes it
+        }
+    }
     const size_t lds = sizeof(double) * (size_t)k * kout + sizeof(float) * kApplyRows * (size_t)k;
     RFX_HIP(allow_lds(apply_small_kernel, lds));
     const unsigned blocks = (unsigned)std::min<int64_t>(ceil_div(N, kApplyRows), 2048);
@@ -456,9 +589,17 @@ int orthonormalise(const float* Y, int64_t N, int k, SmallWs& ws, float* Z, floa
     return apply_small(Z, N, k, ws.T, k, V, st);
 }
 
-int fix_signs(float* V, int64_t N, int kc, hipStream_t st) {
-    hipLaunchKernelGGL(fix_signs_kernel, dim3(kc), dim3(256), 0, st, V, N, kc);
-    RFX_LAUNCH_CHECK("fix_signs_kernel");
+int fix_signs(float* V, int64_t N, int kc, SmallWs& ws, hipStream_t st) {
+    if (kc < 1 || kc > kMaxRank || !ws.sign_val) return fail(RFX_ERR_INVALID_ARG, "fix_signs: kc=%d", kc);
+    int kpad = 1;
+    while (kpad < kc) kpad <<= 1;
+    const int64_t rows_per_block = ceil_div(N, kSignBlocks);
+    const int blocks = (int)ceil_div(N, rows_per_block);
+    hipLaunchKernelGGL(sign_partial_kernel, dim3(blocks), dim3(256), 0, st, V, N, kc, kpad, rows_per_block, ws.sign_val,
+                       ws.sign_row);
+    hipLaunchKernelGGL(sign_apply_kernel, dim3(blocks), dim3(256), 0, st, V, N, kc, kpad, rows_per_block, blocks,
+                       ws.sign_val, ws.sign_row);
+    RFX_LAUNCH_CHECK("fix_signs kernels");
     return RFX_OK;
 }
 

@@ -103,7 +103,7 @@ int rfx_prox_lowrank(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bo
     RFX_HIP(hipMemcpyAsync(V, Z, sizeof(float) * (size_t)N * k, hipMemcpyDeviceToDevice, st));
     hipLaunchKernelGGL(theta_to_float_kernel, dim3((k + 63) / 64), dim3(64), 0, st, ws.theta, k, eigvals);
     RFX_LAUNCH_CHECK("theta_to_float_kernel");
-    if ((rc = rfx::fix_signs(V, N, k, st)) != RFX_OK) return rc;
+    if ((rc = rfx::fix_signs(V, N, k, ws, st)) != RFX_OK) return rc;
     if (Q && (rc = quantise(V, eigvals, N, k, Q, scales, st)) != RFX_OK) return rc;
 
     int h_flag = 0;

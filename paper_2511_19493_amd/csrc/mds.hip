@@ -482,7 +482,7 @@ int mds3d_core(const float* A, int64_t N, int32_t k, int dissim_mode, int32_t m,
     }
     // Ritz vectors of the three largest values: coords = X W[:, 0:3] scaled by sqrt(theta)
     if ((rc = rfx::apply_small(X, N, m, ws.W, 3, coords, st)) != RFX_OK) return rc;
-    if ((rc = rfx::fix_signs(coords, N, 3, st)) != RFX_OK) return rc;
+    if ((rc = rfx::fix_signs(coords, N, 3, ws, st)) != RFX_OK) return rc;
     hipLaunchKernelGGL(mds_coords_kernel, dim3((unsigned)rfx::ceil_div(N * 3, 256)), dim3(256), 0, st, coords, ws.theta, N,
                        eigvals);
     RFX_LAUNCH_CHECK("mds_coords_kernel");
