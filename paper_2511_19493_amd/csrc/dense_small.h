@@ -12,7 +12,7 @@ constexpr int kMaxRank = 128;  // largest block width the small-matrix kernels a
 
 // Scratch shared by the wrappers below, sized for N rows and width k.
 struct SmallWs {
-    double* partial = nullptr;  // [gram_blocks][k][k], one per wave of the Gram kernel
+    double* partial = nullptr;  // [gram_blocks][k][k], one per workgroup of the Gram kernel
     double* G = nullptr;        // [k][k]
     double* T = nullptr;        // [k][k]
     double* theta = nullptr;    // [k]

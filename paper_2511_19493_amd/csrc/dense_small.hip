@@ -11,79 +11,115 @@ constexpr int kApplyRows = 32;  // rows per workgroup step of the tall-times-sma
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
 
-// partial[wave slot][p][q] = sum over the wave's rows of A[i][p] * Bm[i][q] in float64 on the
+// partial[workgroup][p][q] = sum over the workgroup's rows of A[i][p] * Bm[i][q] in float64 on the
 // matrix cores: v_mfma_f64_16x16x4_f64 computes D(16x16) += Aop(16x4) Bop(4x16), 4 rows of the
 // tall blocks per instruction.  Operand layout of a 64-lane wave: lane l supplies
 // Aop[l % 16][l / 16] and Bop[l / 16][l % 16]; the result register v (0..3) of lane l is
 // D[l / 16 + 4 v][l % 16].  With Aop[m][r] = A[i0 + r][16 u + m] and Bop[r][n] = Bm[i0 + r][16 w + n]
 // both operands of lane l are the element (row i0 + l / 16, column 16 * tile + l % 16) of their block:
 // 4 rows x 64 contiguous bytes per load.  A wave keeps PBC x NB output tiles (at most 16) in
-// registers and passes over its rows once per group of PBC tile rows.
-template <int NB>
+// registers and passes over its own row range once per group of PBC tile rows, with the loads of the
+// next 4 rows issued before the instructions of the current ones; the four waves of a workgroup add
+// their tiles up in LDS in wave order.  kSame (A and Bm are the same block): the product is symmetric
+// and only the tiles on and above the diagonal are computed and stored.
+template <int NB, bool kSame>
 __global__ __launch_bounds__(64 * kGramWaves) void gram_partial_kernel(const float* __restrict__ A,
                                                                       const float* __restrict__ Bm, int64_t N, int k,
                                                                       int64_t rows_per_wave,
                                                                       double* __restrict__ partial) {
+    extern __shared__ double gram_sm[];  // [k][k]
     constexpr int PBC = NB <= 4 ? NB : (16 / NB > 0 ? 16 / NB : 1);
-    const int lane = threadIdx.x & 63;
-    const int slot = blockIdx.x * kGramWaves + (threadIdx.x >> 6);
-    const int64_t i_begin = (int64_t)slot * rows_per_wave;
+    constexpr bool kShare = kSame && PBC == NB;  // the left operands are the right ones
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int slot = blockIdx.x * kGramWaves + wave;
+    const int64_t i_begin = min(N, (int64_t)slot * rows_per_wave);
     const int64_t i_end = min(N, i_begin + rows_per_wave);
     const int r = lane >> 4, c = lane & 15;
-    double* out = partial + (int64_t)slot * k * k;
     for (int pg = 0; pg < NB; pg += PBC) {
         double4_t acc[PBC][NB];
 #pragma unroll
         for (int u = 0; u < PBC; ++u)
 #pragma unroll
             for (int w = 0; w < NB; ++w) acc[u][w] = double4_t{0.0, 0.0, 0.0, 0.0};
-        for (int64_t i0 = i_begin; i0 < i_end; i0 += 4) {
+        float a_next[PBC], b_next[NB];
+        auto load_rows = [&](int64_t i0) {
             const int64_t row = i0 + r;
             const bool live = row < i_end;
-            double a[PBC], b[NB];
-#pragma unroll
-            for (int u = 0; u < PBC; ++u) {
-                const int col = 16 * (pg + u) + c;
-                a[u] = (live && pg + u < NB && col < k) ? (double)A[row * k + col] : 0.0;
-            }
 #pragma unroll
             for (int w = 0; w < NB; ++w) {
                 const int col = 16 * w + c;
-                b[w] = (live && col < k) ? (double)Bm[row * k + col] : 0.0;
+                b_next[w] = (live && col < k) ? Bm[row * k + col] : 0.0f;
             }
+            if (!kShare) {
+#pragma unroll
+                for (int u = 0; u < PBC; ++u) {
+                    const int col = 16 * (pg + u) + c;
+                    a_next[u] = (live && pg + u < NB && col < k) ? A[row * k + col] : 0.0f;
+                }
+            }
+        };
+        load_rows(i_begin);
+        for (int64_t i0 = i_begin; i0 < i_end; i0 += 4) {
+            double a[PBC], b[NB];
+#pragma unroll
+            for (int w = 0; w < NB; ++w) b[w] = (double)b_next[w];
+#pragma unroll
+            for (int u = 0; u < PBC; ++u) a[u] = kShare ? b[u] : (double)a_next[u];
+            load_rows(i0 + 4);
 #pragma unroll
             for (int u = 0; u < PBC; ++u)
 #pragma unroll
-                for (int w = 0; w < NB; ++w) acc[u][w] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[w], acc[u][w], 0, 0, 0);
+                for (int w = 0; w < NB; ++w)
+                    if (!kSame || pg + u <= w)
+                        acc[u][w] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[w], acc[u][w], 0, 0, 0);
         }
+        for (int w4 = 0; w4 < kGramWaves; ++w4) {
+            if (wave == w4) {
 #pragma unroll
-        for (int u = 0; u < PBC; ++u)
+                for (int u = 0; u < PBC; ++u)
 #pragma unroll
-            for (int w = 0; w < NB; ++w)
+                    for (int w = 0; w < NB; ++w)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int p = 16 * (pg + u) + r + 4 * v, q = 16 * w + c;
-                    if (pg + u < NB && p < k && q < k) out[p * k + q] = acc[u][w][v];
-                }
+                        for (int v = 0; v < 4; ++v) {
+                            const int p = 16 * (pg + u) + r + 4 * v, q = 16 * w + c;
+                            if ((!kSame || pg + u <= w) && pg + u < NB && p < k && q < k)
+                                gram_sm[p * k + q] = (w4 == 0 ? 0.0 : gram_sm[p * k + q]) + acc[u][w][v];
+                        }
+            }
+            __syncthreads();
+        }
+    }
+    double* out = partial + (int64_t)blockIdx.x * k * k;
+    for (int e = threadIdx.x; e < k * k; e += 64 * kGramWaves) {
+        const int p = e / k, q = e - p * k;
+        if (!kSame || p / 16 <= q / 16) out[e] = gram_sm[e];
     }
 }
 
-// G[e] = sum over blocks of partial[block][e] (symmetrised on request).  16 consecutive lanes share
-// an entry: lane part p adds blocks p, p+16, ..., then the 16 partial sums are added pairwise in a
-// fixed order, so the result does not depend on scheduling.
+// G[e] = sum over workgroups of partial[workgroup][e].  sym: symmetrised, (x[p][q] + x[q][p]) / 2.  upper_only: the
+// 16 x 16 tiles below the diagonal were not stored (symmetric product); their entries are those of the mirrored tile,
+// and the symmetrisation only concerns the diagonal tiles.  16 consecutive lanes share an entry: lane part p adds
+// workgroups p, p+16, ..., then the 16 partial sums are added pairwise in a fixed order, so the result does not
+// depend on scheduling.
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ partial, int blocks, int k, int sym,
-                                                         double* __restrict__ G) {
+                                                         int upper_only, double* __restrict__ G) {
     const int e = blockIdx.x * 16 + (threadIdx.x >> 4);
     const int part = threadIdx.x & 15;
     const bool live = e < k * k;
-    const int p = live ? e / k : 0, q = live ? e - p * k : 0;
+    int p = live ? e / k : 0, q = live ? e - p * k : 0;
+    if (upper_only && p / 16 > q / 16) {
+        const int t = p;
+        p = q;
+        q = t;
+    }
+    const bool both = sym && (!upper_only || p / 16 == q / 16);
     double s = 0.0;
     for (int b = part; b < blocks; b += 16) {
         s += partial[(int64_t)b * k * k + p * k + q];
-        if (sym) s += partial[(int64_t)b * k * k + q * k + p];
+        if (both) s += partial[(int64_t)b * k * k + q * k + p];
     }
     for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 16);
-    if (live && part == 0) G[e] = sym ? 0.5 * s : s;
+    if (live && part == 0) G[e] = both ? 0.5 * s : s;
 }
 
 // One workgroup.  R (upper, G = R^T R) is formed in LDS by the right-looking Cholesky algorithm,
@@ -464,7 +500,7 @@ hipError_t allow_lds(K kern, size_t bytes) {
 }  // namespace
 
 hipError_t SmallWs::alloc(int64_t N, int k) {
-    gram_blocks = (int)std::min<int64_t>(512, ceil_div(ceil_div(N, 64), kGramWaves) * kGramWaves);  // wave slots
+    gram_blocks = (int)std::min<int64_t>(512, ceil_div(N, 64 * kGramWaves));  // workgroups of the Gram kernel
     const size_t kk = (size_t)k * k;
     const size_t doubles = (size_t)gram_blocks * kk + 3 * kk + (size_t)k + kk /*jacobi work*/;
     const size_t sign_entries = (size_t)kSignBlocks * k;
@@ -490,14 +526,23 @@ hipError_t SmallWs::alloc(int64_t N, int k) {
 }
 
 int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& ws, double* G, hipStream_t st) {
-    // every wave slot takes a multiple of 4 rows (one matrix instruction covers 4)
-    const int64_t rpw = ceil_div(ceil_div(N, ws.gram_blocks), 4) * 4;
-    const int blocks = (int)(ceil_div(ceil_div(N, rpw), kGramWaves) * kGramWaves);  // wave slots written (<= gram_blocks)
+    // every wave takes a multiple of 4 rows (one matrix instruction covers 4)
+    const int64_t rpw = ceil_div(ceil_div(N, (int64_t)ws.gram_blocks * kGramWaves), 4) * 4;
+    const int blocks = (int)ceil_div(N, rpw * kGramWaves);  // workgroups with rows (<= gram_blocks)
     const int NB = (k + 15) / 16;
-#define RFX_GRAM(nb)                                                                                                  \
-    case nb:                                                                                                          \
-        hipLaunchKernelGGL(gram_partial_kernel<nb>, dim3(blocks / kGramWaves), dim3(64 * kGramWaves), 0, st, A, Bm, N, k, \
-                           rpw, ws.partial);                                                                          \
+    const bool same = A == Bm;
+    const size_t lds = sizeof(double) * (size_t)k * k;
+#define RFX_GRAM(nb)                                                                                                 \
+    case nb:                                                                                                         \
+        if (same) {                                                                                                  \
+            RFX_HIP(allow_lds(gram_partial_kernel<nb, true>, lds));                                                  \
+            hipLaunchKernelGGL((gram_partial_kernel<nb, true>), dim3(blocks), dim3(64 * kGramWaves), lds, st, A, Bm, N, k, \
+                               rpw, ws.partial);                                                                     \
+        } else {                                                                                                     \
+            RFX_HIP(allow_lds(gram_partial_kernel<nb, false>, lds));                                                 \
+            hipLaunchKernelGGL((gram_partial_kernel<nb, false>), dim3(blocks), dim3(64 * kGramWaves), lds, st, A, Bm, N, k, \
+                               rpw, ws.partial);                                                                     \
+        }                                                                                                            \
         break;
     switch (NB) {
         RFX_GRAM(1) RFX_GRAM(2) RFX_GRAM(3) RFX_GRAM(4) RFX_GRAM(5) RFX_GRAM(6) RFX_GRAM(7) RFX_GRAM(8)
@@ -507,7 +552,7 @@ int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& w
 #undef RFX_GRAM
     RFX_LAUNCH_CHECK("gram_partial_kernel");
     hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)ceil_div(k * k, 16)), dim3(256), 0, st, ws.partial, blocks, k,
-                       sym ? 1 : 0, G);
+                       sym ? 1 : 0, same ? 1 : 0, G);
     RFX_LAUNCH_CHECK("gram_reduce_kernel");
     return RFX_OK;
 }
