@@ -40,12 +40,18 @@ __global__ __launch_bounds__(256) void col_sums_partial_kernel(const float* __re
     }
 }
 
-__global__ void col_sums_reduce_kernel(const double* __restrict__ partial, int blocks, int m, double* __restrict__ sums) {
-    const int c = threadIdx.x;
-    if (c >= m) return;
+// sums[c] = sum over blocks of partial[block][c].  Eight lanes share a column (m <= 32): lane part p adds blocks
+// p, p + 8, ..., then the eight sums are added pairwise in a fixed order.
+__global__ __launch_bounds__(256) void col_sums_reduce_kernel(const double* __restrict__ partial, int blocks, int m,
+                                                             double* __restrict__ sums) {
+    const int c = threadIdx.x >> 3, part = threadIdx.x & 7;
     double s = 0.0;
-    for (int b = 0; b < blocks; ++b) s += partial[(int64_t)b * m + c];
-    sums[c] = s;
+    if (c < m) {
+#pragma unroll 4
+        for (int b = part; b < blocks; b += 8) s += partial[(int64_t)b * m + c];
+    }
+    for (int off = 4; off > 0; off >>= 1) s += __shfl_xor(s, off, 8);
+    if (c < m && part == 0) sums[c] = s;
 }
 
 // For column c = blockIdx.y, over the block's rows, with u_i = X[i][c] - mean_c:
@@ -277,6 +283,68 @@ __global__ __launch_bounds__(256) void mds_quad_kernel(const float* __restrict__
     }
 }
 
+// The SQUARED quadratic form on the matrix cores for k a multiple of 16, k <= 64, rows of A 16-byte aligned:
+// B = A M_c by v_mfma_f64_16x16x4_f64 on tiles of 16 rows, then Z[i][c] = sum_q (B[i][q] - 2 t_c[q]) A[i][q].
+// Lane l = (g = l / 16, r = l % 16) loads A[i0 + r][16 jj + 4 g .. + 3] with one 16-byte load per jj; instruction
+// j = 4 jj + t contracts columns 16 jj + 4 g' + t (g' = 0..3) and the matching entries of M_c stay in registers for
+// all tiles of the wave.  Result register v of lane l is B[i0 + g + 4 v][16 w + r]; the entries of A at those
+// positions are read again (they are in the first-level cache) and the 16 lanes of a row group are summed.
+template <int KB>
+__global__ __launch_bounds__(256) void mds_quad_mfma_kernel(const float* __restrict__ A, const double* __restrict__ M,
+                                                           const double* __restrict__ T, int64_t N, int m,
+                                                           float* __restrict__ Z) {
+    constexpr int k = 16 * KB;
+    extern __shared__ double quad_sm[];  // [k][k] M_c, then [k] t_c
+    const int c = blockIdx.y;
+    for (int e = threadIdx.x; e < k * k; e += 256) quad_sm[e] = M[(int64_t)c * k * k + e];
+    for (int e = threadIdx.x; e < k; e += 256) quad_sm[k * k + e] = T[(int64_t)c * k + e];
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane >> 4, r = lane & 15;
+    double mb[4 * KB][KB], t2[KB];
+#pragma unroll
+    for (int j = 0; j < 4 * KB; ++j)
+#pragma unroll
+        for (int w = 0; w < KB; ++w) mb[j][w] = quad_sm[(16 * (j / 4) + 4 * g + (j % 4)) * k + 16 * w + r];
+#pragma unroll
+    for (int w = 0; w < KB; ++w) t2[w] = 2.0 * quad_sm[k * k + 16 * w + r];
+    const int64_t tiles = (N + 15) / 16;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < tiles; tile += (int64_t)gridDim.x * 4) {
+        const int64_t i0 = tile * 16;
+        const bool live = i0 + r < N;
+        float4 av[KB];
+#pragma unroll
+        for (int jj = 0; jj < KB; ++jj)
+            av[jj] = live ? *reinterpret_cast<const float4*>(A + (i0 + r) * k + 16 * jj + 4 * g) : float4{0.f, 0.f, 0.f, 0.f};
+        float ad[4][KB];  // A at the positions of the result registers
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+            for (int w = 0; w < KB; ++w) ad[v][w] = i0 + g + 4 * v < N ? A[(i0 + g + 4 * v) * k + 16 * w + r] : 0.0f;
+        mds_double4_t acc[KB];
+#pragma unroll
+        for (int w = 0; w < KB; ++w) acc[w] = mds_double4_t{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int jj = 0; jj < KB; ++jj) {
+            const double a4[4] = {(double)av[jj].x, (double)av[jj].y, (double)av[jj].z, (double)av[jj].w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int w = 0; w < KB; ++w)
+                    acc[w] = __builtin_amdgcn_mfma_f64_16x16x4f64(a4[t], mb[4 * jj + t][w], acc[w], 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            double z = 0.0;
+#pragma unroll
+            for (int w = 0; w < KB; ++w) z += (acc[w][v] - t2[w]) * (double)ad[v][w];
+            for (int off = 8; off > 0; off >>= 1) z += __shfl_xor(z, off, 16);
+            const int64_t row = i0 + g + 4 * v;
+            if (r == 0 && row < N) Z[row * m + c] = (float)z;
+        }
+    }
+}
+
 // Y[i][c] = -1/2 (Z[i][c] - mean_c(Z))
 __global__ __launch_bounds__(256) void mds_center_kernel(const float* __restrict__ Z, const double* __restrict__ colsum,
                                                         int64_t N, int m, float* __restrict__ Y) {
@@ -311,7 +379,7 @@ struct MdsWs {
 int col_sums(const float* X, int64_t N, int m, MdsWs& w, hipStream_t st) {
     hipLaunchKernelGGL(col_sums_partial_kernel, dim3(w.blocks), dim3(256), 0, st, X, N, m, w.rows_per_block,
                        w.colsum_partial);
-    hipLaunchKernelGGL(col_sums_reduce_kernel, dim3(1), dim3(64), 0, st, w.colsum_partial, w.blocks, m, w.colsum);
+    hipLaunchKernelGGL(col_sums_reduce_kernel, dim3(1), dim3(256), 0, st, w.colsum_partial, w.blocks, m, w.colsum);
     RFX_LAUNCH_CHECK("col_sums");
     return RFX_OK;
 }
@@ -344,7 +412,17 @@ int apply_gram_nb(const float* A, int64_t N, int k, int m, int squared, const fl
                            mom_blocks, m, k, w.T);
         RFX_LAUNCH_CHECK("moments_reduce_kernel");
     }
-    {
+    if (squared && k % 16 == 0 && k <= 64 && reinterpret_cast<uintptr_t>(A) % 16 == 0) {
+        const size_t lds = sizeof(double) * ((size_t)k * k + k);
+        dim3 grid((unsigned)std::min<int64_t>(rfx::ceil_div(rfx::ceil_div(N, 16), 4), 64), m);
+        switch (k / 16) {
+            case 1: hipLaunchKernelGGL(mds_quad_mfma_kernel<1>, grid, dim3(256), lds, st, A, w.M, w.T, N, m, Z); break;
+            case 2: hipLaunchKernelGGL(mds_quad_mfma_kernel<2>, grid, dim3(256), lds, st, A, w.M, w.T, N, m, Z); break;
+            case 3: hipLaunchKernelGGL(mds_quad_mfma_kernel<3>, grid, dim3(256), lds, st, A, w.M, w.T, N, m, Z); break;
+            default: hipLaunchKernelGGL(mds_quad_mfma_kernel<4>, grid, dim3(256), lds, st, A, w.M, w.T, N, m, Z); break;
+        }
+        RFX_LAUNCH_CHECK("mds_quad_mfma_kernel");
+    } else {
         const bool small_tile = k > 96;
         const int RT = small_tile ? 32 : 64;
         const size_t lds = sizeof(double) * ((squared ? (size_t)k * k : 0) + k) + sizeof(float) * (size_t)RT * k;
