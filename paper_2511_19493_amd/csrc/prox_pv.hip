@@ -43,17 +43,19 @@ constexpr int kBigWaves = 16;
 constexpr int kHistLdsLeaves = 16384;  // largest Lb whose histogram fits LDS (64 KB)
 
 // Histogram of one part (blockIdx.x) of one tree (blockIdx.y) and the slot ids of its samples.
-// kLds: the part's histogram is built in LDS and stored whole; otherwise `count` was zeroed and
-// takes global atomics.
-template <bool kLds>
+// kLds 1: the part's histogram is built in LDS, one 32-bit counter per leaf, and stored whole; kLds 2: the same
+// with two 16-bit counters per LDS word (parts shorter than 65,536 samples, so no counter can carry into its
+// neighbour); kLds 0: `count` was zeroed and takes global atomics.
+template <int kLds>
 __global__ __launch_bounds__(1024) void pv_hist_kernel(const uint32_t* __restrict__ leaf, int64_t N, int32_t Lb,
                                                       int64_t part_len, uint32_t* __restrict__ slot,
                                                       uint32_t* __restrict__ count, int* __restrict__ bad) {
     extern __shared__ uint32_t hist[];
     const int q = blockIdx.x, Q = gridDim.x, b = blockIdx.y;
     uint32_t* mine = count + ((int64_t)b * Q + q) * Lb;
+    const int words = kLds == 2 ? (Lb + 1) / 2 : Lb;
     if (kLds) {
-        for (int l = threadIdx.x; l < Lb; l += blockDim.x) hist[l] = 0;
+        for (int l = threadIdx.x; l < words; l += blockDim.x) hist[l] = 0;
         __syncthreads();
     }
     const int64_t lo = (int64_t)q * part_len, hi = min(N, lo + part_len);
@@ -64,14 +66,17 @@ __global__ __launch_bounds__(1024) void pv_hist_kernel(const uint32_t* __restric
             id = (uint32_t)Lb - 1;
         }
         slot[(int64_t)b * N + i] = (uint32_t)b * (uint32_t)Lb + id;
-        if (kLds)
+        if (kLds == 1)
             atomicAdd(&hist[id], 1u);
+        else if (kLds == 2)
+            atomicAdd(&hist[id >> 1], 1u << (16 * (id & 1)));
         else
             atomicAdd(&mine[id], 1u);
     }
     if (kLds) {
         __syncthreads();
-        for (int l = threadIdx.x; l < Lb; l += blockDim.x) mine[l] = hist[l];
+        for (int l = threadIdx.x; l < Lb; l += blockDim.x)
+            mine[l] = kLds == 2 ? (hist[l >> 1] >> (16 * (l & 1))) & 0xffffu : hist[l];
     }
 }
 
@@ -460,7 +465,8 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
     const int Q = (int)std::max<int64_t>(1, std::min<int64_t>(16, N / 4096));
     const int64_t part_len = rfx::ceil_div(rfx::ceil_div(N, Q), 64) * 64;
     const int64_t max_big = (int64_t)B * N / kBigLeaf + 1;
-    const bool lds_hist = Lb <= kHistLdsLeaves;
+    // 1: 32-bit LDS counters; 2: 16-bit pairs (up to 65,536 leaves, parts below 65,536 samples); 0: global atomics
+    const int lds_hist = Lb <= kHistLdsLeaves ? 1 : ((Lb <= 65536 && part_len < 65536) ? 2 : 0);
     rfx::DevBuf count, flags;
     hipError_t e = hipMalloc((void**)&p->d_slot, sizeof(uint32_t) * (size_t)B * (size_t)N);
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_perm, sizeof(uint32_t) * (size_t)B * (size_t)N);
@@ -470,6 +476,9 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
     if (e == hipSuccess) e = flags.alloc(2 * sizeof(int));
     if (e == hipSuccess && !lds_hist) e = hipMemsetAsync(count.p, 0, sizeof(uint32_t) * (size_t)n_slots * Q, st);
     if (e == hipSuccess) e = hipMemsetAsync(flags.p, 0, 2 * sizeof(int), st);
+    const size_t hist16_lds = sizeof(uint32_t) * (size_t)((Lb + 1) / 2);
+    if (e == hipSuccess && lds_hist == 2 && hist16_lds > 64 * 1024)
+        e = hipFuncSetAttribute((const void*)pv_hist_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hist16_lds);
     if (e != hipSuccess) {
         rfx_pv_plan_destroy(p);
         return rfx::fail(e == hipErrorOutOfMemory ? RFX_ERR_OOM : RFX_ERR_HIP, "rfx_pv_plan_create: %s", hipGetErrorString(e));
@@ -477,11 +486,14 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
     uint32_t* cnt = count.as<uint32_t>();
     int* bad = flags.as<int>();
     int* n_big = bad + 1;
-    if (lds_hist)
-        hipLaunchKernelGGL(pv_hist_kernel<true>, dim3(Q, B), dim3(1024), sizeof(uint32_t) * Lb, st, leaf, N, Lb, part_len,
+    if (lds_hist == 1)
+        hipLaunchKernelGGL(pv_hist_kernel<1>, dim3(Q, B), dim3(1024), sizeof(uint32_t) * Lb, st, leaf, N, Lb, part_len,
                            p->d_slot, cnt, bad);
+    else if (lds_hist == 2)
+        hipLaunchKernelGGL(pv_hist_kernel<2>, dim3(Q, B), dim3(1024), hist16_lds, st, leaf, N, Lb, part_len, p->d_slot, cnt,
+                           bad);
     else
-        hipLaunchKernelGGL(pv_hist_kernel<false>, dim3(Q, B), dim3(1024), 0, st, leaf, N, Lb, part_len, p->d_slot, cnt, bad);
+        hipLaunchKernelGGL(pv_hist_kernel<0>, dim3(Q, B), dim3(1024), 0, st, leaf, N, Lb, part_len, p->d_slot, cnt, bad);
     hipLaunchKernelGGL(pv_scan_kernel, dim3((unsigned)B), dim3(256), 0, st, cnt, N, B, Lb, Q, p->d_seg_start, p->d_big, n_big);
     hipLaunchKernelGGL(pv_scatter_kernel, dim3(Q, B), dim3(64), 0, st, p->d_slot, N, Lb, part_len, cnt, p->d_perm);
     int h_flags[2] = {0, 0};

@@ -121,6 +121,25 @@ def test_matvec_tiny_and_single_tree(torch_cuda):
         np.testing.assert_allclose(Y.cpu().numpy(), ref, rtol=1e-5, atol=1e-6)
 
 
+@pytest.mark.parametrize("N,bound", [(40000, 30001), (40000, 65536), (70000, 70000), (70000, 20000)])
+def test_matvec_with_many_leaves(torch_cuda, N, bound):
+    """Leaf bounds above what a 32-bit LDS histogram holds: 16-bit counter pairs in LDS (bound <= 65,536 and parts
+    below 65,536 samples) and global counters (beyond); most leaves hold one or two samples, a few are skipped."""
+    import oracle
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    B = 3
+    rng = np.random.default_rng(N + bound)
+    leaf = rng.integers(0, bound, size=(B, N)).astype(np.uint32)
+    leaf[0, :9000] = bound - 1            # one big leaf at the last id
+    leaf[1] = rng.permutation(N).astype(np.uint32) % np.uint32(bound)
+    V = rng.standard_normal((N, 8)).astype(np.float32)
+    ref = oracle.pv_implicit(leaf, V.astype(np.float64))
+    Y = rfx.prox_matvec(_dev(torch, leaf), bound, torch.from_numpy(V).cuda())
+    err = np.linalg.norm(Y.cpu().numpy().astype(np.float64) - ref) / np.linalg.norm(ref)
+    assert err <= 1e-5, err
+
+
 def test_matvec_with_one_huge_leaf(torch_cuda):
     """A leaf far above the big-leaf threshold next to many singletons (workgroup-per-leaf path)."""
     import oracle
