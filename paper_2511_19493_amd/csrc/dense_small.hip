@@ -164,41 +164,81 @@ __global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restr
     }
 }
 
-// The same factorisation with one barrier per column, for blocks small enough to hold two k x k arrays in
-// LDS: the Schur complement A is updated in place from its unscaled row j (A[r][c] -= A[j][r] A[j][c] / d),
-// while the scaled row goes to a separate array R, so the update and the scaling of a column do not have to
-// be separated by barriers, and every thread forms 1 / d itself instead of waiting for one thread's square root.
+// The same factorisation with one barrier per column and the Schur complement in registers, for k <= 16 NB16 small
+// enough that two k x k arrays fit LDS.  Thread (ty, tx) of a 16 x 16 arrangement owns the entries (ty + 16 a,
+// tx + 16 b) of the upper triangle for the whole factorisation.  Column step j: everybody reads the unscaled pivot
+// row j (published in LDS by its owners), forms 1 / d and its square root itself, updates its entries
+// (A[r][c] -= A[j][r] A[j][c] / d), and the owners of row j + 1 publish it into the other of two LDS slots; the
+// scaled row goes to the factor R.  Then the inverse of R by back substitution: lane c of the first wave owns
+// column c (columns are independent); the loops over r and p are the same for every lane, so R[r][p] is one
+// broadcast read and Ti[p][c] a conflict-free one; entries below the diagonal are written as zeros before they
+// are read.
+template <int NB16>
 __global__ __launch_bounds__(256) void chol_inverse_fast_kernel(const double* __restrict__ G, int k, double* __restrict__ T,
                                                                int* __restrict__ flag) {
     extern __shared__ double chol_sm[];
-    double* A = chol_sm;      // [k][k]
-    double* R = A + k * k;    // [k][k] upper factor, then [k] reciprocals of its diagonal
-    for (int e = threadIdx.x; e < k * k; e += 256) A[e] = G[e];
+    double* Ti = chol_sm;       // [k][k] inverse of the factor
+    double* R = Ti + k * k;     // [k][k] upper factor
+    double* dinv = R + k * k;   // [k] diagonal of G, later reciprocals of the diagonal of R
+    double* piv = dinv + k;     // [2][k] unscaled pivot rows of even and odd columns
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    double a[NB16][NB16];
+#pragma unroll
+    for (int ia = 0; ia < NB16; ++ia)
+#pragma unroll
+        for (int ib = 0; ib < NB16; ++ib) {
+            const int r = ty + 16 * ia, c = tx + 16 * ib;
+            a[ia][ib] = (r < k && c < k && c >= r) ? G[r * k + c] : 0.0;
+        }
+    for (int c = threadIdx.x; c < k; c += 256) dinv[c] = G[c * k + c];
+    if (ty == 0) {
+#pragma unroll
+        for (int ib = 0; ib < NB16; ++ib)
+            if (tx + 16 * ib < k) piv[tx + 16 * ib] = a[0][ib];
+    }
     __syncthreads();
     double scale = 0.0;
-    for (int j = 0; j < k; ++j) scale = fmax(scale, A[j * k + j]);
-    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    for (int j = 0; j < k; ++j) scale = fmax(scale, dinv[j]);
     for (int j = 0; j < k; ++j) {
-        double d = A[j * k + j];
+        const double* pr = piv + (j & 1) * k;
+        double d = pr[j];
         if (!(d > scale * 1e-28)) {
             if (threadIdx.x == 0) *flag = 1;  // numerically rank-deficient block
             d = scale > 0.0 ? scale * 1e-28 : 1.0;
         }
         const double inv = 1.0 / d, rs = sqrt(inv);
-        for (int c = j + (int)threadIdx.x; c < k; c += 256) R[j * k + c] = (c == j) ? d * rs : A[j * k + c] * rs;
-        for (int r = j + 1 + ty; r < k; r += 16) {
-            const double f = A[j * k + r] * inv;
-            for (int c = j + 1 + tx; c < k; c += 16)
-                if (c >= r) A[r * k + c] -= f * A[j * k + c];
+        if ((int)threadIdx.x >= j && (int)threadIdx.x < k)
+            R[j * k + threadIdx.x] = ((int)threadIdx.x == j) ? d * rs : pr[threadIdx.x] * rs;
+        double fr[NB16], pc[NB16];
+#pragma unroll
+        for (int ia = 0; ia < NB16; ++ia) {
+            const int r = ty + 16 * ia;
+            fr[ia] = (r > j && r < k) ? pr[r] * inv : 0.0;
+        }
+#pragma unroll
+        for (int ib = 0; ib < NB16; ++ib) {
+            const int c = tx + 16 * ib;
+            pc[ib] = (c > j && c < k) ? pr[c] : 0.0;
+        }
+#pragma unroll
+        for (int ia = 0; ia < NB16; ++ia)
+#pragma unroll
+            for (int ib = 0; ib < NB16; ++ib) a[ia][ib] -= fr[ia] * pc[ib];
+        const int jr = j + 1;
+        if (jr < k && ty == (jr & 15)) {
+            double* pw = piv + (jr & 1) * k;
+#pragma unroll
+            for (int ib = 0; ib < NB16; ++ib) {
+                double v = 0.0;
+#pragma unroll
+                for (int ia = 0; ia < NB16; ++ia)
+                    if (ia == (jr >> 4)) v = a[ia][ib];
+                const int c = tx + 16 * ib;
+                if (c >= jr && c < k) pw[c] = v;
+            }
         }
         __syncthreads();
     }
-    // Inverse of the upper factor by back substitution, built in the array the Schur complement no longer needs.
-    // Lane c of the first wave owns column c (columns are independent); the loops over r and p are the same for
-    // every lane, so R[r][p] is one broadcast read and Ti[p][c] a conflict-free one; entries below the diagonal
-    // are written as zeros before they are read.
-    double* Ti = A;
-    double* dinv = R + k * k;  // [k] reciprocals of the diagonal of R
     for (int c = threadIdx.x; c < k; c += 256) dinv[c] = 1.0 / R[c * k + c];
     __syncthreads();
     if (threadIdx.x < 64) {
@@ -221,7 +261,6 @@ __global__ __launch_bounds__(256) void chol_inverse_fast_kernel(const double* __
     __syncthreads();
     for (int e = threadIdx.x; e < k * k; e += 256) T[e] = Ti[e];
 }
-
 
 // One workgroup: cyclic Jacobi on a symmetric k x k matrix held in LDS.  The rotations of one round-robin step
 // act on disjoint index pairs; with pair a = (p_a, q_a) and pair b = (p_b, q_b), the update J^T A J changes the
@@ -560,9 +599,18 @@ int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& w
 int chol_inverse(const double* G, int k, SmallWs& ws, double* T, hipStream_t st) {
     const size_t lds = sizeof(double) * (size_t)k * k;
     if (2 * lds <= 128 * 1024) {
-        const size_t fast_lds = 2 * lds + sizeof(double) * (size_t)k;  // Schur complement / inverse, factor, 1 / diagonal
-        RFX_HIP(allow_lds(chol_inverse_fast_kernel, fast_lds));
-        hipLaunchKernelGGL(chol_inverse_fast_kernel, dim3(1), dim3(256), fast_lds, st, G, k, T, ws.flag);
+        const size_t fast_lds = 2 * lds + sizeof(double) * 3 * (size_t)k;  // inverse, factor, diagonal, two pivot rows
+#define RFX_CHOL(nb)                                                                                             \
+    case nb:                                                                                                     \
+        RFX_HIP(allow_lds(chol_inverse_fast_kernel<nb>, fast_lds));                                              \
+        hipLaunchKernelGGL(chol_inverse_fast_kernel<nb>, dim3(1), dim3(256), fast_lds, st, G, k, T, ws.flag);    \
+        break;
+        switch ((k + 15) / 16) {
+            RFX_CHOL(1) RFX_CHOL(2) RFX_CHOL(3) RFX_CHOL(4) RFX_CHOL(5)
+            default:
+                RFX_CHOL(6)
+        }
+#undef RFX_CHOL
     } else {
         RFX_HIP(allow_lds(chol_inverse_kernel, lds));
         hipLaunchKernelGGL(chol_inverse_kernel, dim3(1), dim3(256), lds, st, G, k, T, ws.flag);
