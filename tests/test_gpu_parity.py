@@ -214,6 +214,7 @@ def _align(coords, ref, lam):
 
 
 @pytest.mark.parametrize("which,k,mode", [("cfg1", 16, "squared"), ("cfg1", 16, "linear"), ("small2", 32, "squared"),
+                                          ("small2", 48, "squared"), ("small2", 64, "squared"), ("small2", 64, "linear"),
                                           ("small2", 100, "squared")])
 def test_mds3d_against_dense_torgerson_scaling(torch_cuda, request, which, k, mode):
     import oracle
