@@ -509,13 +509,18 @@ __global__ __launch_bounds__(256) void outlier_finalise_kernel(const double* __r
 #ifndef RFX_PLAIN_WAVES
 #define RFX_PLAIN_WAVES 4
 #endif
-// waves per SIMD the register allocation aims for: the plain kernel's main loop fits 128 VGPRs
-#define RFX_MIN_WAVES(oob) RFX_PLAIN_WAVES
+// Waves per SIMD the register allocation aims for.  The main loop fits 128 VGPRs up to 14 planes (12 with an in-bag
+// word per sample as well); beyond that the compiler spills a few registers.  Measured at N = 60,000, B = 512: three
+// waves without spills beat four with them for the plain pass at 15 and 16 planes (18.6 -> 17.9 ms, 20.5 -> 17.0 ms)
+// and for the fused pass at 16 (22.8 -> 21.3 ms); everywhere else four waves stay ahead (sparse pass at 16 planes:
+// 14.7 ms against 16.7 ms).
+#define RFX_MIN_WAVES(planes, mode) \
+    ((((mode) == 0 && (planes) >= 15) || ((mode) == 4 && (planes) >= 16)) ? 3 : RFX_PLAIN_WAVES)
 
 // P = number of leaf-id bit planes, J = b samples per wave, kMode = what is counted and how it leaves.
 enum { kModePlain = 0, kModeOob = 1, kModeSparse = 2, kModeOutlier = 3, kModeBoth = 4 };
 template <int P, int J, int kMode>
-__global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(kMode == kModeOob)) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
+__global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(P, kMode)) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
                                                                  int32_t G, int32_t n_tile_rows, TileOut out, TileOut out2) {
     constexpr bool kOob = kMode == kModeOob;
     constexpr bool kBoth = kMode == kModeBoth;  // plain and out-of-bag counts in one pass; out2 takes the latter
