@@ -652,11 +652,11 @@ int apply_small(const float* A, int64_t N, int k, const double* T, int kout, flo
 #define RFX_APPLY(kb, nbo) \
     case kb * 10 + nbo:    \
         return launch_apply_mfma<kb, nbo>(A, N, T, kout, Out, st);
-            RFX_APPLY(1, 1) RFX_APPLY(2, 1) RFX_APPLY(2, 2) RFX_APPLY(3, 1) RFX_APPLY(3, 2) RFX_APPLY(3, 3)
-            RFX_APPLY(4, 1) RFX_APPLY(4, 2) RFX_APPLY(4, 3) RFX_APPLY(4, 4)
+            // square factors (Cholesky-QR, Ritz rotation) and the three coordinate columns of a 16- or 32-wide block
+            RFX_APPLY(1, 1) RFX_APPLY(2, 1) RFX_APPLY(2, 2) RFX_APPLY(3, 3) RFX_APPLY(4, 4)
 #undef RFX_APPLY
             default:
-                break;  // kout > k does not occur; the general kernel takes it
+                break;  // other shapes do not occur on the path; the general kernel takes them
         }
     }
     const size_t lds = sizeof(double) * (size_t)k * kout + sizeof(float) * kApplyRows * (size_t)k;

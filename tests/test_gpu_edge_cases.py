@@ -165,7 +165,7 @@ def test_lowrank_extreme_ranks(torch_cuda, small2):
     torch = torch_cuda
     leaf = small2["leaf"]
     B, N = leaf.shape
-    for k, T in ((1, 30), (40, 6), (80, 6), (128, 6)):   # 40, 80: not multiples of 16; 80, 128: beyond one 64-column tile
+    for k, T in ((1, 30), (40, 6), (80, 6), (96, 6), (112, 6), (128, 6)):   # 40, 80: not multiples of 16; 80..128: beyond one 64-column tile
         V0 = ri.start_block(N, k, seed=21 + k)
         lam_ref, V_ref = oracle.block_iteration(leaf, V0, T)
         lam, V, Q, s = rfx.prox_lowrank(_dev(torch, leaf), int(leaf.max()) + 1, torch.from_numpy(V0).cuda(), T)
@@ -229,7 +229,8 @@ def test_mds_small_blocks_and_linear_rank(torch_cuda, cfg1):
     N = leaf.shape[1]
     lam, V = oracle.block_iteration(leaf, ri.start_block(N, 8), 10)
     Qh, sh = oracle.quantise_int8(V, lam)
-    for m, mode, omode in ((3, rfx.MDS_SQUARED, oracle.SQUARED), (8, rfx.MDS_LINEAR, oracle.LINEAR)):
+    for m, mode, omode in ((3, rfx.MDS_SQUARED, oracle.SQUARED), (8, rfx.MDS_LINEAR, oracle.LINEAR),
+                           (32, rfx.MDS_SQUARED, oracle.SQUARED)):
         ref, ev_ref = oracle.mds3d_dense(Qh, sh, omode)
         x0 = ri.start_block(N, m, seed=779)
         coords, ev, iters = rfx.mds3d(torch.from_numpy(Qh).cuda(), torch.from_numpy(sh).cuda(), torch.from_numpy(x0).cuda(),
