@@ -165,7 +165,7 @@ def test_lowrank_extreme_ranks(torch_cuda, small2):
     torch = torch_cuda
     leaf = small2["leaf"]
     B, N = leaf.shape
-    for k, T in ((1, 30), (40, 6), (80, 6), (96, 6), (112, 6), (128, 6)):   # 40, 80: not multiples of 16; 80..128: beyond one 64-column tile
+    for k, T in ((1, 30), (40, 6), (80, 6), (88, 6), (96, 6), (112, 6), (128, 6)):   # 40, 80: not multiples of 16; 80..128: beyond one 64-column tile
         V0 = ri.start_block(N, k, seed=21 + k)
         lam_ref, V_ref = oracle.block_iteration(leaf, V0, T)
         lam, V, Q, s = rfx.prox_lowrank(_dev(torch, leaf), int(leaf.max()) + 1, torch.from_numpy(V0).cuda(), T)
