@@ -251,7 +251,10 @@ int rfx_oob_vote(const uint32_t* leaf, const uint16_t* inbag, const int32_t* lea
  *   rfx_pv_plan_create: leaf [device] uint32 [B][N] (read during the call only), ids < leaf_bound.
  *   rfx_pv_apply:       V [device] float32 [N][k] in, Y [device] float32 [N][k] out, 1 <= k <= 256,
  *                       V and Y must not overlap.  Asynchronous once the plan's scratch has
- *                       been sized for k (first call with a larger k allocates).
+ *                       been sized for k (first call with a larger k allocates).  Part of the work
+ *                       runs on a stream the plan owns, forked from and joined back into `stream`
+ *                       with events, so work queued on `stream` afterwards sees Y complete; calls
+ *                       on one plan from several streams at once race on its scratch.
  *   rfx_prox_matvec:    one-shot convenience: create plan, apply, destroy.  Synchronous. */
 typedef struct rfx_pv_plan rfx_pv_plan;
 int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, rfx_pv_plan** out,
