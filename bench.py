@@ -283,8 +283,12 @@ def pv_figures(w, kern, copy_rate, plan_ms):
     stream next to the leaf sums of the following one, so the two kernel figures overlap and add up to more."""
     N, B, k = w.N, w.B, w.k
     w_pv = B * N * (2 * 4 * k + 4) + 2 * 4 * N * k
-    pv_ms = kern["pv_apply"]["avg_ms"]
-    applications = max(kern["pv_apply"]["launches"], 1)
+    applications = kern["pv_apply"]["launches"]
+    if applications:
+        pv_ms = kern["pv_apply"]["avg_ms"]
+    else:                                         # one group of trees: the two kernel brackets are the application
+        applications = max(kern["pv_gather_kernel"]["launches"], 1)
+        pv_ms = (kern["pv_leaf_sum_kernel"]["total_ms"] + kern["pv_gather_kernel"]["total_ms"]) / applications
     rate = w_pv / (pv_ms * 1e-3) if pv_ms > 0 else 0.0
     return {"bytes_per_application": w_pv, "avg_ms": pv_ms, "GBps": rate / 1e9, "frac_of_hbm_peak": rate / PEAK_HBM_BYTES,
             "leaf_sum_ms": kern["pv_leaf_sum_kernel"]["total_ms"] / applications,

@@ -43,6 +43,8 @@ struct DevBuf {
 // the launch stream; rfx_timing_get waits for the events and accumulates the elapsed times.
 struct TimedLaunch {
     TimedLaunch(const char* name, hipStream_t st);
+    TimedLaunch(const TimedLaunch&) = delete;
+    TimedLaunch& operator=(const TimedLaunch&) = delete;
     ~TimedLaunch();
     const char* name_;
     hipStream_t st_;

@@ -23,6 +23,7 @@
 // to group, the same additions in the same order as one sweep), the caller's stream joining at the end.
 #include <algorithm>
 #include <mutex>
+#include <optional>
 #include <type_traits>
 #include <vector>
 
@@ -52,9 +53,11 @@ struct rfx_pv_plan {
 namespace {
 
 constexpr int kGatherTile = 32;   // Y rows per wave in the gather
-// Groups of trees per application (forests of at least 16 trees per group).  Measured at N = 100,000, B = 1,000,
-// k = 64: 5.66 ms in one group, 5.17 in two, 5.07 in four, 5.30 in eight.
+// Groups of trees per application.  Measured at N = 100,000, B = 1,000, k = 64: 5.66 ms in one group, 5.17 in two,
+// 5.07 in four, 5.30 in eight.  Small problems stay in one group: their kernels are too short to pay for the extra
+// launches and the cross-stream events (N = 10,000, B = 500: 0.57 ms in one group, 0.67 ms in four).
 constexpr int kApplyChunks = rfx_pv_plan::kMaxChunks;
+constexpr int64_t kApplyChunkMinPairs = 10000000;   // B * N from which the groups pay
 constexpr int kBigLeaf = 256;     // slots with more members are summed by a whole workgroup
 constexpr int kBigWaves = 16;
 constexpr int kHistLdsLeaves = 16384;  // largest Lb whose histogram fits LDS (64 KB)
@@ -376,11 +379,11 @@ __global__ __launch_bounds__(64 * kBigWaves) void pv_leaf_sum_big_kernel(const u
 
 // Gather.  A wave owns kGatherTile consecutive samples and sweeps the trees b_begin .. b_end - 1 in order, two
 // trees per step; all row loads of a step are issued before any is consumed.  The sums start from zero for the
-// first group of trees and from the values the previous group left in Y otherwise (the same additions in the same
+// first group of trees (kFirst) and from the values the previous group left in Y otherwise (the same additions in the same
 // order as one sweep over all trees); the last group divides by B.
 constexpr int kGatherTrees = 2;
 
-template <int KCH, int RPW>
+template <int KCH, int RPW, bool kFirst>
 __global__ __launch_bounds__(256) void pv_gather_kernel(const uint32_t* __restrict__ slot, int64_t N, int32_t B,
                                                        int32_t b_begin, int32_t b_end,
                                                        const float* __restrict__ S, int32_t k, float* __restrict__ Y) {
@@ -400,7 +403,7 @@ __global__ __launch_bounds__(256) void pv_gather_kernel(const uint32_t* __restri
 #pragma unroll
         for (int c = 0; c < KCH; ++c) {
             const int r = s * RPW + grp, cc = lane_col<RPW>(lane) + 64 * c;
-            acc[s][c] = (b_begin > 0 && r < rows && cc < k) ? Y[(i0 + r) * k + cc] : 0.0f;
+            acc[s][c] = (!kFirst && r < rows && cc < k) ? Y[(i0 + r) * k + cc] : 0.0f;
         }
     // lane l < 32 carries the slot of sample i0 + l (clamped to the tile's last valid row)
     const int64_t my_row = i0 + min(lane & (kGatherTile - 1), rows - 1);
@@ -462,7 +465,9 @@ hipError_t side_stream(hipStream_t* out) {
 template <int KCH, int RPW>
 int launch_apply(const rfx_pv_plan* p, const float* V, int32_t k, float* Y, hipStream_t st) {
     const int64_t tiles = rfx::ceil_div(p->N, kGatherTile);
-    rfx::TimedLaunch whole("pv_apply", st);
+    // with one group the two kernel brackets below add up to the application; no third pair of events then
+    std::optional<rfx::TimedLaunch> whole;
+    if (p->n_chunks > 1) whole.emplace("pv_apply", st);
     for (int c = 0; c < p->n_chunks; ++c) {
         const int b0 = p->tree_off[c], b1 = p->tree_off[c + 1];
         const int64_t slot_begin = (int64_t)b0 * p->Lb, slot_end = (int64_t)b1 * p->Lb;
@@ -485,8 +490,12 @@ int launch_apply(const rfx_pv_plan* p, const float* V, int32_t k, float* Y, hipS
         }
         {
             rfx::TimedLaunch timed("pv_gather_kernel", gs);
-            hipLaunchKernelGGL((pv_gather_kernel<KCH, RPW>), dim3((unsigned)rfx::ceil_div(tiles, 4)), dim3(256), 0, gs,
-                               p->d_slot, p->N, p->B, b0, b1, p->d_S, k, Y);
+            if (c == 0)
+                hipLaunchKernelGGL((pv_gather_kernel<KCH, RPW, true>), dim3((unsigned)rfx::ceil_div(tiles, 4)), dim3(256), 0,
+                                   gs, p->d_slot, p->N, p->B, b0, b1, p->d_S, k, Y);
+            else
+                hipLaunchKernelGGL((pv_gather_kernel<KCH, RPW, false>), dim3((unsigned)rfx::ceil_div(tiles, 4)), dim3(256), 0,
+                                   gs, p->d_slot, p->N, p->B, b0, b1, p->d_S, k, Y);
         }
         RFX_LAUNCH_CHECK("pv_gather_kernel");
     }
@@ -534,7 +543,7 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
     const int Q = (int)std::max<int64_t>(1, std::min<int64_t>(16, N / 4096));
     const int64_t part_len = rfx::ceil_div(rfx::ceil_div(N, Q), 64) * 64;
     // groups of trees for the overlapped application, each with its own list of big slots
-    p->n_chunks = B >= 16 * kApplyChunks ? kApplyChunks : 1;
+    p->n_chunks = (B >= 16 * kApplyChunks && (int64_t)B * N >= kApplyChunkMinPairs) ? kApplyChunks : 1;
     BigGroups groups;
     groups.n = p->n_chunks;
     int64_t max_big = 0;
