@@ -382,9 +382,11 @@ __global__ __launch_bounds__(64 * kBigWaves) void pv_leaf_sum_big_kernel(const u
 // first group of trees (kFirst) and from the values the previous group left in Y otherwise (the same additions in the same
 // order as one sweep over all trees); the last group divides by B.
 constexpr int kGatherTrees = 2;
+// For k in 33..64 the kernel needs 131 registers as written; held to 128 (four waves per SIMD instead of three, one
+// register spilled) an application takes 4.89 instead of 5.07 ms; at 102 (five waves) the spills cost more (5.26 ms).
 
 template <int KCH, int RPW, bool kFirst>
-__global__ __launch_bounds__(256) void pv_gather_kernel(const uint32_t* __restrict__ slot, int64_t N, int32_t B,
+__global__ __launch_bounds__(256, (KCH == 1 && RPW == 1) ? 4 : 1) void pv_gather_kernel(const uint32_t* __restrict__ slot, int64_t N, int32_t B,
                                                        int32_t b_begin, int32_t b_end,
                                                        const float* __restrict__ S, int32_t k, float* __restrict__ Y) {
     constexpr int kSteps = kGatherTile / RPW;  // load instructions per tree
