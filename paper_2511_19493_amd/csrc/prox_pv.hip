@@ -193,6 +193,52 @@ __global__ __launch_bounds__(64) void pv_scatter_kernel(const uint32_t* __restri
     }
 }
 
+// The same scatter with the part's cursors in LDS (leaf bounds up to kScatterLdsLeaves): they are loaded once,
+// coalesced, and the first lane of every group of equal slots advances its cursor with a plain read and write
+// (the groups of a step have distinct slots), so no global atomic and no round trip per step is left.
+constexpr int kScatterLdsLeaves = 8192;  // 32 KB of cursors per wave, five waves per CU
+
+__global__ __launch_bounds__(64) void pv_scatter_lds_kernel(const uint32_t* __restrict__ slot, int64_t N, int32_t Lb,
+                                                           int64_t part_len, const uint32_t* __restrict__ cursor,
+                                                           uint32_t* __restrict__ perm) {
+    extern __shared__ uint32_t cur[];  // [Lb]
+    const int q = blockIdx.x, Q = gridDim.x, b = blockIdx.y;
+    const int lane = threadIdx.x;
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    const uint32_t* s = slot + (int64_t)b * N;
+    const uint32_t* mine = cursor + ((int64_t)b * Q + q) * Lb;
+    for (int l = lane; l < Lb; l += 64) cur[l] = mine[l];
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t slot0 = (uint32_t)b * (uint32_t)Lb;
+    const int64_t lo = (int64_t)q * part_len, hi = min(N, lo + part_len);
+    for (int64_t i0 = lo; i0 < hi; i0 += 64) {
+        const int64_t i = i0 + lane;
+        const bool valid = i < hi;
+        const uint32_t key = valid ? s[i] - slot0 : 0xffffffffu;
+        uint64_t remaining = __ballot(valid);
+        int my_leader = lane;
+        uint32_t rank = 0, gcount = 0;
+        while (remaining) {
+            const int leader = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)remaining) - 1);
+            const uint32_t lk = __builtin_amdgcn_readlane(key, leader);
+            const uint64_t m = __ballot(valid && key == lk);
+            if (valid && key == lk) {
+                my_leader = leader;
+                rank = (uint32_t)__popcll(m & lt_mask);
+                gcount = (uint32_t)__popcll(m);
+            }
+            remaining &= ~m;
+        }
+        uint32_t base = 0;
+        if (valid && my_leader == lane) {
+            base = cur[key];
+            cur[key] = base + gcount;
+        }
+        base = __shfl(base, my_leader);
+        if (valid) perm[base + rank] = (uint32_t)i;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Column handled by a lane.  RPW = rows (samples) a wave touches with one load instruction:
 // 1 for k > 32 (lanes are columns lane, lane+64, ...), 2 for 16 < k <= 32, 4 for k <= 16 (each
@@ -594,7 +640,11 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
         hipLaunchKernelGGL(pv_hist_kernel<0>, dim3(Q, B), dim3(1024), 0, st, leaf, N, Lb, part_len, p->d_slot, cnt, bad);
     hipLaunchKernelGGL(pv_scan_kernel, dim3((unsigned)B), dim3(256), 0, st, cnt, N, B, Lb, Q, p->d_seg_start, p->d_big, n_big,
                        groups);
-    hipLaunchKernelGGL(pv_scatter_kernel, dim3(Q, B), dim3(64), 0, st, p->d_slot, N, Lb, part_len, cnt, p->d_perm);
+    if (Lb <= kScatterLdsLeaves)
+        hipLaunchKernelGGL(pv_scatter_lds_kernel, dim3(Q, B), dim3(64), sizeof(uint32_t) * Lb, st, p->d_slot, N, Lb, part_len,
+                           cnt, p->d_perm);
+    else
+        hipLaunchKernelGGL(pv_scatter_kernel, dim3(Q, B), dim3(64), 0, st, p->d_slot, N, Lb, part_len, cnt, p->d_perm);
     int h_flags[kFlags] = {};
     e = hipGetLastError();
     if (e == hipSuccess) e = hipMemcpyAsync(h_flags, flags.p, kFlags * sizeof(int), hipMemcpyDeviceToHost, st);
