@@ -139,8 +139,8 @@ int rfx_grown_destroy(rfx_grown* grown);
 uint64_t rfx_growth_draw(uint64_t seed, uint64_t tree, uint64_t a, uint64_t b);
 
 /* Leaf assignment: leaf[b*N + i] = dense leaf index of sample i in tree b, for every tree and
- * every sample, in-bag or not ("for each tree, terminal node assignments are computed for all
- * samples", CPU Proximity Computation; traversal rule: "Threshold-based Splits").
+ * every sample, in-bag or not (CPU Proximity Computation; traversal rule: "Threshold-based
+ * Splits").
  *   X    [device] float32 [N][M] row-major samples, M == forest n_features
  *   leaf [device] uint32 [B][N] out
  * Asynchronous.  Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG (N < 1, M mismatch). */

@@ -7,7 +7,7 @@
  * thresholds taken from the values present in the node with x <= tau going left ("Threshold-based
  * Splits"), trees grown until the nodes are pure).  Shares no code with the HIP library.
  *
- * What the paper leaves open is fixed as follows (the HIP grower takes the same readings):
+ * What the paper leaves open is fixed as follows:
  *   - Random numbers come from a counter-based generator, so that they do not depend on the order
  *     in which nodes are processed: draw(seed, tree, a, b) = mix(mix(mix(seed ^ (tree+1) K) ^ a) ^ b)
  *     with mix = the output function of splitmix64 and K = 0x9e3779b97f4a7c15; an integer below n

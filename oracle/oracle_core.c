@@ -8,9 +8,9 @@
  * Steps (paper passages):
  *   orc_leaf_assign   terminal node of every sample in every tree; rows with
  *                     x <= tau go left, rows with x > tau go right
- *                     (Methodology, "Threshold-based Splits"; "for each tree,
- *                     terminal node assignments are computed for all
- *                     samples", CPU Proximity Computation).
+ *                     (Methodology, "Threshold-based Splits"; every sample,
+ *                     in-bag or not, is dropped down every tree: CPU
+ *                     Proximity Computation).
  *   orc_counts_rows   cnt(i,j) = #{b : node_b(i) = node_b(j)}, the numerator
  *                     of the proximity equation p(i,j) = (1/B) sum_b I(...)
  *                     (Methodology, "Proximity Matrices").

@@ -52,6 +52,34 @@ def test_encodings_bit_exact(torch_cuda, N, k):
         assert cb == rc.nbytes and ns == rs.size
 
 
+def test_nf4_level_table_of_the_library_equals_the_oracles(torch_cuda):
+    """Every one of the 16 codes decoded on the GPU with unit scales gives the oracle's level bit for bit
+    (the oracle's table is pinned to the normal-quantile construction by a CPU test), and the decision
+    thresholds (midpoints of adjacent levels) agree: values just below, at and just above every midpoint
+    encode to the same codes on both sides."""
+    import oracle
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    N, k = 64, 1
+    code = (np.arange(N) % 16).astype(np.uint8).reshape(N, 1)
+    packed = (code[0::2] | (code[1::2] << 4)).astype(np.uint8)
+    ones = np.ones((1, 1), np.float32)
+    A = rfx.dequantise_factor(torch.from_numpy(packed).cuda(), torch.from_numpy(ones).cuda(), N, k, rfx.ENC_NF4)
+    np.testing.assert_array_equal(A.cpu().numpy()[:16, 0], oracle.NF4_LEVELS)
+    np.testing.assert_array_equal(A.cpu().numpy(), oracle.dequantise_factor(packed, ones, oracle.ENC_NF4, N))
+    # one block whose maximum is exactly 1, so the normalised values are the values themselves
+    lv = oracle.NF4_LEVELS
+    mid = ((lv[:-1] + lv[1:]) * np.float32(0.5)).astype(np.float32)
+    vals = np.concatenate([[1.0], np.nextafter(mid, np.float32(-2)), mid, np.nextafter(mid, np.float32(2)), lv[1:-1]])
+    V = np.zeros((64, 1), np.float32)
+    V[:vals.size, 0] = vals.astype(np.float32)
+    lam = np.ones(1, np.float32)
+    codes, scales = rfx.quantise_factor(torch.from_numpy(V).cuda(), torch.from_numpy(lam).cuda(), rfx.ENC_NF4)
+    rc, rs = oracle.quantise_factor(V, lam, oracle.ENC_NF4)
+    np.testing.assert_array_equal(codes.cpu().numpy().reshape(rc.shape), rc)
+    np.testing.assert_array_equal(scales.cpu().numpy().reshape(rs.shape), rs)
+
+
 def test_scaling_from_every_encoding_and_correlation_with_the_full_matrix(torch_cuda, small2):
     import oracle
     import paper_2511_19493_amd as rfx

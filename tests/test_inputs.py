@@ -137,3 +137,81 @@ def test_first_split_maximises_gini_decrease(cfg1):
     gains = np.array([gain(t) for t in vals])
     assert gain(tau) >= gains.max() - 1e-12
     assert tau == vals[np.argmax(gains >= gains.max() - 1e-15)] or gain(tau) == pytest.approx(gains.max(), abs=1e-12)
+
+
+def _exact_scores(X, y, w, rows, f, C):
+    """Exact score of every candidate threshold of feature f in a node: maximising the paper's Gini decrease
+    dI = I(parent) - nL/n I(left) - nR/n I(right) is maximising sum_c wL_c^2/nL + sum_c wR_c^2/nR, a fraction
+    of integers when the weights are in-bag counts.  Returns [(Fraction score, threshold)] over the node's
+    distinct values except the largest."""
+    from fractions import Fraction
+    order = sorted(rows, key=lambda i: X[i, f])
+    tot = [0] * C
+    for i in order:
+        tot[y[i]] += int(w[i])
+    n = sum(tot)
+    left = [0] * C
+    out = []
+    for p, i in enumerate(order[:-1]):
+        left[y[i]] += int(w[i])
+        if X[order[p + 1], f] == X[i, f]:
+            continue
+        nL = sum(left)
+        nR = n - nL
+        a = sum(v * v for v in left)
+        c = sum((t - v) * (t - v) for t, v in zip(tot, left))
+        out.append((Fraction(a, nL) + Fraction(c, nR), X[i, f]))
+    return out
+
+
+def _walk_nodes(F, b, X):
+    """Yields (node, rows) for every node of tree b, rows = the in-bag rows that reach it under x <= tau."""
+    s = int(F.node_offset[b])
+    stack = [(0, [i for i in range(X.shape[0]) if F.inbag[b][i] > 0])]
+    while stack:
+        v, rows = stack.pop()
+        yield v, rows
+        f = int(F.feature[s + v])
+        if f >= 0:
+            t = F.threshold[s + v]
+            stack.append((int(F.left[s + v]), [i for i in rows if X[i, f] <= t]))
+            stack.append((int(F.right[s + v]), [i for i in rows if X[i, f] > t]))
+
+
+def test_every_interior_split_maximises_the_gini_decrease(cfg1):
+    """Every internal node of the generator's trees, not only the root: the stored threshold attains the
+    exact maximum of the Gini decrease over all thresholds of the stored feature (fractions of integers, so
+    the check does not share the generator's floating-point gain).  Where two candidates tie exactly the
+    lower threshold must have been kept (first best)."""
+    F, X, y = cfg1["F"], cfg1["X"], cfg1["y"]
+    checked = 0
+    for b in (0, 3, 41, 99):
+        s = int(F.node_offset[b])
+        for v, rows in _walk_nodes(F, b, X):
+            f = int(F.feature[s + v])
+            if f < 0:
+                assert len({int(y[i]) for i in rows}) == 1
+                continue
+            cands = _exact_scores(X, y, F.inbag[b], rows, f, 3)
+            best = max(sc for sc, _ in cands)
+            first = min(t for sc, t in cands if sc == best)
+            assert F.threshold[s + v] == first, (b, v)
+            checked += 1
+    assert checked > 30
+
+
+def test_every_split_is_the_global_best_when_all_features_are_offered(cfg1):
+    """With mtry = M the feature draw offers every feature at every node, so the split must be a global
+    maximiser of the Gini decrease over all (feature, threshold) pairs, at every depth."""
+    X, y, c = cfg1["X"], cfg1["y"], cfg1["c"]
+    F = ri.grow_forest(X, y, c.C, 3, c.M, iseed=4321)
+    for b in range(3):
+        s = int(F.node_offset[b])
+        for v, rows in _walk_nodes(F, b, X):
+            f = int(F.feature[s + v])
+            if f < 0:
+                continue
+            per_feature = {g: _exact_scores(X, y, F.inbag[b], rows, g, c.C) for g in range(c.M)}
+            best = max(sc for cands in per_feature.values() for sc, _ in cands)
+            chosen = [sc for sc, t in per_feature[f] if t == F.threshold[s + v]]
+            assert chosen and chosen[0] == best, (b, v)

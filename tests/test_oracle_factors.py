@@ -163,6 +163,28 @@ def test_mds_operator_and_invariants(cfg1, mode):
         assert np.linalg.eigvalsh(G).min() > -1e-10                         # 1/2 H P^ H is PSD
 
 
+def test_nf4_levels_follow_the_normal_quantile_construction():
+    """The 16 NormalFloat levels of the QLoRA paper (cited under "Low-Rank Factorization and Quantization
+    Trade-offs") are quantiles of N(0,1): eight positive levels from 9 equally spaced probabilities between
+    an offset and 1/2 (the 1/2 dropped), seven negative ones from 8 such probabilities, an exact zero, all
+    divided by the largest magnitude; the offset is the mean of 1 - 1/30 and 1 - 1/32.  The stored table is
+    rebuilt here from scipy's normal quantile function; a wrong digit in any level fails."""
+    from scipy.stats import norm
+    offset = 0.5 * ((1.0 - 1.0 / 30.0) + (1.0 - 1.0 / 32.0))
+    pos = norm.ppf(np.linspace(offset, 0.5, 9))[:-1]
+    neg = -norm.ppf(np.linspace(offset, 0.5, 8))[:-1]
+    built = np.sort(np.concatenate([neg, [0.0], pos]))
+    built /= np.abs(built).max()
+    assert built.shape == (16,)
+    np.testing.assert_allclose(oracle.NF4_LEVELS.astype(np.float64), built, rtol=0, atol=2.5e-7)
+    # float32 neighbours of a level differ by up to 6e-8, adjacent levels by at least 0.079: no other
+    # table of float32 values passes for a different level
+    assert np.diff(built).min() > 0.079
+    # asymmetric by construction: one more positive level than negative ones, and no level is mirrored
+    assert (oracle.NF4_LEVELS > 0).sum() == 8 and (oracle.NF4_LEVELS < 0).sum() == 7
+    assert not np.isclose(-oracle.NF4_LEVELS[1], oracle.NF4_LEVELS[14], atol=1e-3)
+
+
 def test_nf4_levels_and_fp16_nf4_encodings():
     lv = oracle.NF4_LEVELS
     assert lv.shape == (16,) and lv[0] == -1.0 and lv[7] == 0.0 and lv[15] == 1.0 and (np.diff(lv) > 0).all()
