@@ -17,12 +17,23 @@
  *     addresses.  All arrays are dense, row-major, with the index order written in brackets.
  *   - `stream` is a hipStream_t passed as void* (null = the default stream).  Work is
  *     enqueued on that stream in order.  Calls documented as "asynchronous" return before
- *     the work has finished and their outputs are valid once the caller has synchronised
- *     the stream; the others synchronise the stream before returning.
- *   - Scratch memory is allocated and freed by the library inside the call (hipMalloc /
- *     hipFree), except for plans and forests, which own theirs until destroyed.
- *   - Arguments are validated on the host before anything is launched; a call that
- *     returns an error has launched nothing that writes caller memory.
+ *     the work has finished, never wait for the device, allocate nothing, and their outputs are
+ *     valid once the caller has synchronised the stream; the others synchronise the stream
+ *     before returning.
+ *   - Scratch memory.  Every step has an asynchronous form that takes its scratch from the
+ *     caller: rfx_*_workspace_bytes reports the size for a problem, and the *_ws / *_plan call
+ *     takes `workspace` [device], 256-byte aligned, of at least that many bytes (else
+ *     RFX_ERR_CAPACITY).  The workspace holds nothing between calls and may be reused by the
+ *     next call on the same stream; two calls that use one workspace on different streams race.
+ *     The calls without a workspace argument are conveniences for one-off use: they allocate
+ *     their scratch (hipMalloc / hipFree inside the call), run the asynchronous form and wait.
+ *     Plans and forests own their memory until destroyed.
+ *   - Arguments are validated on the host before anything is launched: a call that returns an
+ *     argument error (RFX_ERR_NULL, _INVALID_ARG, _OVERFLOW, _UNSUPPORTED, _FOREST, and
+ *     _CAPACITY of a workspace) has launched nothing that writes caller memory.  Conditions that
+ *     only the device can see are reported after the outputs were written: a leaf id at or above
+ *     leaf_bound (rfx_pv_plan_create), a block that lost rank (rfx_prox_lowrank), more
+ *     qualifying pairs than the capacity (rfx_prox_sparse), and failures of the HIP runtime.
  */
 #ifndef RFX_H
 #define RFX_H
@@ -166,9 +177,15 @@ int rfx_probe_copy(int64_t bytes, double* bytes_per_s, void* stream);
  *   layout      RFX_FULL or RFX_UPPER_PACKED, applies to both outputs
  *   counts      [device] nullable; cnt(i,j) = #{b : leaf_b(i) = leaf_b(j)}; diagonal = B
  *   prox        [device] nullable float32; cnt / B in IEEE float32 division; diagonal = 1
- * At least one of counts / prox must be given.  Synchronous (the bit-plane scratch is freed
- * before returning).
- * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_OVERFLOW, RFX_ERR_OOM. */
+ * At least one of counts / prox must be given.
+ * rfx_prox_workspace_bytes: scratch of every rfx_prox_*_ws call for this N, B, leaf_bound (the
+ * leaf ids transposed into bit planes, 4 * ceil(B/32) * roundup(N, 256) * roundup4(bits + 1)
+ * bytes, plus 16 N bytes of per-sample sums and a counter).  1 <= N <= 3,000,000.
+ * rfx_prox_dense_ws: asynchronous.  rfx_prox_dense: synchronous convenience.
+ * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_OVERFLOW, RFX_ERR_CAPACITY, RFX_ERR_OOM. */
+int rfx_prox_workspace_bytes(int64_t N, int32_t B, int32_t leaf_bound, int64_t* bytes);
+int rfx_prox_dense_ws(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
+                      void* counts, float* prox, void* workspace, int64_t workspace_bytes, void* stream);
 int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
                    void* counts, float* prox, void* stream);
 
@@ -178,7 +195,11 @@ int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_boun
  *   prox(i,j) = num/den in IEEE float32 division, 0 where den = 0, 1 on the diagonal.
  *   inbag [device] uint16 [B][N];  num, den, prox [device] nullable (at least one given);
  *   other arguments as rfx_prox_dense.  Diagonal of num and den in RFX_FULL = |OOB_i|.
- * B <= 65535 (numerator and denominator share one 32-bit counter), else RFX_ERR_UNSUPPORTED. */
+ * B <= 65535 (numerator and denominator share one 32-bit counter), else RFX_ERR_UNSUPPORTED.
+ * rfx_prox_oob_ws: asynchronous, scratch of rfx_prox_workspace_bytes.  rfx_prox_oob: synchronous. */
+int rfx_prox_oob_ws(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
+                    int count_dtype, int layout, void* num, void* den, float* prox, void* workspace,
+                    int64_t workspace_bytes, void* stream);
 int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
                  int count_dtype, int layout, void* num, void* den, float* prox, void* stream);
 
@@ -187,7 +208,11 @@ int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t
  * meaning exactly as rfx_prox_dense (counts, prox, in `layout`) and rfx_prox_oob (num, den,
  * prox_oob, in `oob_layout`); at least one output of each kind must be given.  The three counts
  * of a pair share one 32-bit counter, so B <= 1023, else RFX_ERR_UNSUPPORTED (use the two calls).
- * Synchronous. */
+ * rfx_prox_dense_oob_ws: asynchronous, scratch of rfx_prox_workspace_bytes.  rfx_prox_dense_oob:
+ * synchronous. */
+int rfx_prox_dense_oob_ws(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
+                          int count_dtype, int layout, void* counts, float* prox, int oob_layout, void* num, void* den,
+                          float* prox_oob, void* workspace, int64_t workspace_bytes, void* stream);
 int rfx_prox_dense_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
                        int count_dtype, int layout, void* counts, float* prox, int oob_layout, void* num, void* den,
                        float* prox_oob, void* stream);
@@ -204,9 +229,16 @@ int rfx_prox_dense_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, i
  *   prox       [device] nullable float32 [capacity]: cnt / B in IEEE float32 division
  *   nnz        [host] out: number of qualifying pairs, also when it exceeds the capacity
  * The order of the entries is unspecified (it varies from call to call); every qualifying pair
- * appears exactly once.  Synchronous.  B < 2^20, else RFX_ERR_UNSUPPORTED.  When nnz > capacity > 0
- * the call returns RFX_ERR_CAPACITY and the arrays hold an unspecified subset.
+ * appears exactly once.  B < 2^20, else RFX_ERR_UNSUPPORTED.
+ * rfx_prox_sparse (synchronous): when nnz > capacity > 0 the call returns RFX_ERR_CAPACITY and the
+ * arrays hold an unspecified subset.
+ * rfx_prox_sparse_ws (asynchronous, scratch of rfx_prox_workspace_bytes): nnz is a [device]
+ * uint64, 8-byte aligned, that the call clears and the kernels count in; the caller reads it
+ * after synchronising and compares it with the capacity itself.
  * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_OVERFLOW, RFX_ERR_OOM, RFX_ERR_CAPACITY. */
+int rfx_prox_sparse_ws(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count,
+                       int count_dtype, int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox,
+                       uint64_t* nnz, void* workspace, int64_t workspace_bytes, void* stream);
 int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count, int count_dtype,
                     int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox, int64_t* nnz,
                     void* stream);
@@ -220,8 +252,12 @@ int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
  *   leaf, leaf_bound as rfx_prox_dense;  labels [device] nullable int32 [N];
  *   printed, classic [device] nullable float64 [N] (at least one given).
  * The sum of squares is accumulated as an exact integer; the sum of inverse squares in float64
- * with atomics, so its last bits can differ from call to call.  Synchronous.  N >= 2, B < 2^20.
- * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_UNSUPPORTED, RFX_ERR_OOM. */
+ * with atomics, so its last bits can differ from call to call.  N >= 2, B < 2^20.
+ * rfx_prox_outlier_ws: asynchronous, scratch of rfx_prox_workspace_bytes.  rfx_prox_outlier:
+ * synchronous.
+ * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_UNSUPPORTED, RFX_ERR_CAPACITY, RFX_ERR_OOM. */
+int rfx_prox_outlier_ws(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const int32_t* labels,
+                        double* printed, double* classic, void* workspace, int64_t workspace_bytes, void* stream);
 int rfx_prox_outlier(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const int32_t* labels,
                      double* printed, double* classic, void* stream);
 
@@ -249,9 +285,15 @@ int rfx_oob_vote(const uint32_t* leaf, const uint16_t* inbag, const int32_t* lea
  * P is never formed.  A plan holds the per-tree grouping of samples by leaf (built once per
  * forest) and the scratch for the per-leaf sums.
  *   rfx_pv_plan_create: leaf [device] uint32 [B][N] (read during the call only), ids < leaf_bound.
+ *                       B <= 65535, B * N < 2^32 and B * leaf_bound < 2^32, else
+ *                       RFX_ERR_UNSUPPORTED.  Synchronous (it reports a leaf id >= leaf_bound).
+ *   rfx_pv_plan_reserve: sizes the per-leaf sums for rank k now (4 B leaf_bound k bytes; waits for
+ *                       the device when it has to replace a smaller buffer), so that every later
+ *                       application of rank <= k is asynchronous.
+ *   rfx_pv_plan_info:   N, B and the rank reserved so far ([host] out, each nullable).
  *   rfx_pv_apply:       V [device] float32 [N][k] in, Y [device] float32 [N][k] out, 1 <= k <= 256,
  *                       V and Y must not overlap.  Asynchronous once the plan's scratch has
- *                       been sized for k (first call with a larger k allocates).  Part of the work
+ *                       been sized for k (a call with a larger k reserves first).  Part of the work
  *                       runs on a stream the plan owns, forked from and joined back into `stream`
  *                       with events, so work queued on `stream` afterwards sees Y complete; calls
  *                       on one plan from several streams at once race on its scratch.
@@ -260,6 +302,8 @@ typedef struct rfx_pv_plan rfx_pv_plan;
 int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, rfx_pv_plan** out,
                        void* stream);
 int rfx_pv_plan_destroy(rfx_pv_plan* plan);
+int rfx_pv_plan_reserve(rfx_pv_plan* plan, int32_t k);
+int rfx_pv_plan_info(const rfx_pv_plan* plan, int64_t* N, int32_t* B, int32_t* k_reserved);
 int rfx_pv_apply(rfx_pv_plan* plan, const float* V, int32_t k, float* Y, void* stream);
 int rfx_prox_matvec(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const float* V, int32_t k,
                     float* Y, void* stream);
@@ -277,7 +321,16 @@ int rfx_prox_matvec(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
  *   V       [device] float32 [N][k] out, orthonormal Ritz vectors (before quantisation)
  *   Q       [device] int8 [N][k] out, nullable together with scales
  *   scales  [device] float32 [k] out
- * 1 <= k <= 128, k <= N, iters >= 1.  Synchronous. */
+ * 1 <= k <= 128, k <= N, iters >= 1.
+ * rfx_prox_lowrank (synchronous): builds a plan for the call and destroys it; a block that lost
+ * rank (start block or P of rank < k) returns RFX_ERR_INVALID_ARG after the outputs were written.
+ * rfx_prox_lowrank_plan (asynchronous): the same on an existing plan whose sums were reserved for
+ * rank >= k (rfx_pv_plan_reserve), with scratch of rfx_lowrank_workspace_bytes(N, k);
+ *   status  [device] nullable int32 out: 1 if a block lost rank, else 0. */
+int rfx_lowrank_workspace_bytes(int64_t N, int32_t k, int64_t* bytes);
+int rfx_prox_lowrank_plan(rfx_pv_plan* plan, int32_t k, int32_t iters, const float* V0, float* eigvals, float* V,
+                          int8_t* Q, float* scales, int32_t* status, void* workspace, int64_t workspace_bytes,
+                          void* stream);
 int rfx_prox_lowrank(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t k, int32_t iters,
                      const float* V0, float* eigvals, float* V, int8_t* Q, float* scales, void* stream);
 
@@ -313,19 +366,33 @@ int rfx_dequantise_factor(const void* codes, const float* scales, int64_t N, int
  * Proximity Matrices", Steps 1-4).  With A^ = Q diag(scales), P^ = A^ A^^T and D = 1 - P^ (the
  * paper's max P - P with max P = 1): G = -1/2 H D2 H, H = I - 11^T/N, D2 = D o D
  * (RFX_MDS_SQUARED) or D (RFX_MDS_LINEAR).  G is applied through the factors only
- * (u = H v, z = D2 u, w = H z, G v = -w/2).  The three algebraically largest eigenpairs are
- * found by simultaneous power iteration on a block of m vectors with a Rayleigh-Ritz step
- * (the power method with deflation of Step 3, done for all vectors at once); coordinates are
+ * (u = H v, z = D2 u, w = H z, G v = -w/2); the INT8 codes are decoded where they are read.
+ * The three algebraically largest eigenpairs are found by simultaneous power iteration on a
+ * block of m vectors with a Rayleigh-Ritz step (the power method with deflation of Step 3, done
+ * for all vectors at once).  In RFX_MDS_SQUARED mode G can have negative eigenvalues; the
+ * iteration runs on G + sigma I with sigma = the largest -theta_min any Rayleigh-Ritz step has
+ * seen (0 while every Ritz value of the block is non-negative), which never exceeds
+ * |lambda_min(G)| and makes the iteration converge to the largest eigenvalues rather than the
+ * largest magnitudes; the reported eigenvalues are those of G.  Coordinates are
  * x_i = (sqrt(l1) v1_i, sqrt(l2) v2_i, sqrt(l3) v3_i), a non-positive eigenvalue giving a zero
- * column; each column is signed so that its largest-magnitude entry is positive.
+ * column; each column is signed so that its largest-magnitude entry is positive.  A block whose
+ * rank is below m (G of rank < m, k < m in RFX_MDS_LINEAR mode, dependent columns of x0) is not
+ * an error: dependent directions are dropped and their Ritz values are 0.
  *   Q [device] int8 [N][k], scales [device] float32 [k], 1 <= k <= 128
- *   m          block width, 3..16 (extra vectors speed up convergence)
+ *   m          block width, 3..32, m <= N (extra vectors speed up convergence)
  *   x0         [device] float32 [N][m] start block
- *   max_iters  >= 1; tol: stop when the three leading Ritz values change by less than
- *              tol * |value| between two checks
  *   coords     [device] float32 [N][3] out;  eigvals [device] float32 [3] out
- *   iters_done [host] nullable out: applications of G performed
- * Synchronous. */
+ * rfx_mds3d (synchronous): max_iters >= 1; tol >= 0: the host looks at the iteration every 4
+ *   applications of G and stops when, in the last one, the three leading Ritz values changed by
+ *   at most tol * |value|;  iters_done [host] nullable out: applications of G performed.
+ * rfx_mds3d_ws (asynchronous, scratch of rfx_mds3d_workspace_bytes(N, k, m, dissim_mode)):
+ *   exactly `iters` applications of G;  rel_change [device] nullable float32 out: the largest
+ *   relative change of the three leading Ritz values in the last application (inf for iters = 1),
+ *   for the caller to judge convergence. */
+int rfx_mds3d_workspace_bytes(int64_t N, int32_t k, int32_t m, int dissim_mode, int64_t* bytes);
+int rfx_mds3d_ws(const int8_t* Q, const float* scales, int64_t N, int32_t k, int dissim_mode, int32_t m, int32_t iters,
+                 const float* x0, float* coords, float* eigvals, float* rel_change, void* workspace,
+                 int64_t workspace_bytes, void* stream);
 int rfx_mds3d(const int8_t* Q, const float* scales, int64_t N, int32_t k, int dissim_mode, int32_t m,
               int32_t max_iters, float tol, const float* x0, float* coords, float* eigvals,
               int32_t* iters_done, void* stream);

@@ -28,6 +28,9 @@ EXPORTS = (
     "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_dense_oob", "rfx_prox_sparse", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
+    "rfx_prox_workspace_bytes", "rfx_prox_dense_ws", "rfx_prox_oob_ws", "rfx_prox_dense_oob_ws", "rfx_prox_sparse_ws",
+    "rfx_prox_outlier_ws", "rfx_pv_plan_reserve", "rfx_pv_plan_info", "rfx_lowrank_workspace_bytes", "rfx_prox_lowrank_plan",
+    "rfx_mds3d_workspace_bytes", "rfx_mds3d_ws",
 )
 
 
@@ -86,6 +89,18 @@ def load():
             "rfx_factor_sizes": [ci, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)],
             "rfx_quantise_factor": [vp, vp, i64, i32, ci, vp, vp, vp],
             "rfx_dequantise_factor": [vp, vp, i64, i32, ci, vp, vp],
+            "rfx_prox_workspace_bytes": [i64, i32, i32, ctypes.POINTER(i64)],
+            "rfx_prox_dense_ws": [vp, i64, i32, i32, ci, ci, vp, vp, vp, i64, vp],
+            "rfx_prox_oob_ws": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp, i64, vp],
+            "rfx_prox_dense_oob_ws": [vp, vp, i64, i32, i32, ci, ci, vp, vp, ci, vp, vp, vp, vp, i64, vp],
+            "rfx_prox_sparse_ws": [vp, i64, i32, i32, i32, ci, i64, vp, vp, vp, vp, vp, vp, i64, vp],
+            "rfx_prox_outlier_ws": [vp, i64, i32, i32, vp, vp, vp, vp, i64, vp],
+            "rfx_pv_plan_reserve": [vp, i32],
+            "rfx_pv_plan_info": [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)],
+            "rfx_lowrank_workspace_bytes": [i64, i32, ctypes.POINTER(i64)],
+            "rfx_prox_lowrank_plan": [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp],
+            "rfx_mds3d_workspace_bytes": [i64, i32, i32, ci, ctypes.POINTER(i64)],
+            "rfx_mds3d_ws": [vp, vp, i64, i32, ci, i32, i32, vp, vp, vp, vp, vp, i64, vp],
         }
         for name, args in sigs.items():
             fn = getattr(lib, name)
@@ -458,3 +473,136 @@ def mds3d_factor(A, x0, mode: int = MDS_SQUARED, max_iters: int = 300, tol: floa
     _check(load().rfx_mds3d_factor(_dev(A, torch.float32), N, k, mode, m, max_iters, tol, _dev(x0, torch.float32, (N, m)),
                                    coords.data_ptr(), ev.data_ptr(), ctypes.byref(it), _stream()))
     return coords, ev, int(it.value)
+
+
+# ------------------------------------------------------------------------------ asynchronous forms
+# Scratch comes from a caller-owned workspace tensor; nothing here waits for the device.
+
+def _ws_ptr(workspace):
+    import torch
+    if workspace is None or not workspace.is_cuda or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous CUDA uint8 tensor")
+    return workspace.data_ptr(), workspace.numel()
+
+
+def prox_workspace_bytes(N: int, B: int, leaf_bound: int) -> int:
+    """rfx_prox_workspace_bytes."""
+    out = ctypes.c_int64(0)
+    _check(load().rfx_prox_workspace_bytes(N, B, leaf_bound, ctypes.byref(out)))
+    return out.value
+
+
+def new_workspace(nbytes: int, device="cuda"):
+    """A device buffer usable as `workspace` (torch allocations are at least 256-byte aligned)."""
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def prox_dense_ws(leaf, leaf_bound: int, workspace, count_dtype: int = U32, layout: int = FULL, counts=None, prox=None):
+    """rfx_prox_dense_ws: writes the given outputs (at least one); asynchronous."""
+    import torch
+    B, N = leaf.shape
+    shp = _sym_shape(N, layout)
+    wp, wb = _ws_ptr(workspace)
+    _check(load().rfx_prox_dense_ws(_dev(leaf, torch.int32), N, B, leaf_bound, count_dtype, layout,
+                                    _dev(counts, _count_dtype(count_dtype), shp), _dev(prox, torch.float32, shp), wp, wb,
+                                    _stream()))
+
+
+def prox_oob_ws(leaf, inbag, leaf_bound: int, workspace, count_dtype: int = U32, layout: int = FULL, num=None, den=None,
+                prox=None):
+    """rfx_prox_oob_ws; asynchronous."""
+    import torch
+    B, N = leaf.shape
+    shp = _sym_shape(N, layout)
+    cdt = _count_dtype(count_dtype)
+    wp, wb = _ws_ptr(workspace)
+    _check(load().rfx_prox_oob_ws(_dev(leaf, torch.int32), _dev(inbag, torch.int16, (B, N)), N, B, leaf_bound, count_dtype,
+                                  layout, _dev(num, cdt, shp), _dev(den, cdt, shp), _dev(prox, torch.float32, shp), wp, wb,
+                                  _stream()))
+
+
+def prox_dense_oob_ws(leaf, inbag, leaf_bound: int, workspace, count_dtype: int = U32, layout: int = FULL,
+                      oob_layout: int = FULL, counts=None, prox=None, num=None, den=None, prox_oob=None):
+    """rfx_prox_dense_oob_ws; asynchronous."""
+    import torch
+    B, N = leaf.shape
+    cdt = _count_dtype(count_dtype)
+    s1, s2 = _sym_shape(N, layout), _sym_shape(N, oob_layout)
+    wp, wb = _ws_ptr(workspace)
+    _check(load().rfx_prox_dense_oob_ws(_dev(leaf, torch.int32), _dev(inbag, torch.int16, (B, N)), N, B, leaf_bound,
+                                        count_dtype, layout, _dev(counts, cdt, s1), _dev(prox, torch.float32, s1), oob_layout,
+                                        _dev(num, cdt, s2), _dev(den, cdt, s2), _dev(prox_oob, torch.float32, s2), wp, wb,
+                                        _stream()))
+
+
+def prox_sparse_ws(leaf, leaf_bound: int, workspace, nnz, rows=None, cols=None, counts=None, prox=None, min_count: int = 1,
+                   count_dtype: int = U32):
+    """rfx_prox_sparse_ws: nnz is a CUDA int64 tensor of one element that receives the pair count; the
+    capacity is the length of rows (0 without it: count only); asynchronous."""
+    import torch
+    B, N = leaf.shape
+    cap = 0 if rows is None else rows.numel()
+    wp, wb = _ws_ptr(workspace)
+    _check(load().rfx_prox_sparse_ws(_dev(leaf, torch.int32), N, B, leaf_bound, min_count, count_dtype, cap,
+                                     _dev(rows, torch.int32), _dev(cols, torch.int32, (cap,)) if cols is not None else 0,
+                                     _dev(counts, _count_dtype(count_dtype), (cap,)) if counts is not None else 0,
+                                     _dev(prox, torch.float32, (cap,)) if prox is not None else 0,
+                                     _dev(nnz, torch.int64, (1,)), wp, wb, _stream()))
+
+
+def prox_outlier_ws(leaf, leaf_bound: int, workspace, labels=None, printed=None, classic=None):
+    """rfx_prox_outlier_ws; asynchronous."""
+    import torch
+    B, N = leaf.shape
+    wp, wb = _ws_ptr(workspace)
+    _check(load().rfx_prox_outlier_ws(_dev(leaf, torch.int32), N, B, leaf_bound, _dev(labels, torch.int32, (N,)),
+                                      _dev(printed, torch.float64, (N,)), _dev(classic, torch.float64, (N,)), wp, wb,
+                                      _stream()))
+
+
+def pv_plan_reserve(plan: "PvPlan", k: int):
+    """rfx_pv_plan_reserve."""
+    _check(load().rfx_pv_plan_reserve(plan._h, k))
+
+
+def pv_plan_info(plan: "PvPlan"):
+    """rfx_pv_plan_info: (N, B, reserved rank)."""
+    n, b, k = ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(load().rfx_pv_plan_info(plan._h, ctypes.byref(n), ctypes.byref(b), ctypes.byref(k)))
+    return n.value, b.value, k.value
+
+
+def lowrank_workspace_bytes(N: int, k: int) -> int:
+    """rfx_lowrank_workspace_bytes."""
+    out = ctypes.c_int64(0)
+    _check(load().rfx_lowrank_workspace_bytes(N, k, ctypes.byref(out)))
+    return out.value
+
+
+def prox_lowrank_plan(plan: "PvPlan", V0, iters: int, workspace, eigvals, V, Q=None, scales=None, status=None):
+    """rfx_prox_lowrank_plan: outputs are written into the given tensors; asynchronous."""
+    import torch
+    N, k = V0.shape
+    wp, wb = _ws_ptr(workspace)
+    _check(load().rfx_prox_lowrank_plan(plan._h, k, iters, _dev(V0, torch.float32, (N, k)), _dev(eigvals, torch.float32, (k,)),
+                                        _dev(V, torch.float32, (N, k)), _dev(Q, torch.int8, (N, k)),
+                                        _dev(scales, torch.float32, (k,)), _dev(status, torch.int32, (1,)), wp, wb, _stream()))
+
+
+def mds3d_workspace_bytes(N: int, k: int, m: int, mode: int = MDS_SQUARED) -> int:
+    """rfx_mds3d_workspace_bytes."""
+    out = ctypes.c_int64(0)
+    _check(load().rfx_mds3d_workspace_bytes(N, k, m, mode, ctypes.byref(out)))
+    return out.value
+
+
+def mds3d_ws(Q, scales, x0, iters: int, workspace, coords, eigvals, rel_change=None, mode: int = MDS_SQUARED):
+    """rfx_mds3d_ws: exactly `iters` applications of the Gram operator; asynchronous."""
+    import torch
+    N, k = Q.shape
+    m = x0.shape[1]
+    wp, wb = _ws_ptr(workspace)
+    _check(load().rfx_mds3d_ws(_dev(Q, torch.int8), _dev(scales, torch.float32, (k,)), N, k, mode, m, iters,
+                               _dev(x0, torch.float32, (N, m)), _dev(coords, torch.float32, (N, 3)),
+                               _dev(eigvals, torch.float32, (3,)), _dev(rel_change, torch.float32, (1,)), wp, wb, _stream()))

@@ -22,12 +22,18 @@ struct SmallWs {
     float* sign_val = nullptr;      // [256][k] and its value
     int gram_blocks = 0;
     DevBuf buf;
-    hipError_t alloc(int64_t N, int k);
+    // Either the scratch is carved from caller memory (`bytes` of it, 256-byte aligned; bind clears the status word
+    // with a kernel on `st`), or alloc takes it from hipMalloc and binds it.
+    static size_t bytes(int64_t N, int k);
+    int bind(void* mem, int64_t N, int k, hipStream_t st);
+    int alloc(int64_t N, int k, hipStream_t st);
 };
 
 // G = A^T Bm (k x k, float64), A and Bm float32 [N][k]; symmetrised (G + G^T)/2 if sym.
 int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& ws, double* G, hipStream_t st);
-// T = inverse of the upper Cholesky factor R of G (G = R^T R); sets *ws.flag on a bad pivot.
+// T = inverse of the upper Cholesky factor R of G (G = R^T R).  A column of G whose pivot is not positive (the
+// column of the block lies in the span of the columns before it) sets *ws.flag and is dropped: row and column of T
+// are zero, so the orthonormalised block gets a zero column there.
 int chol_inverse(const double* G, int k, SmallWs& ws, double* T, hipStream_t st);
 // Eigen-decomposition of the symmetric k x k matrix H: theta descending, W columns = vectors.
 int jacobi_eigh(const double* H, int k, SmallWs& ws, double* theta, double* W, hipStream_t st);

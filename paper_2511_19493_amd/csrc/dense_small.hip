@@ -134,12 +134,16 @@ __global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restr
     for (int j = 0; j < k; ++j) scale = fmax(scale, R[j * k + j]);
     for (int j = 0; j < k; ++j) {
         if (threadIdx.x == 0) {
-            double d = R[j * k + j];
+            const double d = R[j * k + j];
             if (!(d > scale * 1e-28)) {
-                *flag = 1;  // numerically rank-deficient block
-                d = scale > 0.0 ? scale * 1e-28 : 1.0;
+                // Column j lies in the span of the columns before it: the flag reports it, and an infinite pivot
+                // drops the column (row j of the factor and column j of its inverse become zero, so column j of
+                // the orthonormalised block is a zero vector and the remaining columns are unaffected).
+                *flag = 1;
+                R[j * k + j] = __builtin_inf();
+            } else {
+                R[j * k + j] = sqrt(d);
             }
-            R[j * k + j] = sqrt(d);
         }
         __syncthreads();
         const double piv = R[j * k + j];
@@ -155,7 +159,7 @@ __global__ __launch_bounds__(256) void chol_inverse_kernel(const double* __restr
     }
     for (int c = threadIdx.x; c < k; c += 256) {
         for (int r = k - 1; r > c; --r) T[r * k + c] = 0.0;
-        T[c * k + c] = 1.0 / R[c * k + c];
+        T[c * k + c] = 1.0 / R[c * k + c];  // 0 for a dropped column
         for (int r = c - 1; r >= 0; --r) {
             double s = 0.0;
             for (int p = r + 1; p <= c; ++p) s += R[r * k + p] * T[p * k + c];
@@ -201,14 +205,16 @@ __global__ __launch_bounds__(256) void chol_inverse_fast_kernel(const double* __
     for (int j = 0; j < k; ++j) scale = fmax(scale, dinv[j]);
     for (int j = 0; j < k; ++j) {
         const double* pr = piv + (j & 1) * k;
-        double d = pr[j];
-        if (!(d > scale * 1e-28)) {
-            if (threadIdx.x == 0) *flag = 1;  // numerically rank-deficient block
-            d = scale > 0.0 ? scale * 1e-28 : 1.0;
-        }
-        const double inv = 1.0 / d, rs = sqrt(inv);
+        const double d = pr[j];
+        // A pivot that is not positive at the scale of the matrix: column j lies in the span of the columns
+        // before it.  The flag reports it and the column is dropped: with 1 / d taken as 0 and the diagonal of the
+        // factor as infinity, row j of the factor and column j of its inverse are zero, so column j of the
+        // orthonormalised block is a zero vector and the remaining columns are unaffected.
+        const bool dependent = !(d > scale * 1e-28);
+        if (dependent && threadIdx.x == 0) *flag = 1;
+        const double inv = dependent ? 0.0 : 1.0 / d, rs = sqrt(inv);
         if ((int)threadIdx.x >= j && (int)threadIdx.x < k)
-            R[j * k + threadIdx.x] = ((int)threadIdx.x == j) ? d * rs : pr[threadIdx.x] * rs;
+            R[j * k + threadIdx.x] = ((int)threadIdx.x == j) ? (dependent ? __builtin_inf() : d * rs) : pr[threadIdx.x] * rs;
         double fr[NB16], pc[NB16];
 #pragma unroll
         for (int ia = 0; ia < NB16; ++ia) {
@@ -538,14 +544,31 @@ hipError_t allow_lds(K kern, size_t bytes) {
 
 }  // namespace
 
-hipError_t SmallWs::alloc(int64_t N, int k) {
-    gram_blocks = (int)std::min<int64_t>(512, ceil_div(N, 64 * kGramWaves));  // workgroups of the Gram kernel
+namespace {
+__global__ void clear_flag_kernel(int* flag) { *flag = 0; }
+
+struct SmallLayout {
+    int gram_blocks;
+    size_t doubles, sign_entries, total;
+};
+SmallLayout small_layout(int64_t N, int k) {
+    SmallLayout l;
+    l.gram_blocks = (int)std::min<int64_t>(512, ceil_div(N, 64 * kGramWaves));  // workgroups of the Gram kernel
     const size_t kk = (size_t)k * k;
-    const size_t doubles = (size_t)gram_blocks * kk + 3 * kk + (size_t)k + kk /*jacobi work*/;
-    const size_t sign_entries = (size_t)kSignBlocks * k;
-    hipError_t e = buf.alloc(doubles * sizeof(double) + 64 + sign_entries * (sizeof(long long) + sizeof(float)));
-    if (e != hipSuccess) return e;
-    double* p = buf.as<double>();
+    l.doubles = (size_t)l.gram_blocks * kk + 3 * kk + (size_t)k + kk /*jacobi work*/;
+    l.sign_entries = (size_t)kSignBlocks * k;
+    l.total = l.doubles * sizeof(double) + 64 + l.sign_entries * (sizeof(long long) + sizeof(float));
+    return l;
+}
+}  // namespace
+
+size_t SmallWs::bytes(int64_t N, int k) { return (small_layout(N, k).total + 255) & ~(size_t)255; }
+
+int SmallWs::bind(void* mem, int64_t N, int k, hipStream_t st) {
+    const SmallLayout l = small_layout(N, k);
+    gram_blocks = l.gram_blocks;
+    const size_t kk = (size_t)k * k;
+    double* p = static_cast<double*>(mem);
     partial = p;
     p += (size_t)gram_blocks * kk;
     G = p;
@@ -560,8 +583,15 @@ hipError_t SmallWs::alloc(int64_t N, int k) {
     flag = (int*)p;
     p += 8;  // 64 bytes for the status word
     sign_row = (long long*)p;
-    sign_val = (float*)(sign_row + sign_entries);
-    return hipMemset(flag, 0, sizeof(int));
+    sign_val = (float*)(sign_row + l.sign_entries);
+    hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, st, flag);
+    RFX_LAUNCH_CHECK("clear_flag_kernel");
+    return RFX_OK;
+}
+
+int SmallWs::alloc(int64_t N, int k, hipStream_t st) {
+    RFX_HIP(buf.alloc(bytes(N, k)));
+    return bind(buf.p, N, k, st);
 }
 
 int gram(const float* A, const float* Bm, int64_t N, int k, bool sym, SmallWs& ws, double* G, hipStream_t st) {

@@ -21,6 +21,8 @@
 // strict upper triangle, only values that reach a threshold): instead of writing its tile, a wave
 // compacts the pairs whose count reaches min_count and appends them to a coordinate list.
 #include <algorithm>
+#include <mutex>
+#include <optional>
 
 #include "common.h"
 
@@ -631,7 +633,8 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(P, kMode)) void prox_til
 }
 
 template <int P, int J, int kMode>
-int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, const TileOut& out2, hipStream_t st) {
+int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, const TileOut& out2, hipStream_t st,
+                 bool timing) {
     constexpr int kRatio = kATile / (J * kWaves);
     const int64_t rows = Npad / kATile;
     // XCD x works through tile rows x, x+8, ...; the last XCD that has `cnt` rows has the longest list
@@ -648,7 +651,10 @@ int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut&
     static_assert(sizeof(uint32_t) * kWaves * 64 * (J + 4) >= 16 * kWaves * kATile, "outlier sums reuse the transposition buffers");
     const size_t lds = sizeof(uint32_t) * kWaves * 64 * (J + 4) +
                        (o.use_tab ? sizeof(float) * (size_t)(out.B + 1) : 0);
-    rfx::TimedLaunch timed(kMode == kModeBoth ? "prox_tile_kernel_both" : kOob ? "prox_tile_kernel_oob" : (kMode == kModeSparse ? "prox_tile_kernel_sparse" : (kMode == kModeOutlier ? "prox_tile_kernel_outlier" : "prox_tile_kernel")), st);
+    // the event pair of the timing aid is created only when a caller may allocate
+    std::optional<rfx::TimedLaunch> timed;
+    if (timing)
+        timed.emplace(kMode == kModeBoth ? "prox_tile_kernel_both" : kOob ? "prox_tile_kernel_oob" : (kMode == kModeSparse ? "prox_tile_kernel_sparse" : (kMode == kModeOutlier ? "prox_tile_kernel_outlier" : "prox_tile_kernel")), st);
     hipLaunchKernelGGL((prox_tile_kernel<P, J, kMode>), dim3((unsigned)blocks), dim3(64 * kWaves), lds, st, planes, Npad, G,
                        (int32_t)rows, o, out2);
     RFX_LAUNCH_CHECK("prox_tile_kernel");
@@ -657,7 +663,7 @@ int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut&
 
 template <int kMode>
 int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, const TileOut& out2,
-                    hipStream_t st) {
+                    hipStream_t st, bool timing) {
 #ifndef RFX_J_PLAIN
 #define RFX_J_PLAIN 16
 #endif
@@ -665,7 +671,7 @@ int dispatch_planes(int P, const uint32_t* planes, int64_t Npad, int32_t G, cons
     switch (P) {
 #define RFX_CASE(p) \
     case p:         \
-        return launch_tiles<p, J, kMode>(planes, Npad, G, out, out2, st);
+        return launch_tiles<p, J, kMode>(planes, Npad, G, out, out2, st, timing);
 #ifdef RFX_ONLY_P  // development builds: a single plane count compiles in seconds
         RFX_CASE(RFX_ONLY_P)
 #else
@@ -702,62 +708,148 @@ int planes_for(int32_t leaf_bound) {
     return P <= 16 ? P : (P + 1) & ~1;
 }
 
+// Scratch of one call, carved from a caller's workspace: the bit planes, then (outlier pass) the two per-sample
+// sums, then (sparse pass) the 64-bit cursor.  Every part starts on a 256-byte boundary.
+struct ProxScratch {
+    size_t plane_bytes, sums_off, cursor_off, total;
+};
+ProxScratch prox_scratch(int64_t N, int32_t B, int32_t leaf_bound) {
+    const int P = planes_for(leaf_bound);
+    const int PS = plane_stride(P);
+    const size_t G = (size_t)((B + 31) / 32);
+    const size_t Npad = (size_t)(rfx::ceil_div(N, kATile) * kATile);
+    ProxScratch s;
+    s.plane_bytes = sizeof(uint32_t) * G * Npad * (size_t)PS;
+    s.sums_off = (s.plane_bytes + 255) & ~(size_t)255;
+    s.cursor_off = s.sums_off + ((16 * (size_t)N + 255) & ~(size_t)255);
+    s.total = s.cursor_off + 256;
+    return s;
+}
+
+int check_workspace(const char* who, const void* workspace, int64_t workspace_bytes, const ProxScratch& need) {
+    if (!workspace) return rfx::fail(RFX_ERR_NULL, "%s: workspace is null", who);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return rfx::fail(RFX_ERR_INVALID_ARG, "%s: workspace is not 256-byte aligned", who);
+    if (workspace_bytes < 0 || (size_t)workspace_bytes < need.total)
+        return rfx::fail(RFX_ERR_CAPACITY, "%s: workspace of %lld bytes, %zu needed", who, (long long)workspace_bytes, need.total);
+    return RFX_OK;
+}
+
+__global__ void zero_words_kernel(uint32_t* p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+int zero_words(void* p, size_t bytes, hipStream_t st) {
+    const int64_t n = (int64_t)(bytes / 4);
+    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)rfx::ceil_div(n, 256)), dim3(256), 0, st, static_cast<uint32_t*>(p), n);
+    RFX_LAUNCH_CHECK("zero_words_kernel");
+    return RFX_OK;
+}
+
+// Enqueues the transposition into bit planes and the tile pass on `st`; `planes` is scratch of
+// prox_scratch(...).plane_bytes bytes that must stay untouched until the kernels have run.  No allocation, no
+// synchronisation.
 template <int kMode>
-int run(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound, const TileOut& out,
-        hipStream_t st, const TileOut& out2 = TileOut{}) {
+int enqueue(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound, const TileOut& out,
+            hipStream_t st, uint32_t* planes, const TileOut& out2 = TileOut{}, bool timing = true) {
     const int P = planes_for(leaf_bound);
     const int PS = plane_stride(P);
     const int32_t G = (B + 31) / 32;
     const int64_t Npad = rfx::ceil_div(N, kATile) * kATile;
-    rfx::DevBuf planes;
-    RFX_HIP(planes.alloc(sizeof(uint32_t) * (size_t)G * (size_t)Npad * (size_t)PS));
     hipLaunchKernelGGL(pack_planes_kernel, dim3((unsigned)rfx::ceil_div(Npad, 256), (unsigned)G), dim3(256), 0, st, leaf,
-                       inbag, N, B, Npad, P, PS, planes.as<uint32_t>());
+                       inbag, N, B, Npad, P, PS, planes);
     RFX_LAUNCH_CHECK("pack_planes_kernel");
-    int rc = dispatch_planes<kMode>(P, planes.as<uint32_t>(), Npad, G, out, out2, st);
-    // the scratch is freed on return, so wait for the kernels that read it
-    hipError_t e = hipStreamSynchronize(st);
+    return dispatch_planes<kMode>(P, planes, Npad, G, out, out2, st, timing);
+}
+
+// The synchronous conveniences: scratch allocated for the call, the asynchronous variant, a wait, the scratch freed.
+template <class Call>
+int with_own_workspace(const char* who, int64_t N, int32_t B, int32_t leaf_bound, hipStream_t st, Call&& call) {
+    const ProxScratch need = prox_scratch(N, B, leaf_bound);
+    rfx::DevBuf ws;
+    RFX_HIP(ws.alloc(need.total));
+    int rc = call(ws.p, (int64_t)need.total);
+    hipError_t e = hipStreamSynchronize(st);  // the scratch is freed on return
     if (rc != RFX_OK) return rc;
-    if (e != hipSuccess) return rfx::fail(RFX_ERR_HIP, "proximity kernels failed: %s", hipGetErrorString(e));
+    if (e != hipSuccess) return rfx::fail(RFX_ERR_HIP, "%s: kernels failed: %s", who, hipGetErrorString(e));
     return RFX_OK;
 }
 
 }  // namespace
 
+// RFX_TILE_MODE (0..4), when defined, compiles the entry points of one mode only, so that the build can
+// compile the five sets of kernel instantiations side by side.
 extern "C" {
 
-// RFX_TILE_MODE (0..4), when defined, compiles the entry point of one mode only, so that the build can
-// compile the four sets of kernel instantiations side by side.
 #if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 0
-int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
-                   void* counts, float* prox, void* stream) {
+int rfx_prox_workspace_bytes(int64_t N, int32_t B, int32_t leaf_bound, int64_t* bytes) {
+    if (!bytes) return rfx::fail(RFX_ERR_NULL, "rfx_prox_workspace_bytes: bytes is null");
+    int rc = check_common("rfx_prox_workspace_bytes", bytes, N, B, leaf_bound, RFX_U32, RFX_FULL);
+    if (rc != RFX_OK) return rc;
+    *bytes = (int64_t)prox_scratch(N, B, leaf_bound).total;
+    return RFX_OK;
+}
+
+static int check_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
+                       const void* counts, const float* prox) {
     int rc = check_common("rfx_prox_dense", leaf, N, B, leaf_bound, count_dtype, layout);
     if (rc != RFX_OK) return rc;
     if (!counts && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_dense: neither counts nor prox given");
-    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
-    return run<kModePlain>(leaf, nullptr, N, B, leaf_bound, out, rfx::as_stream(stream));
+    return RFX_OK;
 }
 
+int rfx_prox_dense_ws(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
+                      void* counts, float* prox, void* workspace, int64_t workspace_bytes, void* stream) {
+    int rc = check_dense(leaf, N, B, leaf_bound, count_dtype, layout, counts, prox);
+    if (rc != RFX_OK) return rc;
+    if ((rc = check_workspace("rfx_prox_dense", workspace, workspace_bytes, prox_scratch(N, B, leaf_bound))) != RFX_OK) return rc;
+    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
+    return enqueue<kModePlain>(leaf, nullptr, N, B, leaf_bound, out, rfx::as_stream(stream), static_cast<uint32_t*>(workspace));
+}
+
+int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
+                   void* counts, float* prox, void* stream) {
+    int rc = check_dense(leaf, N, B, leaf_bound, count_dtype, layout, counts, prox);
+    if (rc != RFX_OK) return rc;
+    return with_own_workspace("rfx_prox_dense", N, B, leaf_bound, rfx::as_stream(stream), [&](void* ws, int64_t bytes) {
+        return rfx_prox_dense_ws(leaf, N, B, leaf_bound, count_dtype, layout, counts, prox, ws, bytes, stream);
+    });
+}
 #endif
 
 #if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 1
-int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
-                 int count_dtype, int layout, void* num, void* den, float* prox, void* stream) {
+static int check_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype,
+                     int layout, const void* num, const void* den, const float* prox) {
     int rc = check_common("rfx_prox_oob", leaf, N, B, leaf_bound, count_dtype, layout);
     if (rc != RFX_OK) return rc;
     if (!inbag) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: inbag is null");
     if (B > 65535) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_oob: more than 65535 trees");
     if (!num && !den && !prox) return rfx::fail(RFX_ERR_NULL, "rfx_prox_oob: no output given");
-    TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
-    return run<kModeOob>(leaf, inbag, N, B, leaf_bound, out, rfx::as_stream(stream));
+    return RFX_OK;
 }
 
+int rfx_prox_oob_ws(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype,
+                    int layout, void* num, void* den, float* prox, void* workspace, int64_t workspace_bytes, void* stream) {
+    int rc = check_oob(leaf, inbag, N, B, leaf_bound, count_dtype, layout, num, den, prox);
+    if (rc != RFX_OK) return rc;
+    if ((rc = check_workspace("rfx_prox_oob", workspace, workspace_bytes, prox_scratch(N, B, leaf_bound))) != RFX_OK) return rc;
+    TileOut out{num, den, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
+    return enqueue<kModeOob>(leaf, inbag, N, B, leaf_bound, out, rfx::as_stream(stream), static_cast<uint32_t*>(workspace));
+}
+
+int rfx_prox_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
+                 int count_dtype, int layout, void* num, void* den, float* prox, void* stream) {
+    int rc = check_oob(leaf, inbag, N, B, leaf_bound, count_dtype, layout, num, den, prox);
+    if (rc != RFX_OK) return rc;
+    return with_own_workspace("rfx_prox_oob", N, B, leaf_bound, rfx::as_stream(stream), [&](void* ws, int64_t bytes) {
+        return rfx_prox_oob_ws(leaf, inbag, N, B, leaf_bound, count_dtype, layout, num, den, prox, ws, bytes, stream);
+    });
+}
 #endif
 
 #if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 2
-int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count, int count_dtype,
-                    int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox, int64_t* nnz,
-                    void* stream) {
+static int check_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count, int count_dtype,
+                        int64_t capacity, const uint32_t* rows, const uint32_t* cols, const void* nnz) {
     int rc = check_common("rfx_prox_sparse", leaf, N, B, leaf_bound, count_dtype, RFX_UPPER_PACKED);
     if (rc != RFX_OK) return rc;
     if (!nnz) return rfx::fail(RFX_ERR_NULL, "rfx_prox_sparse: nnz is null");
@@ -765,29 +857,51 @@ int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
     if (capacity < 0) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_sparse: capacity=%lld", (long long)capacity);
     if (capacity > 0 && (!rows || !cols)) return rfx::fail(RFX_ERR_NULL, "rfx_prox_sparse: rows / cols are null");
     if (B >= (1 << 20)) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_sparse: 2^20 trees or more");
-    hipStream_t st = rfx::as_stream(stream);
-    rfx::DevBuf cursor;
-    RFX_HIP(cursor.alloc(sizeof(unsigned long long)));
-    RFX_HIP(hipMemsetAsync(cursor.p, 0, sizeof(unsigned long long), st));
-    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, 1, 0, rows, cols, cursor.as<unsigned long long>(),
-                (unsigned long long)capacity, (uint32_t)min_count, nullptr, nullptr, nullptr};
-    rc = run<kModeSparse>(leaf, nullptr, N, B, leaf_bound, out, st);
+    return RFX_OK;
+}
+
+int rfx_prox_sparse_ws(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count, int count_dtype,
+                       int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox, uint64_t* nnz,
+                       void* workspace, int64_t workspace_bytes, void* stream) {
+    int rc = check_sparse(leaf, N, B, leaf_bound, min_count, count_dtype, capacity, rows, cols, nnz);
     if (rc != RFX_OK) return rc;
+    if (reinterpret_cast<uintptr_t>(nnz) % 8 != 0) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_sparse: nnz is not 8-byte aligned");
+    if ((rc = check_workspace("rfx_prox_sparse", workspace, workspace_bytes, prox_scratch(N, B, leaf_bound))) != RFX_OK) return rc;
+    hipStream_t st = rfx::as_stream(stream);
+    if ((rc = zero_words(nnz, sizeof(uint64_t), st)) != RFX_OK) return rc;
+    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, 1, 0, rows, cols, reinterpret_cast<unsigned long long*>(nnz),
+                (unsigned long long)capacity, (uint32_t)min_count, nullptr, nullptr, nullptr};
+    return enqueue<kModeSparse>(leaf, nullptr, N, B, leaf_bound, out, st, static_cast<uint32_t*>(workspace));
+}
+
+int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count, int count_dtype,
+                    int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox, int64_t* nnz,
+                    void* stream) {
+    int rc = check_sparse(leaf, N, B, leaf_bound, min_count, count_dtype, capacity, rows, cols, nnz);
+    if (rc != RFX_OK) return rc;
+    const ProxScratch need = prox_scratch(N, B, leaf_bound);
     unsigned long long total = 0;
-    RFX_HIP(hipMemcpy(&total, cursor.p, sizeof(total), hipMemcpyDeviceToHost));
+    rc = with_own_workspace("rfx_prox_sparse", N, B, leaf_bound, rfx::as_stream(stream), [&](void* ws, int64_t bytes) {
+        uint64_t* cursor = reinterpret_cast<uint64_t*>(static_cast<char*>(ws) + need.cursor_off);
+        int r = rfx_prox_sparse_ws(leaf, N, B, leaf_bound, min_count, count_dtype, capacity, rows, cols, counts, prox, cursor,
+                                   ws, bytes, stream);
+        if (r != RFX_OK) return r;
+        RFX_HIP(hipMemcpyAsync(&total, cursor, sizeof(total), hipMemcpyDeviceToHost, rfx::as_stream(stream)));
+        return RFX_OK;
+    });
+    if (rc != RFX_OK) return rc;
     *nnz = (int64_t)total;
     if (total > (unsigned long long)capacity && capacity > 0)
         return rfx::fail(RFX_ERR_CAPACITY, "rfx_prox_sparse: %llu pairs reach the threshold, capacity is %lld", total,
                          (long long)capacity);
     return RFX_OK;
 }
-
 #endif
 
 #if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 4
-int rfx_prox_dense_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
-                       int count_dtype, int layout, void* counts, float* prox, int oob_layout, void* num, void* den,
-                       float* prox_oob, void* stream) {
+static int check_both(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype,
+                      int layout, const void* counts, const float* prox, int oob_layout, const void* num, const void* den,
+                      const float* prox_oob) {
     int rc = check_common("rfx_prox_dense_oob", leaf, N, B, leaf_bound, count_dtype, layout);
     if (rc != RFX_OK) return rc;
     if (oob_layout != RFX_FULL && oob_layout != RFX_UPPER_PACKED)
@@ -796,36 +910,71 @@ int rfx_prox_dense_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, i
     if (B > 1023) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_dense_oob: more than 1023 trees");
     if ((!counts && !prox) || (!num && !den && !prox_oob))
         return rfx::fail(RFX_ERR_NULL, "rfx_prox_dense_oob: an output of each kind is required");
+    return RFX_OK;
+}
+
+int rfx_prox_dense_oob_ws(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
+                          int count_dtype, int layout, void* counts, float* prox, int oob_layout, void* num, void* den,
+                          float* prox_oob, void* workspace, int64_t workspace_bytes, void* stream) {
+    int rc = check_both(leaf, inbag, N, B, leaf_bound, count_dtype, layout, counts, prox, oob_layout, num, den, prox_oob);
+    if (rc != RFX_OK) return rc;
+    if ((rc = check_workspace("rfx_prox_dense_oob", workspace, workspace_bytes, prox_scratch(N, B, leaf_bound))) != RFX_OK) return rc;
     TileOut plain{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
     TileOut oob{num, den, prox_oob, N, B, count_dtype == RFX_U16, oob_layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
-    return run<kModeBoth>(leaf, inbag, N, B, leaf_bound, plain, rfx::as_stream(stream), oob);
+    return enqueue<kModeBoth>(leaf, inbag, N, B, leaf_bound, plain, rfx::as_stream(stream), static_cast<uint32_t*>(workspace), oob);
+}
+
+int rfx_prox_dense_oob(const uint32_t* leaf, const uint16_t* inbag, int64_t N, int32_t B, int32_t leaf_bound,
+                       int count_dtype, int layout, void* counts, float* prox, int oob_layout, void* num, void* den,
+                       float* prox_oob, void* stream) {
+    int rc = check_both(leaf, inbag, N, B, leaf_bound, count_dtype, layout, counts, prox, oob_layout, num, den, prox_oob);
+    if (rc != RFX_OK) return rc;
+    return with_own_workspace("rfx_prox_dense_oob", N, B, leaf_bound, rfx::as_stream(stream), [&](void* ws, int64_t bytes) {
+        return rfx_prox_dense_oob_ws(leaf, inbag, N, B, leaf_bound, count_dtype, layout, counts, prox, oob_layout, num, den,
+                                     prox_oob, ws, bytes, stream);
+    });
 }
 #endif
 
 #if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 3
-int rfx_prox_outlier(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const int32_t* labels,
-                     double* printed, double* classic, void* stream) {
+static int check_outlier(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const double* printed,
+                         const double* classic) {
     int rc = check_common("rfx_prox_outlier", leaf, N, B, leaf_bound, RFX_U32, RFX_FULL);
     if (rc != RFX_OK) return rc;
     if (!printed && !classic) return rfx::fail(RFX_ERR_NULL, "rfx_prox_outlier: neither output given");
     if (N < 2) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_outlier: needs at least 2 samples");
     if (B >= (1 << 20)) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_outlier: 2^20 trees or more");
+    return RFX_OK;
+}
+
+int rfx_prox_outlier_ws(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const int32_t* labels,
+                        double* printed, double* classic, void* workspace, int64_t workspace_bytes, void* stream) {
+    int rc = check_outlier(leaf, N, B, leaf_bound, printed, classic);
+    if (rc != RFX_OK) return rc;
+    const ProxScratch need = prox_scratch(N, B, leaf_bound);
+    if ((rc = check_workspace("rfx_prox_outlier", workspace, workspace_bytes, need)) != RFX_OK) return rc;
     hipStream_t st = rfx::as_stream(stream);
-    rfx::DevBuf sums;  // inv [N] float64, then sq [N] uint64
-    RFX_HIP(sums.alloc(16 * (size_t)N));
-    RFX_HIP(hipMemsetAsync(sums.p, 0, 16 * (size_t)N, st));
-    double* inv = sums.as<double>();
+    // inv [N] float64, then sq [N] uint64
+    double* inv = reinterpret_cast<double*>(static_cast<char*>(workspace) + need.sums_off);
     unsigned long long* sq = reinterpret_cast<unsigned long long*>(inv + N);
+    if ((rc = zero_words(inv, 16 * (size_t)N, st)) != RFX_OK) return rc;
     TileOut out{nullptr, nullptr, nullptr, N, B, 0, 0, 0, nullptr, nullptr, nullptr, 0, 0, printed ? inv : nullptr,
                 classic ? sq : nullptr, labels};
-    rc = run<kModeOutlier>(leaf, nullptr, N, B, leaf_bound, out, st);
+    rc = enqueue<kModeOutlier>(leaf, nullptr, N, B, leaf_bound, out, st, static_cast<uint32_t*>(workspace));
     if (rc != RFX_OK) return rc;
     hipLaunchKernelGGL(outlier_finalise_kernel, dim3((unsigned)rfx::ceil_div(N, 256)), dim3(256), 0, st, inv, sq, N, B,
                        printed, classic);
     RFX_LAUNCH_CHECK("outlier_finalise_kernel");
-    RFX_HIP(hipStreamSynchronize(st));  // the sums are freed on return
     return RFX_OK;
 }
 
+int rfx_prox_outlier(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, const int32_t* labels,
+                     double* printed, double* classic, void* stream) {
+    int rc = check_outlier(leaf, N, B, leaf_bound, printed, classic);
+    if (rc != RFX_OK) return rc;
+    return with_own_workspace("rfx_prox_outlier", N, B, leaf_bound, rfx::as_stream(stream), [&](void* ws, int64_t bytes) {
+        return rfx_prox_outlier_ws(leaf, N, B, leaf_bound, labels, printed, classic, ws, bytes, stream);
+    });
+}
 #endif
 }  // extern "C"

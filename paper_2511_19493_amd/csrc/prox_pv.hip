@@ -659,19 +659,36 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
     return RFX_OK;
 }
 
+int rfx_pv_plan_reserve(rfx_pv_plan* p, int32_t k) {
+    if (!p) return rfx::fail(RFX_ERR_NULL, "rfx_pv_plan_reserve: plan is null");
+    if (k < 1 || k > 256) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_plan_reserve: k=%d outside 1..256", k);
+    if (k <= p->k_cap) return RFX_OK;
+    // earlier applications on any stream may still read the old buffer
+    RFX_HIP(hipDeviceSynchronize());
+    if (p->d_S) (void)hipFree(p->d_S);
+    p->d_S = nullptr;
+    p->k_cap = 0;
+    RFX_HIP(hipMalloc((void**)&p->d_S, sizeof(float) * (size_t)p->B * (size_t)p->Lb * (size_t)k));
+    p->k_cap = k;
+    return RFX_OK;
+}
+
+int rfx_pv_plan_info(const rfx_pv_plan* p, int64_t* N, int32_t* B, int32_t* k_reserved) {
+    if (!p) return rfx::fail(RFX_ERR_NULL, "rfx_pv_plan_info: plan is null");
+    if (N) *N = p->N;
+    if (B) *B = p->B;
+    if (k_reserved) *k_reserved = p->k_cap;
+    return RFX_OK;
+}
+
 int rfx_pv_apply(rfx_pv_plan* p, const float* V, int32_t k, float* Y, void* stream) {
     if (!p || !V || !Y) return rfx::fail(RFX_ERR_NULL, "rfx_pv_apply: null argument");
     if (k < 1 || k > 256) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_apply: k=%d outside 1..256", k);
     if (V == Y) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_apply: V and Y must not overlap");
     hipStream_t st = rfx::as_stream(stream);
     if (k > p->k_cap) {
-        // earlier applies on any stream may still read the old buffer
-        RFX_HIP(hipDeviceSynchronize());
-        if (p->d_S) (void)hipFree(p->d_S);
-        p->d_S = nullptr;
-        p->k_cap = 0;
-        RFX_HIP(hipMalloc((void**)&p->d_S, sizeof(float) * (size_t)p->B * (size_t)p->Lb * (size_t)k));
-        p->k_cap = k;
+        int rc = rfx_pv_plan_reserve(p, k);
+        if (rc != RFX_OK) return rc;
     }
     if (k <= 16) return launch_apply<1, 4>(p, V, k, Y, st);
     if (k <= 32) return launch_apply<1, 2>(p, V, k, Y, st);

@@ -10,7 +10,7 @@ measured data set is 178 rows x 13 features in 3 classes (Results,
 "Memory Feasibility Analysis").  Those records are not available, so seeded
 Gaussian mixtures of the same shapes stand in for them.
 """
-from .mixture import CONFIGS, WorkloadConfig, gaussian_mixture, start_block, workload
+from .mixture import CONFIGS, WorkloadConfig, gaussian_mixture, random_int8_factor, start_block, workload
 from .forest import Forest, build_grower, grow_forest, leaf_classes, load_or_grow
 
 __all__ = [
@@ -18,6 +18,7 @@ __all__ = [
     "WorkloadConfig",
     "gaussian_mixture",
     "start_block",
+    "random_int8_factor",
     "workload",
     "Forest",
     "build_grower",

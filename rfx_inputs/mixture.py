@@ -86,5 +86,19 @@ def start_block(N: int, k: int, seed: int = START_SEED) -> np.ndarray:
     return rng.standard_normal((N, k)).astype(np.float32)
 
 
+def random_int8_factor(N: int, k: int, spread: float, seed: int):
+    """A synthetic INT8 factor that is not a proximity factor: codes round(127 z / max|z|) of iid N(0,1) draws z
+    per column and scales spread * max|z| / 127, so that the rows of Q diag(scales) are about N(0, spread^2 I).
+    With a spread of 1 or more the element-wise square of P^ = A A^T outweighs P^ itself, which makes the
+    squared-dissimilarity Gram matrix of the scaling step strongly indefinite: the case a solver that
+    converges to the largest magnitudes gets wrong.  Returns (Q int8 [N][k], scales float32 [k])."""
+    rng = np.random.default_rng(seed)
+    z = rng.standard_normal((N, k))
+    top = np.abs(z).max(axis=0)
+    Q = np.rint(127.0 * z / top[None, :]).astype(np.int8)
+    scales = (spread * top / 127.0).astype(np.float32)
+    return Q, scales
+
+
 def workload(cfg: int) -> WorkloadConfig:
     return CONFIGS[cfg]

@@ -62,6 +62,29 @@ def test_host_side_argument_checks():
     assert lib.rfx_forest_grow(fake, fake, 100, 4, 65, 0, 1, 2, 7, ctypes.byref(h), None) == rfx.ERR_INVALID_ARG
     assert lib.rfx_forest_grow(fake, None, 100, 4, 2, 0, 1, 2, 7, ctypes.byref(h), None) == rfx.ERR_NULL
     assert lib.rfx_grown_sizes(None, None, None, None, None) == rfx.ERR_NULL
+    # asynchronous forms: workspace size queries and their argument checks run without a device
+    nb = ctypes.c_int64(0)
+    assert lib.rfx_prox_workspace_bytes(1000, 100, 300, ctypes.byref(nb)) == 0
+    planes = 4 * 4 * 1024 * 12                                  # 4 tree groups x 1024 padded samples x 12 words
+    assert nb.value == planes + 16128 + 256                     # + per-sample sums (16 N, padded) + counter
+    assert lib.rfx_prox_workspace_bytes(0, 100, 300, ctypes.byref(nb)) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_prox_workspace_bytes(1000, 100, 300, None) == rfx.ERR_NULL
+    assert lib.rfx_prox_dense_ws(fake, 10, 4, 8, rfx.U32, rfx.FULL, fake, None, None, 1 << 20, None) == rfx.ERR_NULL
+    assert lib.rfx_prox_dense_ws(fake, 10, 4, 8, rfx.U32, rfx.FULL, fake, None, fake, 100, None) == rfx.ERR_CAPACITY
+    assert lib.rfx_prox_dense_ws(fake, 10, 4, 8, rfx.U32, rfx.FULL, fake, None, ctypes.c_void_p(0x1010), 1 << 20, None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_prox_sparse_ws(fake, 10, 4, 8, 1, rfx.U32, 0, None, None, None, None, ctypes.c_void_p(0x1004), fake, 1 << 20, None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_prox_outlier_ws(fake, 10, 4, 8, None, fake, None, fake, 16, None) == rfx.ERR_CAPACITY
+    assert lib.rfx_lowrank_workspace_bytes(1000, 16, ctypes.byref(nb)) == 0 and nb.value > 2 * 1000 * 16 * 4
+    assert lib.rfx_lowrank_workspace_bytes(10, 16, ctypes.byref(nb)) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_prox_lowrank_plan(None, 4, 5, fake, fake, fake, None, None, None, fake, 1 << 20, None) == rfx.ERR_NULL
+    assert lib.rfx_pv_plan_reserve(None, 4) == rfx.ERR_NULL and lib.rfx_pv_plan_info(None, None, None, None) == rfx.ERR_NULL
+    assert lib.rfx_mds3d_workspace_bytes(1000, 16, 12, rfx.MDS_SQUARED, ctypes.byref(nb)) == 0 and nb.value > 3 * 1000 * 12 * 4
+    sq = nb.value
+    assert lib.rfx_mds3d_workspace_bytes(1000, 16, 12, rfx.MDS_LINEAR, ctypes.byref(nb)) == 0 and nb.value < sq
+    assert lib.rfx_mds3d_workspace_bytes(1000, 16, 2, rfx.MDS_SQUARED, ctypes.byref(nb)) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_mds3d_ws(fake, fake, 1000, 16, rfx.MDS_SQUARED, 12, 10, fake, fake, fake, None, fake, 64, None) == rfx.ERR_CAPACITY
+    assert lib.rfx_mds3d_ws(fake, fake, 1000, 16, rfx.MDS_SQUARED, 12, 0, fake, fake, fake, None, fake, 1 << 30, None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_mds3d(fake, fake, 1000, 16, rfx.MDS_SQUARED, 12, 10, -1.0, fake, fake, fake, None, None) == rfx.ERR_INVALID_ARG
     out = ctypes.c_double(0)
     assert lib.rfx_probe_valu(0, ctypes.byref(out), None) == rfx.ERR_INVALID_ARG
     assert lib.rfx_probe_copy(5, ctypes.byref(out), None) == rfx.ERR_INVALID_ARG

@@ -242,3 +242,55 @@ def test_mds_small_blocks_and_linear_rank(torch_cuda, cfg1):
     q = torch.from_numpy(Qh).cuda()
     assert lib.rfx_mds3d(q.data_ptr(), q.data_ptr(), N, 8, 0, 2, 10, 1e-6, q.data_ptr(), q.data_ptr(), q.data_ptr(), None,
                          None) == -1   # block narrower than 3
+
+
+@pytest.mark.parametrize("N,k,spread,m,seed", [(400, 4, 1.5, 8, 31), (500, 8, 1.0, 12, 32), (300, 3, 2.0, 6, 33)])
+def test_mds_on_a_gram_matrix_dominated_by_negative_eigenvalues(torch_cuda, N, k, spread, m, seed):
+    """The squared-dissimilarity Gram matrix of these synthetic factors has at least m negative eigenvalues larger in
+    magnitude than its third-largest eigenvalue (checked on the CPU in tests/test_oracle_factors.py): only an
+    iteration that converges to the algebraically largest eigenvalues matches the dense reference."""
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    torch = torch_cuda
+    print(f"indefinite scaling N={N} k={k} spread={spread} m={m}", flush=True)
+    Q, s = ri.random_int8_factor(N, k, spread, seed)
+    ref, ev_ref = oracle.mds3d_dense(Q, s, oracle.SQUARED)
+    x0 = ri.start_block(N, m, seed=780)
+    coords, ev, iters = rfx.mds3d(torch.from_numpy(Q).cuda(), torch.from_numpy(s).cuda(), torch.from_numpy(x0).cuda(),
+                                  rfx.MDS_SQUARED, max_iters=4000, tol=1e-9)
+    coords, ev = coords.cpu().numpy().astype(np.float64), ev.cpu().numpy().astype(np.float64)
+    print(f"  iterations={iters} eig={ev} ref={ev_ref}", flush=True)
+    np.testing.assert_allclose(ev, ev_ref, rtol=1e-4)
+    gaps = np.abs(np.diff(ev_ref)) / ev_ref[0]
+    if gaps.min() < 1e-2:
+        U, _, Vt = np.linalg.svd(coords.T @ ref)
+        coords = coords @ (U @ Vt)
+    err = np.linalg.norm(coords - ref) / np.linalg.norm(ref)
+    assert err <= 1e-3, (err, iters)
+
+
+def test_mds_of_a_factor_of_rank_below_the_block_width(torch_cuda):
+    """LINEAR mode with k = 2 and a block of 8 vectors: G has rank 2, the block cannot keep full rank, and that is
+    not an error: the third eigenvalue is (numerically) zero and the third coordinate vanishes, as in the dense
+    reference.  The same with a start block that has two equal columns."""
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    torch = torch_cuda
+    N, k, m = 200, 2, 8
+    Q, s = ri.random_int8_factor(N, k, 0.3, 34)
+    ref, ev_ref = oracle.mds3d_dense(Q, s, oracle.LINEAR)
+    for dup in (False, True):
+        x0 = ri.start_block(N, m, seed=781)
+        if dup:
+            x0[:, 4] = x0[:, 1]
+        coords, ev, iters = rfx.mds3d(torch.from_numpy(Q).cuda(), torch.from_numpy(s).cuda(), torch.from_numpy(x0).cuda(),
+                                      rfx.MDS_LINEAR, max_iters=200, tol=1e-9)
+        coords, ev = coords.cpu().numpy().astype(np.float64), ev.cpu().numpy().astype(np.float64)
+        print(f"rank-2 scaling dup={dup}: iterations={iters} eig={ev} ref={ev_ref}", flush=True)
+        np.testing.assert_allclose(ev[:2], ev_ref[:2], rtol=1e-4)
+        assert abs(ev[2]) <= 1e-5 * ev_ref[0]
+        err = np.linalg.norm(coords[:, :2] - ref[:, :2]) / np.linalg.norm(ref[:, :2])
+        assert err <= 1e-3, err
+        assert np.abs(coords[:, 2]).max() <= 3e-3 * np.abs(ref[:, 0]).max()

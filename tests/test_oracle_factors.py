@@ -251,3 +251,37 @@ def test_mds_correlation_metric(cfg1):
         rho[name] = oracle.mds_correlation(emb, full)
     assert rho["fp32"] > 0.95 and rho["fp16"] > 0.95 and rho["int8"] > 0.95 and rho["nf4"] > 0.9, rho
     assert abs(rho["fp16"] - rho["fp32"]) < 1e-3 and abs(rho["int8"] - rho["fp32"]) < 1e-2
+
+
+INDEFINITE_CASES = [(400, 4, 1.5, 8, 31), (500, 8, 1.0, 12, 32), (300, 3, 2.0, 6, 33)]   # N, k, spread, block width m, seed
+
+
+@pytest.mark.parametrize("N,k,spread,m,seed", INDEFINITE_CASES)
+def test_scaling_takes_the_largest_eigenvalues_not_the_largest_magnitudes(N, k, spread, m, seed):
+    """MDS Steps 3-4 ask for the largest eigenvalues of G.  On these synthetic factors the squared-dissimilarity
+    Gram matrix G = H P^ H - 1/2 H (P^ o P^) H has at least m negative eigenvalues that are larger in magnitude
+    than its third-largest eigenvalue, so an unshifted block power iteration of width m cannot hold the wanted
+    eigenvectors.  The dense reference must still return the algebraically largest three, and the implicit
+    operator solved for the algebraically largest agrees with it."""
+    Q, s = ri.random_int8_factor(N, k, spread, seed)
+    G = oracle.mds_gram_dense(oracle.dequantise(Q, s), oracle.SQUARED)
+    ev = np.linalg.eigvalsh(0.5 * (G + G.T))
+    lam3 = ev[-3]
+    assert lam3 > 0
+    assert (ev < -lam3).sum() >= m                       # the dominant part of the spectrum is negative
+    assert -ev[0] > 1.5 * ev[-1]
+    coords, lam = oracle.mds3d_dense(Q, s, oracle.SQUARED)
+    np.testing.assert_allclose(lam, ev[::-1][:3], rtol=1e-12)
+    assert (lam > 0).all()
+    np.testing.assert_allclose(coords.T @ coords, np.diag(lam), atol=1e-8 * lam[0])
+    c2, lam2 = oracle.mds3d_implicit(Q, s, oracle.SQUARED)
+    np.testing.assert_allclose(lam2, lam, rtol=1e-9)
+
+
+def test_scaling_of_a_factor_of_rank_below_three():
+    """LINEAR mode with k = 2: G = 1/2 H P^ H has rank 2, the third eigenvalue is zero and the third
+    coordinate vanishes (a non-positive eigenvalue gives a zero column, MDS Step 4 with lambda_3 = 0)."""
+    Q, s = ri.random_int8_factor(200, 2, 0.3, 34)
+    coords, lam = oracle.mds3d_dense(Q, s, oracle.LINEAR)
+    assert lam[1] > 1e-3 * lam[0] and abs(lam[2]) < 1e-10 * lam[0]
+    assert np.abs(coords[:, 2]).max() < 1e-4 * np.abs(coords[:, 0]).max()
