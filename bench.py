@@ -21,12 +21,9 @@ import time
 import numpy as np
 
 PEAK_VALU_LANE_OPS = 256 * 64 * 2.4e9   # 256 CUs x 64 lanes/clk x 2.4 GHz: plain 32-bit vector ops per second
-# rocprofv3 --pmc per-launch counters (KiB) at workload 4, from the committed summaries under profiles/
-FUSED_FETCH_KIB, FUSED_WRITE_KIB = 39202305.0, 63045597.1      # fused plain + out-of-bag tile kernel
-PLAIN_FETCH_KIB, PLAIN_WRITE_KIB = 39087769.4, 42359959.7      # plain tile kernel
-PV_FETCH_KIB, PV_WRITE_KIB = (7119809.3, 3330050.5, 2570010.1), (827637.2, 25000.0)   # the kernels of one P.V application
-LEAF_FETCH_KIB, LEAF_WRITE_KIB = 970263.7, 390625.0            # leaf assignment
 PEAK_HBM_BYTES = 8.0e12
+ROOT = os.path.dirname(os.path.abspath(__file__))
+MDS_TOL = 1e-5
 
 
 def log(*a):
@@ -36,8 +33,8 @@ def log(*a):
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--cfg", type=int, default=4, help="workload 1..5 (default: N=100,000, B=1,000)")
     ap.add_argument("--trees", type=int, default=0, help="override the tree count (debugging only)")
     ap.add_argument("--rows", type=int, default=0, help="override the row count (debugging only)")
@@ -45,7 +42,13 @@ def parse_args():
     ap.add_argument("--mds-block", type=int, default=16)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 4 GiB device copy before the steps (reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--summarise-kernel-trace", metavar="CSV",
+                    help="print the per-kernel table of a rocprofv3 --kernel-trace csv (kernel_trace.csv) and exit")
+    ap.add_argument("--summarise-pmc", nargs="+", metavar="CSV",
+                    help="print the per-kernel averages of rocprofv3 --pmc counter_collection.csv files and exit")
     args = ap.parse_args()
+    if args.summarise_kernel_trace or args.summarise_pmc:
+        return args
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
@@ -103,11 +106,28 @@ class Workload:
         self.lib = rfx.load()
         self.stream = torch.cuda.current_stream().cuda_stream
         self.phase_events = {}
+        # Everything the step needs is allocated here, once: the step itself calls the asynchronous forms of the
+        # boundary with these workspaces and allocates nothing.
+        k, m = self.k, self.m
+        rfx.leaf_assign(self.gf, self.dX, self.leaf)
+        self.ws_prox = rfx.new_workspace(rfx.prox_workspace_bytes(N, B, self.Lb))
+        self.ws_lr = rfx.new_workspace(rfx.lowrank_workspace_bytes(N, k))
+        self.ws_mds = rfx.new_workspace(rfx.mds3d_workspace_bytes(N, k, m, rfx.MDS_SQUARED))
+        self.plan = rfx.PvPlan(self.leaf, self.Lb)          # regrouped inside every step (rfx_pv_plan_rebuild)
+        rfx.pv_plan_reserve(self.plan, k)
+        self.lam = torch.empty(k, dtype=torch.float32, device=dev)
+        self.V = torch.empty((N, k), dtype=torch.float32, device=dev)
+        self.Q = torch.empty((N, k), dtype=torch.int8, device=dev)
+        self.scales = torch.empty(k, dtype=torch.float32, device=dev)
+        self.status = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.coords = torch.empty((N, 3), dtype=torch.float32, device=dev)
+        self.ev = torch.empty(3, dtype=torch.float32, device=dev)
+        self.mds_rel = torch.zeros(1, dtype=torch.float32, device=dev)
+        self.mds_iters = 0           # fixed by the first warm-up step: the count the tolerance-driven call needs
         if large:
             # capacity of the sparse list: one counting call on the leaf ids of this forest
-            rfx.leaf_assign(self.gf, self.dX, self.leaf)
             self.sp_cap = max(rfx.prox_sparse_count(self.leaf, self.Lb, 1), 1)
-            self.sp_got = ctypes.c_int64(0)
+            self.sp_nnz = torch.zeros(1, dtype=torch.int64, device=dev)
             self.alloc_sparse(self.sp_cap)
         else:
             self.prox = torch.empty((N, N), dtype=torch.float32, device=dev)
@@ -131,68 +151,75 @@ class Workload:
         self.phase_events.setdefault(name, []).append((e0, e1))
         return out
 
-    def phase_means(self, names=None):
-        """Mean milliseconds per phase from the recorded event pairs (after a synchronize); removes what it reports."""
+    def phase_stats(self, names=None):
+        """Per phase, from the recorded event pairs (after a synchronize): mean, median, min in milliseconds and the
+        number of samples; removes what it reports."""
         names = list(self.phase_events) if names is None else names
-        return {n: float(np.mean([a.elapsed_time(b) for a, b in self.phase_events.pop(n)])) for n in names}
+        out = {}
+        for n in names:
+            t = np.array([a.elapsed_time(b) for a, b in self.phase_events.pop(n)], np.float64)
+            out[n] = {"mean": float(t.mean()), "median": float(np.median(t)), "min": float(t.min()), "n": int(t.size)}
+        return out
 
-    def sparse_pass(self, cap, got):
+    def sparse_pass(self):
         rfx = self.rfx
-        rfx._check(self.lib.rfx_prox_sparse(self.leaf.data_ptr(), self.N, self.B, self.Lb, 1, rfx.U16, cap,
-                                            self.sp_rows.data_ptr(), self.sp_cols.data_ptr(), self.sp_cnt.data_ptr(),
-                                            0, ctypes.byref(got), self.stream))
+        rfx.prox_sparse_ws(self.leaf, self.Lb, self.ws_prox, self.sp_nnz, self.sp_rows, self.sp_cols, self.sp_cnt,
+                           min_count=1, count_dtype=rfx.U16)
 
     def dense_and_oob_separately(self):
         rfx = self.rfx
-        self.timed("prox_dense", lambda: rfx.prox_dense(self.leaf, self.Lb, rfx.U32, rfx.FULL, prox=self.prox,
-                                                        want_counts=False))
-        self.timed("prox_oob", lambda: rfx._check(self.lib.rfx_prox_oob(
-            self.leaf.data_ptr(), self.d_inbag.data_ptr(), self.N, self.B, self.Lb, rfx.U32, rfx.UPPER_PACKED, 0, 0,
-            self.prox_oob.data_ptr(), self.stream)))
+        self.timed("prox_dense", lambda: rfx.prox_dense_ws(self.leaf, self.Lb, self.ws_prox, rfx.U32, rfx.FULL, prox=self.prox))
+        self.timed("prox_oob", lambda: rfx.prox_oob_ws(self.leaf, self.d_inbag, self.Lb, self.ws_prox, rfx.U32,
+                                                       rfx.UPPER_PACKED, prox=self.prox_oob))
 
     def step(self):
-        """One pass of the whole path."""
+        """One pass of the whole path, enqueued on one stream: traversal, the dense pass (fused plain + out-of-bag, or
+        the exact sparse list where the dense outputs do not fit), the grouping of the samples by leaf for the
+        implicit product (it depends on this step's leaf ids; the only call that waits for the device: it reads the
+        number of big leaves back), the factorisation with INT8 factors, the scaling."""
         rfx = self.rfx
         self.timed("leaf_assign", lambda: rfx.leaf_assign(self.gf, self.dX, self.leaf))
         if self.large:
-            self.timed("prox_sparse", lambda: self.sparse_pass(self.sp_cap, self.sp_got))
+            self.timed("prox_sparse", self.sparse_pass)
         elif self.fused:
-            self.timed("prox_dense_oob", lambda: rfx._check(self.lib.rfx_prox_dense_oob(
-                self.leaf.data_ptr(), self.d_inbag.data_ptr(), self.N, self.B, self.Lb, rfx.U32, rfx.FULL, 0,
-                self.prox.data_ptr(), rfx.UPPER_PACKED, 0, 0, self.prox_oob.data_ptr(), self.stream)))
+            self.timed("prox_dense_oob", lambda: rfx.prox_dense_oob_ws(
+                self.leaf, self.d_inbag, self.Lb, self.ws_prox, rfx.U32, rfx.FULL, rfx.UPPER_PACKED, prox=self.prox,
+                prox_oob=self.prox_oob))
         else:
             self.dense_and_oob_separately()
-        lam, V, Q, s = self.timed("prox_lowrank", lambda: rfx.prox_lowrank(self.leaf, self.Lb, self.dV0, self.T))
-        res = self.timed("mds3d", lambda: rfx.mds3d(Q, s, self.dx0, rfx.MDS_SQUARED, max_iters=200, tol=1e-5))
-        return lam, res
+        self.timed("pv_plan", lambda: rfx.pv_plan_rebuild(self.plan, self.leaf))
+        self.timed("prox_lowrank", lambda: rfx.prox_lowrank_plan(self.plan, self.dV0, self.T, self.ws_lr, self.lam, self.V,
+                                                                 self.Q, self.scales, self.status))
+        if self.mds_iters == 0:
+            # first warm-up step: the tolerance-driven call fixes the number of applications for the timed steps
+            _, _, self.mds_iters = rfx.mds3d(self.Q, self.scales, self.dx0, rfx.MDS_SQUARED, max_iters=200, tol=MDS_TOL)
+        self.timed("mds3d", lambda: rfx.mds3d_ws(self.Q, self.scales, self.dx0, self.mds_iters, self.ws_mds, self.coords,
+                                                 self.ev, self.mds_rel))
 
 
 def calibration_copy(w):
-    """A plain device-to-device copy of known size: calibrates the HBM byte counters of a --pmc run."""
-    torch = w.torch
-    n_cal = 1 << 30
-    src = torch.empty(n_cal, dtype=torch.int32, device=w.dev).fill_(1)
-    dst = torch.empty_like(src)
-    dst.copy_(src)
-    torch.cuda.synchronize()
-    log(f"calibration copy: {4 * n_cal} bytes read and {4 * n_cal} bytes written by one elementwise copy kernel")
+    """A plain device-to-device copy of known size by the library's copy kernel (copy_probe_kernel: 4 GiB read and 4 GiB
+    written per dispatch): the row the HBM byte counters of a --pmc run are scaled by."""
+    rate = w.rfx.probe_copy(1 << 32)
+    log(f"calibration copy: 4 GiB read and 4 GiB written per dispatch of copy_probe_kernel ({rate / 1e12:.2f} TB/s)")
 
 
 def measure_sparse(w, kern):
     """The thresholded sparse form of the same counts (every non-zero pair); outside the step unless the workload is large."""
-    rfx = w.rfx
+    rfx, torch = w.rfx, w.torch
     if w.large:
-        assert w.sp_got.value == w.sp_cap, "the sparse pass found a different number of pairs than the counting call"
+        assert int(w.sp_nnz[0]) == w.sp_cap, "the sparse pass found a different number of pairs than the counting call"
         nnz, sp_ms = w.sp_cap, kern["prox_tile_kernel_sparse"]["avg_ms"]
     else:
         nnz = rfx.prox_sparse_count(w.leaf, w.Lb, 1)
         w.alloc_sparse(max(nnz, 1))
-        got = ctypes.c_int64(0)
+        w.sp_nnz = torch.zeros(1, dtype=torch.int64, device=w.dev)
         rfx.timing_enable(True)          # also clears the kernel timers
         for _ in range(2):
-            w.sparse_pass(max(nnz, 1), got)
+            w.sparse_pass()
         sp_ms, sp_n = rfx.timing_get("prox_tile_kernel_sparse")
         sp_ms /= max(sp_n, 1)
+        assert int(w.sp_nnz[0]) == nnz
     w.free_sparse()
     N, tests = w.N, w.tests
     return {"note": ("part of the step" if w.large else "not part of the step")
@@ -220,16 +247,20 @@ def measure_consumers(w):
             "oob_error": oob_wrong / max(oob_voted, 1)}
 
 
-def measure_plan_build(w):
-    """Once-per-forest grouping of samples by leaf for the implicit product (inside every prox_lowrank call of the step)."""
-    torch = w.torch
+def measure_one_shot(w):
+    """What the synchronous conveniences cost on top of the step's asynchronous calls (outside the step): a plan built
+    from nothing (allocation included) and rfx_prox_lowrank, which builds and destroys its own plan and scratch."""
+    torch, rfx = w.torch, w.rfx
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    plan = w.rfx.PvPlan(w.leaf, w.Lb)
+    plan = rfx.PvPlan(w.leaf, w.Lb)
     torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3
+    plan_ms = (time.perf_counter() - t0) * 1e3
     plan.close()
-    return ms
+    t0 = time.perf_counter()
+    rfx.prox_lowrank(w.leaf, w.Lb, w.dV0, w.T)
+    torch.cuda.synchronize()
+    return {"pv_plan_create_ms": plan_ms, "prox_lowrank_one_shot_ms": (time.perf_counter() - t0) * 1e3}
 
 
 def measure_growth(w):
@@ -246,25 +277,128 @@ def measure_growth(w):
             "pairs_per_s": grown["sorted_pairs"] / grow_s}
 
 
-def roofline_of_tile_kernel(w, kern, valu_rate):
+# ------------------------------------------------------------------------------------------------------------------
+# rocprofv3 summaries.  The byte counters quoted in the line are read from the committed summary of a --pmc run of this
+# file on the same workload (profiles/bench_cfg<c>_pmc_fetch_write.txt, written by --summarise-pmc below), never typed in.
+
+def _short_kernel_name(name):
+    import re
+    name = name.replace("(anonymous namespace)::", "").replace("void ", "").strip().strip('"')
+    name = re.sub(r"\(.*", "", name)
+    return re.sub(r"\s+", "", name)
+
+
+def summarise_kernel_trace(path):
+    """Per-kernel table (calls, total, average, min, max in ms, share) of a rocprofv3 kernel_trace.csv."""
+    import collections
+    import csv
+    agg = collections.OrderedDict()
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            d = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) * 1e-6
+            agg.setdefault(_short_kernel_name(r["Kernel_Name"]), []).append(d)
+    total = sum(sum(v) for v in agg.values())
+    print(f"{'kernel':64s} {'calls':>6s} {'total_ms':>10s} {'avg_ms':>9s} {'min_ms':>9s} {'max_ms':>9s} {'%':>6s}")
+    for n, v in sorted(agg.items(), key=lambda kv: -sum(kv[1])):
+        print(f"{n[:64]:64s} {len(v):6d} {sum(v):10.3f} {sum(v) / len(v):9.4f} {min(v):9.4f} {max(v):9.4f} {100 * sum(v) / total:6.2f}")
+
+
+def summarise_pmc(paths):
+    """Per-kernel averages per dispatch of every counter found in rocprofv3 counter_collection.csv files (one run each)."""
+    import collections
+    import csv
+    agg = collections.OrderedDict()
+    counters = []
+    for path in paths:
+        with open(path) as f:
+            for r in csv.DictReader(f):
+                c = r["Counter_Name"]
+                if c not in counters:
+                    counters.append(c)
+                a = agg.setdefault(_short_kernel_name(r["Kernel_Name"]), {}).setdefault(c, [0, 0.0])
+                a[0] += 1
+                a[1] += float(r["Counter_Value"])
+    print("kernel".ljust(64) + " " + " ".join(f"{'disp':>6s} {c[:18]:>18s}" for c in counters))
+    for n, cs in sorted(agg.items(), key=lambda kv: -max(v[1] for v in kv[1].values())):
+        cells = []
+        for c in counters:
+            a = cs.get(c)
+            cells.append(f"{a[0]:6d} {a[1] / a[0]:18.1f}" if a else f"{'-':>6s} {'-':>18s}")
+        print(f"{n[:64]:64s} " + " ".join(cells))
+
+
+def load_pmc_profile(cfg):
+    """{kernel: {counter: (dispatches, average per dispatch)}} from the committed summary of this workload, the file's name and a
+    hash of its contents; (None, None, None) when there is no summary."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", f"bench_cfg{cfg}_pmc_fetch_write.txt")
+    if not os.path.exists(path):
+        return None, None, None
+    text = open(path).read()
+    table, counters = {}, None
+    for line in text.splitlines():
+        if line.startswith("#") or not line.strip():
+            continue
+        parts = line.split()
+        if parts[0] == "kernel":
+            counters = [p for p in parts[1:] if p != "disp"]
+            continue
+        if counters is None or len(parts) != 1 + 2 * len(counters):
+            continue
+        row = {}
+        for i, c in enumerate(counters):
+            if parts[2 + 2 * i] != "-":
+                row[c] = (int(parts[1 + 2 * i]), float(parts[2 + 2 * i]))     # dispatches, average per dispatch
+        table[parts[0]] = row
+    return table, os.path.relpath(path, ROOT), hashlib.sha256(text.encode()).hexdigest()[:16]
+
+
+def fabric_bytes(profile, kernels):
+    """HBM-side bytes per launch of the named kernels from the profile: FETCH_SIZE and WRITE_SIZE (KiB per dispatch),
+    each scaled by what the same counter reads for the library's plain copy kernel of known size (copy_probe_kernel:
+    4 GiB read, 4 GiB written per dispatch).  None if a kernel or the calibration row is missing."""
+    if not profile or "copy_probe_kernel" not in profile:
+        return None
+
+    def average(prefix, counter):
+        """Average per dispatch over all rows whose kernel name starts with prefix (template variants of one kernel)."""
+        n = tot = 0
+        for name, row in profile.items():
+            if name.startswith(prefix) and counter in row:
+                n += row[counter][0]
+                tot += row[counter][0] * row[counter][1]
+        return tot / n if n else None
+
+    known_kib = float(1 << 32) / 1024.0
+    cal_f, cal_w = average("copy_probe_kernel", "FETCH_SIZE"), average("copy_probe_kernel", "WRITE_SIZE")
+    if not cal_f or not cal_w:
+        return None
+    total = 0.0
+    for kname in kernels:
+        f, wr = average(kname, "FETCH_SIZE"), average(kname, "WRITE_SIZE")
+        if f is None or wr is None:
+            return None
+        total += (f * known_kib / cal_f + wr * known_kib / cal_w) * 1024.0
+    return total
+
+
+def roofline_of_tile_kernel(w, kern, valu_rate, profile, profile_src):
     """Dominant kernel: bit-plane compare-and-count.  One launch covers the tile pairs on and below the diagonal of the
     (padded) N x N grid; per 32 trees and pair, P + 1 vector ops for the plain count, P + 7 for the fused pass that also
     yields the out-of-bag numerator and denominator."""
     tests, P = w.tests, w.P
+    mode = 2 if w.large else (4 if w.fused else 0)
     dom = "prox_tile_kernel_sparse" if w.large else ("prox_tile_kernel_both" if w.fused else "prox_tile_kernel")
     ops_per_test = (P + 7) / 32.0 if w.fused else (P + 1) / 32.0
     tile_ms = kern[dom]["avg_ms"]
     achieved = tests * ops_per_test / (tile_ms * 1e-3) if tile_ms > 0 else 0.0
-    # HBM-side bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB,
-    # calibrated on a 4 GiB copy); measured for workload 4 only
-    traffic = None
-    if w.c.cfg == 4 and not w.reduced:
-        fetch_kib, write_kib = (FUSED_FETCH_KIB, FUSED_WRITE_KIB) if w.fused else (PLAIN_FETCH_KIB, PLAIN_WRITE_KIB)
-        traffic = (fetch_kib * 2.0 + write_kib) * 1024.0
+    traffic = None if w.reduced else fabric_bytes(profile, [f"prox_tile_kernel<{P},16,{mode}>"])
     plain_ms = kern["prox_tile_kernel"]["avg_ms"]
     return {"kernel": dom, "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_VALU_LANE_OPS / 1e12,
             "unit": "T lane-ops/s", "frac": achieved / PEAK_VALU_LANE_OPS, "traffic": traffic,
-            "traffic_source": "profiles/bench_cfg4_pmc_fetch_write.txt (L2-to-fabric bytes; outputs are 4*N*N + 2*N*(N-1))",
+            "traffic_source": (f"{profile_src[0]} (sha256 {profile_src[1]}): FETCH_SIZE and WRITE_SIZE per dispatch, each scaled by "
+                               "the copy_probe_kernel row of the same file; L2-to-fabric bytes") if traffic is not None else None,
+            "algorithmic_bytes": (4.0 * w.N * w.N + 2.0 * w.N * (w.N - 1) if w.fused else 4.0 * w.N * w.N) if not w.large else None,
             "ops_per_test": ops_per_test, "avg_launch_ms": tile_ms,
             # the plain compare-and-count kernel on its own (P + 1 ops per 32 trees), run outside the step
             "plain_kernel": {"avg_launch_ms": plain_ms, "ops_per_test": (P + 1) / 32.0,
@@ -277,10 +411,16 @@ def roofline_of_tile_kernel(w, kern, valu_rate):
             "measured_valu_lane_ops_per_s": valu_rate, "frac_of_measured_valu": achieved / valu_rate if valu_rate > 0 else 0.0}
 
 
-def pv_figures(w, kern, copy_rate, plan_ms):
+def pv_figures(w, kern, copy_rate, profile):
     """Implicit product: algorithmic bytes per application = B*N*(2*4k + 4) + 2*4*N*k.  One application (`pv_apply`: a
     bracket on the caller's stream around the whole call) runs in groups of trees, the gather of a group on a second
-    stream next to the leaf sums of the following one, so the two kernel figures overlap and add up to more."""
+    stream next to the leaf sums of the following one, so the two kernel figures overlap and add up to more.
+
+    The row reads of both phases come from the caches, not from HBM, so the ceiling they are held against is measured:
+    rfx_probe_gather reads rows of k floats at random indices, eight loads in flight per wave, from a table the size of V
+    (the leaf sums gather V rows) and from a table the size of one tree's leaf sums (the gather phase sweeps the trees
+    in order, so that is what is live in L2)."""
+    rfx = w.rfx
     N, B, k = w.N, w.B, w.k
     w_pv = B * N * (2 * 4 * k + 4) + 2 * 4 * N * k
     applications = kern["pv_apply"]["launches"]
@@ -290,23 +430,48 @@ def pv_figures(w, kern, copy_rate, plan_ms):
         applications = max(kern["pv_gather_kernel"]["launches"], 1)
         pv_ms = (kern["pv_leaf_sum_kernel"]["total_ms"] + kern["pv_gather_kernel"]["total_ms"]) / applications
     rate = w_pv / (pv_ms * 1e-3) if pv_ms > 0 else 0.0
+    sum_ms = kern["pv_leaf_sum_kernel"]["total_ms"] / applications
+    gat_ms = kern["pv_gather_kernel"]["total_ms"] / applications
+    kp = 16 if k <= 16 else (32 if k <= 32 else 64 * ((k + 63) // 64))     # row width the probe supports
+    leaves_per_tree = max(64, int(np.mean(w.F.n_leaves)))
+    gathers = int(min(B * N, 1 << 27))
+    ceil_v = rfx.probe_gather(max(N, 64), kp, gathers)                 # rows of V: table of N rows
+    ceil_s = rfx.probe_gather(leaves_per_tree, kp, gathers)            # rows of one tree's leaf sums
+    rows_bytes = 4.0 * k * B * N                                       # row bytes either phase reads
+    sum_rate = rows_bytes / (sum_ms * 1e-3) if sum_ms > 0 else 0.0
+    gat_rate = rows_bytes / (gat_ms * 1e-3) if gat_ms > 0 else 0.0
+    ceil_both = 2.0 / (1.0 / ceil_v + 1.0 / ceil_s)                    # both phases one after the other, each at its ceiling
+    both_rate = 2.0 * rows_bytes / ((sum_ms + gat_ms) * 1e-3) if sum_ms + gat_ms > 0 else 0.0
+    fabric = None if w.reduced else fabric_bytes(profile, ["pv_leaf_sum_kernel<", "pv_leaf_sum_big_kernel<", "pv_gather_kernel<"])
+    if fabric is not None:
+        # the profile's rows are per dispatch, one dispatch per group of trees
+        fabric *= max(kern["pv_gather_kernel"]["launches"] // applications, 1)
     return {"bytes_per_application": w_pv, "avg_ms": pv_ms, "GBps": rate / 1e9, "frac_of_hbm_peak": rate / PEAK_HBM_BYTES,
-            "leaf_sum_ms": kern["pv_leaf_sum_kernel"]["total_ms"] / applications,
-            "gather_ms": kern["pv_gather_kernel"]["total_ms"] / applications,
+            "leaf_sum_ms": sum_ms, "gather_ms": gat_ms,
             "tree_groups": kern["pv_gather_kernel"]["launches"] // applications,
             "compulsory_floor_bytes": 4 * N * B + 8 * N * k,
-            # rocprofv3 FETCH_SIZE x 2 + WRITE_SIZE of the three kernels of one application (workload 4 only)
-            "measured_fabric_bytes": (sum(PV_FETCH_KIB) * 2.0 + sum(PV_WRITE_KIB)) * 1024.0
-            if (w.c.cfg == 4 and not w.reduced) else None,
+            "roofline": {"bound": "cache gather", "unit": "GB/s of row reads",
+                         "achieved": both_rate / 1e9, "ceiling": ceil_both / 1e9, "frac": both_rate / ceil_both,
+                         "leaf_sums": {"achieved": sum_rate / 1e9, "ceiling": ceil_v / 1e9, "frac": sum_rate / ceil_v,
+                                       "ceiling_is": f"rfx_probe_gather on a table of {max(N, 64)} rows x {kp} floats (the size of V)"},
+                         "gather": {"achieved": gat_rate / 1e9, "ceiling": ceil_s / 1e9, "frac": gat_rate / ceil_s,
+                                    "ceiling_is": f"rfx_probe_gather on a table of {leaves_per_tree} rows x {kp} floats (one tree's leaf sums)"},
+                         "note": "kernel times of the two phases added up (in the step they overlap on two streams: avg_ms)"},
+            "measured_fabric_bytes": fabric,
+            "measured_fabric_frac_of_hbm_peak": fabric / (pv_ms * 1e-3) / PEAK_HBM_BYTES if fabric and pv_ms > 0 else None,
             "measured_copy_bytes_per_s": copy_rate, "frac_of_measured_copy": rate / copy_rate if copy_rate > 0 else 0.0,
-            "valu_bound_ms": 2.0 * B * N * k / PEAK_VALU_LANE_OPS * 1e3, "plan_build_ms": plan_ms,
-            "note": "above 100 % of the HBM peak = cache-assisted: V and the per-tree sums are served by L2 / Infinity Cache"}
+            "valu_bound_ms": 2.0 * B * N * k / PEAK_VALU_LANE_OPS * 1e3,
+            "note": "GBps is the byte model over the time; above 100 % of the HBM peak = cache-assisted: V and the per-tree sums are "
+                    "served by L2 / Infinity Cache, which is why the roofline above uses a measured cache-gather ceiling"}
 
 
-def leaf_assign_figures(w, kern):
+def leaf_assign_figures(w, kern, profile):
     """Leaf assignment: one 8-byte node record and one 4-byte feature value per visited internal node, plus the leaf-id
-    write and X read once."""
-    torch, F, N, B = w.torch, w.F, w.N, w.B
+    write and X read once.  The walk is a chain of dependent loads, so the ceiling it is held against is measured:
+    rfx_probe_chase advances chains of dependent 8-byte loads (a dependent LDS read between two of them, as the feature
+    lookup) at the kernel's occupancy, through a table that stays in the first-level caches (every step a hit: no walk
+    can be faster) and, for reference, through a table the size of the forest (no locality at all)."""
+    torch, F, N, B, rfx = w.torch, w.F, w.N, w.B, w.rfx
     depth_tab = np.zeros((B, w.Lb), np.int32)
     for b in range(B):
         s, e = int(F.node_offset[b]), int(F.node_offset[b + 1])
@@ -317,17 +482,30 @@ def leaf_assign_figures(w, kern):
     w_la = path_total * (8 + 4) + 4 * N * B + 4 * N * w.c.M
     la_ms = kern["leaf_assign_kernel"]["avg_ms"]
     rate = w_la / (la_ms * 1e-3) if la_ms > 0 else 0.0
+    steps_rate = path_total / (la_ms * 1e-3) if la_ms > 0 else 0.0
+    ceil_hit = rfx.probe_chase(16 << 10, 2, 2048, True)
+    ceil_cold = rfx.probe_chase(max(8 * int(F.total_nodes), 4096), 2, 256, True)
+    fabric = None if w.reduced else fabric_bytes(profile, ["leaf_assign_kernel<"])
     return {"bytes_model": w_la, "mean_path": path_total / (N * B), "avg_ms": la_ms, "GBps": rate / 1e9,
             "frac_of_hbm_peak": rate / PEAK_HBM_BYTES,
             "compulsory_floor_bytes": 4 * N * w.c.M + 8 * int(F.total_nodes) + 4 * N * B,
-            "measured_fabric_bytes": (LEAF_FETCH_KIB * 2.0 + LEAF_WRITE_KIB) * 1024.0
-            if (w.c.cfg == 4 and not w.reduced) else None,
+            "roofline": {"bound": "dependent load chain", "unit": "G node steps/s", "achieved": steps_rate / 1e9,
+                         "ceiling": ceil_hit / 1e9, "frac": steps_rate / ceil_hit if ceil_hit > 0 else 0.0,
+                         "ceiling_is": "rfx_probe_chase, 2 walks per thread, 16 KiB table (every step a first-level cache hit)",
+                         "no_locality_reference": ceil_cold / 1e9,
+                         "no_locality_is": f"the same chase through {8 * int(F.total_nodes)} bytes (the forest's node records)"},
+            "measured_fabric_bytes": fabric,
+            "measured_fabric_frac_of_hbm_peak": fabric / (la_ms * 1e-3) / PEAK_HBM_BYTES if fabric and la_ms > 0 else None,
             "forest_create_ms": w.forest_create_ms,
             "note": "gather-latency bound; nodes and X are cache / LDS resident, so the byte model is not HBM traffic"}
 
 
 def main():
     args = parse_args()
+    if args.summarise_kernel_trace:
+        return summarise_kernel_trace(args.summarise_kernel_trace)
+    if args.summarise_pmc:
+        return summarise_pmc(args.summarise_pmc)
     import torch
     import paper_2511_19493_amd as rfx
     import rfx_inputs as ri
@@ -338,7 +516,7 @@ def main():
     if args.calibrate_copy:
         calibration_copy(w)
 
-    for _ in range(args.warmup):
+    for _ in range(max(args.warmup, 1)):      # the first warm-up step fixes the scaling step's iteration count
         w.step()
     torch.cuda.synchronize()
     w.phase_events.clear()
@@ -346,18 +524,22 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        lam, (coords, ev, mds_iters) = w.step()
+        w.step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    mds_iters, mds_rel = w.mds_iters, float(w.mds_rel[0])
+    assert int(w.status[0]) == 0, "the factorisation's block lost rank"
+    assert mds_rel <= 10 * MDS_TOL, f"the scaling step has not converged after {mds_iters} applications ({mds_rel})"
 
-    phases = w.phase_means()
+    stats = w.phase_stats()
     if w.fused:
         # the two passes the fused one replaces, outside the step, for their own kernel times
-        for _ in range(2):
+        for _ in range(3):
             w.dense_and_oob_separately()
         torch.cuda.synchronize()
-        sep = w.phase_means(["prox_dense", "prox_oob"])
-        phases["separate_prox_dense"], phases["separate_prox_oob"] = sep["prox_dense"], sep["prox_oob"]
+        sep = w.phase_stats(["prox_dense", "prox_oob"])
+        stats["separate_prox_dense"], stats["separate_prox_oob"] = sep["prox_dense"], sep["prox_oob"]
+    phases = {n: v["mean"] for n, v in stats.items()}
     kern = {}
     for name in ("leaf_assign_kernel", "prox_tile_kernel_both", "prox_tile_kernel", "prox_tile_kernel_oob",
                  "prox_tile_kernel_sparse", "pv_apply", "pv_leaf_sum_kernel", "pv_gather_kernel"):
@@ -366,21 +548,24 @@ def main():
 
     sparse = measure_sparse(w, kern)
     consumers = measure_consumers(w)
-    plan_ms = measure_plan_build(w)
+    one_shot = measure_one_shot(w)
     growth = measure_growth(w)
     # practical ceilings of this GPU next to the published peaks
     valu_rate = rfx.probe_valu(4096)
     copy_rate = rfx.probe_copy(1 << 32)
+    profile, prof_file, prof_hash = load_pmc_profile(w.c.cfg)
 
     c, N, B, tests = w.c, w.N, w.B, w.tests
     dense_phase = "prox_sparse" if w.large else ("prox_dense_oob" if w.fused else "prox_dense")
+    pv = pv_figures(w, kern, copy_rate, profile)
     out = {
-        "metric": "leaf co-occurrence tests/s (N^2*B/2 per pass of the whole proximity path)",
+        "metric": "leaf co-occurrence tests/s: N^2*B/2 per pass of the whole proximity path (traversal, dense pass, "
+                  "factorisation, scaling); the dense pass alone is dense_tests_per_s",
         "value": tests / (ms_per_step * 1e-3),
         "unit": "tests/s",
         "n_gpus": 1,
         "steps": args.steps,
-        "warmup": args.warmup,
+        "warmup": max(args.warmup, 1),
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -389,17 +574,23 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"cfg{c.cfg}: N={N} M={c.M} B={B} trees to purity, mtry={c.mtry}, k={w.k}, T={w.T}"
                                + (" (REDUCED, debugging)" if w.reduced else "")
-                               + (" (dense outputs do not fit: exact sparse list instead; forest grown by rfx_forest_grow)"
+                               + (" (dense outputs do not fit: exact sparse list instead; forest grown by rfx_forest_grow, "
+                                  "checked against the oracle by tests/test_gpu_y_fullsize.py::test_cfg5_full_tree_count)"
                                   if w.large else ""),
                    "leaf_bound": w.Lb, "bit_planes": w.P, "mds_block": w.m, "mds_iters": mds_iters},
         "phases_ms": phases,
-        "mds": {"iterations": mds_iters, "ms_per_iteration": phases["mds3d"] / max(mds_iters, 1),
+        "phases_median_ms": {n: v["median"] for n, v in stats.items()},
+        "phases_min_ms": {n: v["min"] for n, v in stats.items()},
+        "phases_samples": {n: v["n"] for n, v in stats.items()},
+        "lowrank_outside_pv_ms": phases["prox_lowrank"] - w.T * pv["avg_ms"],
+        "mds": {"iterations": mds_iters, "rel_change_last": mds_rel, "ms_per_iteration": phases["mds3d"] / max(mds_iters, 1),
                 "factor_GBps": N * w.k * mds_iters / (phases["mds3d"] * 1e-3) / 1e9},
         "dense_tests_per_s": tests / (phases[dense_phase] * 1e-3),
-        "pv": pv_figures(w, kern, copy_rate, plan_ms),
-        "leaf_assign": leaf_assign_figures(w, kern),
+        "pv": pv,
+        "leaf_assign": leaf_assign_figures(w, kern, profile),
         "kernels": kern,
-        "roofline": roofline_of_tile_kernel(w, kern, valu_rate),
+        "roofline": roofline_of_tile_kernel(w, kern, valu_rate, profile, (prof_file, prof_hash)),
+        "one_shot_conveniences": one_shot,
         "consumers": consumers,
         "growth": growth,
         "sparse": sparse,

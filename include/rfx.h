@@ -162,11 +162,24 @@ int rfx_leaf_assign(const rfx_forest* forest, const float* X, int64_t N, int32_t
  * of the two vector operations the compare-and-count kernel is made of (3-input boolean op,
  * population count with accumulate) on every CU for `rounds` rounds (1..2^20) and reports the
  * lane-operations per second reached; rfx_probe_copy copies `bytes` (2^20..2^36) of device
- * memory with a plain kernel and reports bytes read + written per second (best of 3).  Both
+ * memory with a plain kernel and reports bytes read + written per second (best of 3).  All probes
  * allocate their own buffers and are synchronous.  Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG,
  * RFX_ERR_OOM. */
 int rfx_probe_valu(int32_t rounds, double* lane_ops_per_s, void* stream);
 int rfx_probe_copy(int64_t bytes, double* bytes_per_s, void* stream);
+/* rfx_probe_gather: the access pattern of the implicit product with everything else taken away.  Waves read
+ * `gathers` rows of k float32 (k = 16, 32, 64, 128, 192 or 256) at pseudo-random indices of a table of table_rows rows
+ * (64..2^26), eight row loads in flight per wave, and add them up; reports row bytes read per second (best of 3).  A
+ * table smaller than the 4 MB second-level cache of an XCD measures gathers that hit it, one of tens of MB gathers
+ * served by the last-level cache, one of GBs gathers from HBM.  xcd_local = 1 lets every workgroup draw from the eighth
+ * of the table that belongs to the XCD running it.
+ * rfx_probe_chase: the access pattern of tree traversal.  Every thread of two 1,024-thread workgroups per CU advances
+ * walks_per_thread (1, 2 or 4) independent chains of `steps` dependent 8-byte loads through a table of table_bytes
+ * (4 KiB..16 GiB) of pseudo-randomly linked records; with_lds = 1 puts a dependent 4-byte LDS read between two loads,
+ * as the feature lookup of a node does.  Reports chain steps per second over all walks (best of 2). */
+int rfx_probe_gather(int64_t table_rows, int32_t k, int64_t gathers, int32_t xcd_local, double* bytes_per_s, void* stream);
+int rfx_probe_chase(int64_t table_bytes, int32_t walks_per_thread, int32_t steps, int32_t with_lds, double* steps_per_s,
+                    void* stream);
 
 /* Dense proximity (equation p(i,j) = (1/B) sum_b I(node_b(i) = node_b(j)), "Proximity
  * Matrices").
@@ -287,6 +300,10 @@ int rfx_oob_vote(const uint32_t* leaf, const uint16_t* inbag, const int32_t* lea
  *   rfx_pv_plan_create: leaf [device] uint32 [B][N] (read during the call only), ids < leaf_bound.
  *                       B <= 65535, B * N < 2^32 and B * leaf_bound < 2^32, else
  *                       RFX_ERR_UNSUPPORTED.  Synchronous (it reports a leaf id >= leaf_bound).
+ *   rfx_pv_plan_rebuild: regroups an existing plan for new leaf ids of the same N, B and leaf_bound
+ *                       without allocating (the plan keeps the scratch of its grouping: 4 B leaf_bound
+ *                       min(16, N/4096) bytes).  Synchronous; applications of the old grouping must have
+ *                       finished.  After a failed rebuild the plan refuses applications until one succeeds.
  *   rfx_pv_plan_reserve: sizes the per-leaf sums for rank k now (4 B leaf_bound k bytes; waits for
  *                       the device when it has to replace a smaller buffer), so that every later
  *                       application of rank <= k is asynchronous.
@@ -302,6 +319,7 @@ typedef struct rfx_pv_plan rfx_pv_plan;
 int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, rfx_pv_plan** out,
                        void* stream);
 int rfx_pv_plan_destroy(rfx_pv_plan* plan);
+int rfx_pv_plan_rebuild(rfx_pv_plan* plan, const uint32_t* leaf, void* stream);
 int rfx_pv_plan_reserve(rfx_pv_plan* plan, int32_t k);
 int rfx_pv_plan_info(const rfx_pv_plan* plan, int64_t* N, int32_t* B, int32_t* k_reserved);
 int rfx_pv_apply(rfx_pv_plan* plan, const float* V, int32_t k, float* Y, void* stream);

@@ -16,6 +16,7 @@ own data and forests and stays "parity unpinned" (context only).
 from __future__ import annotations
 
 import ctypes
+import os
 import subprocess
 from pathlib import Path
 from typing import Tuple
@@ -23,7 +24,11 @@ from typing import Tuple
 import numpy as np
 
 _HERE = Path(__file__).resolve().parent
-_LIB_PATH = _HERE / "liboracle_core.so"
+# RFX_SANITIZE=1 selects builds with AddressSanitizer and UndefinedBehaviorSanitizer (own file names, so both kinds
+# can sit side by side); the process that loads them must have the sanitizer runtimes preloaded.
+_SANITIZE = os.environ.get("RFX_SANITIZE", "") == "1"
+_SAN_FLAGS = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-g"]
+_LIB_PATH = _HERE / ("liboracle_core_san.so" if _SANITIZE else "liboracle_core.so")
 _lib = None
 
 SQUARED = 0   # dissimilarity squared before double-centring (the paper's Step 1-2)
@@ -34,12 +39,12 @@ def build_core(force: bool = False) -> Path:
     """Compiles oracle_core.c with gcc (in-tree)."""
     src = _HERE / "oracle_core.c"
     if force or not _LIB_PATH.exists() or _LIB_PATH.stat().st_mtime < src.stat().st_mtime:
-        subprocess.run(["gcc", "-O2", "-std=c99", "-fopenmp", "-Wall", "-shared", "-fPIC", str(src), "-o",
-                        str(_LIB_PATH)], check=True)
+        subprocess.run(["gcc", "-O2", "-std=c99", "-fopenmp", "-Wall", "-shared", "-fPIC", *(_SAN_FLAGS if _SANITIZE else []),
+                        str(src), "-o", str(_LIB_PATH)], check=True)
     return _LIB_PATH
 
 
-_GROW_PATH = _HERE / "liboracle_grow.so"
+_GROW_PATH = _HERE / ("liboracle_grow_san.so" if _SANITIZE else "liboracle_grow.so")
 _grow_lib = None
 
 
@@ -47,8 +52,8 @@ def build_grow(force: bool = False) -> Path:
     """Compiles grow_core.c with gcc (in-tree)."""
     src = _HERE / "grow_core.c"
     if force or not _GROW_PATH.exists() or _GROW_PATH.stat().st_mtime < src.stat().st_mtime:
-        subprocess.run(["gcc", "-O2", "-std=c99", "-fopenmp", "-Wall", "-shared", "-fPIC", str(src), "-o",
-                        str(_GROW_PATH)], check=True)
+        subprocess.run(["gcc", "-O2", "-std=c99", "-fopenmp", "-Wall", "-shared", "-fPIC", *(_SAN_FLAGS if _SANITIZE else []),
+                        str(src), "-o", str(_GROW_PATH)], check=True)
     return _GROW_PATH
 
 
@@ -331,7 +336,7 @@ def fix_signs(V) -> np.ndarray:
     return V * s
 
 
-def block_iteration(leaf, V0, T: int) -> Tuple[np.ndarray, np.ndarray]:
+def block_iteration(leaf, V0, T: int, progress=None) -> Tuple[np.ndarray, np.ndarray]:
     """Top-k eigenpairs of P by block power iteration with exactly T applications of P, float64.
 
     V <- orth(V0); T-1 times V <- orth(P V); then Y = P V, H = sym(V^T Y), H = W diag(theta) W^T
@@ -339,11 +344,17 @@ def block_iteration(leaf, V0, T: int) -> Tuple[np.ndarray, np.ndarray]:
     Gram matrices Z_b Z_b^T), so P ~ V diag(theta) V^T is the symmetric form of the paper's
     low-rank factorisation P ~ Q U^T with Q = U = V diag(sqrt(theta)).
     Returns (theta [k] descending, V [N][k]) with the sign convention of fix_signs.
+    `progress`, if given, is called with the number of applications done after each one (long runs
+    report their own steps); it takes no part in the arithmetic.
     """
     V, _ = np.linalg.qr(np.asarray(V0, np.float64))
-    for _ in range(T - 1):
+    for t in range(T - 1):
         V, _ = np.linalg.qr(pv_implicit(leaf, V))
+        if progress:
+            progress(t + 1)
     Y = pv_implicit(leaf, V)
+    if progress:
+        progress(T)
     H = V.T @ Y
     H = 0.5 * (H + H.T)
     theta, W = np.linalg.eigh(H)
@@ -358,6 +369,23 @@ def dense_eig(P, k: int) -> Tuple[np.ndarray, np.ndarray]:
     n = P.shape[0]
     lam, U = sla.eigh(P, subset_by_index=[n - k, n - 1])
     return lam[::-1].copy(), fix_signs(U[:, ::-1])
+
+
+def implicit_eig(leaf, k: int, tol: float = 1e-12, seed: int = 4243) -> Tuple[np.ndarray, np.ndarray]:
+    """Top-k eigenpairs of P (descending) from the float64 implicit operator with ARPACK, for N too large to
+    materialise P; the dense eigendecomposition is the definition, this is the same spectrum to `tol`."""
+    import scipy.sparse.linalg as spla
+    leaf = np.asarray(leaf)
+    n = leaf.shape[1]
+
+    def mv(v):
+        return pv_implicit(leaf, np.asarray(v, np.float64).reshape(n, -1)).reshape(np.shape(v))
+
+    L = spla.LinearOperator((n, n), matvec=mv, matmat=mv, dtype=np.float64)
+    rng = np.random.default_rng(seed)
+    lam, U = spla.eigsh(L, k=k, which="LA", tol=tol, v0=rng.standard_normal(n))
+    order = np.argsort(lam)[::-1]
+    return lam[order], fix_signs(U[:, order])
 
 
 def principal_angle(U, V) -> float:

@@ -24,12 +24,12 @@ MDS_SQUARED, MDS_LINEAR = 0, 1
 ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
 
 EXPORTS = (
-    "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_probe_valu", "rfx_probe_copy", "rfx_forest_grow", "rfx_grown_sizes", "rfx_grown_export", "rfx_grown_destroy", "rfx_growth_draw", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
+    "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_probe_valu", "rfx_probe_copy", "rfx_probe_gather", "rfx_probe_chase", "rfx_forest_grow", "rfx_grown_sizes", "rfx_grown_export", "rfx_grown_destroy", "rfx_growth_draw", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
     "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_dense_oob", "rfx_prox_sparse", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
     "rfx_prox_workspace_bytes", "rfx_prox_dense_ws", "rfx_prox_oob_ws", "rfx_prox_dense_oob_ws", "rfx_prox_sparse_ws",
-    "rfx_prox_outlier_ws", "rfx_pv_plan_reserve", "rfx_pv_plan_info", "rfx_lowrank_workspace_bytes", "rfx_prox_lowrank_plan",
+    "rfx_prox_outlier_ws", "rfx_pv_plan_reserve", "rfx_pv_plan_rebuild", "rfx_pv_plan_info", "rfx_lowrank_workspace_bytes", "rfx_prox_lowrank_plan",
     "rfx_mds3d_workspace_bytes", "rfx_mds3d_ws",
 )
 
@@ -67,6 +67,8 @@ def load():
             "rfx_timing_get": [ctypes.c_char_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)],
             "rfx_probe_valu": [i32, ctypes.POINTER(ctypes.c_double), vp],
             "rfx_probe_copy": [i64, ctypes.POINTER(ctypes.c_double), vp],
+            "rfx_probe_gather": [i64, i32, i64, i32, ctypes.POINTER(ctypes.c_double), vp],
+            "rfx_probe_chase": [i64, i32, i32, i32, ctypes.POINTER(ctypes.c_double), vp],
             "rfx_forest_grow": [vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_uint64, ctypes.POINTER(vp), vp],
             "rfx_grown_sizes": [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i64)],
             "rfx_grown_export": [vp] * 11,
@@ -96,6 +98,7 @@ def load():
             "rfx_prox_sparse_ws": [vp, i64, i32, i32, i32, ci, i64, vp, vp, vp, vp, vp, vp, i64, vp],
             "rfx_prox_outlier_ws": [vp, i64, i32, i32, vp, vp, vp, vp, i64, vp],
             "rfx_pv_plan_reserve": [vp, i32],
+            "rfx_pv_plan_rebuild": [vp, vp, vp],
             "rfx_pv_plan_info": [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)],
             "rfx_lowrank_workspace_bytes": [i64, i32, ctypes.POINTER(i64)],
             "rfx_prox_lowrank_plan": [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp],
@@ -158,6 +161,20 @@ def probe_copy(nbytes: int = 1 << 32) -> float:
     """rfx_probe_copy: bytes read + written per second by a plain device copy of nbytes."""
     r = ctypes.c_double(0.0)
     _check(load().rfx_probe_copy(nbytes, ctypes.byref(r), _stream()))
+    return r.value
+
+
+def probe_gather(table_rows: int, k: int = 64, gathers: int = 1 << 26, xcd_local: bool = False) -> float:
+    """rfx_probe_gather: row bytes per second of pseudo-random row gathers from a table of table_rows x k floats."""
+    r = ctypes.c_double(0.0)
+    _check(load().rfx_probe_gather(table_rows, k, gathers, 1 if xcd_local else 0, ctypes.byref(r), _stream()))
+    return r.value
+
+
+def probe_chase(table_bytes: int, walks_per_thread: int = 2, steps: int = 256, with_lds: bool = True) -> float:
+    """rfx_probe_chase: dependent-load chain steps per second through a table of table_bytes."""
+    r = ctypes.c_double(0.0)
+    _check(load().rfx_probe_chase(table_bytes, walks_per_thread, steps, 1 if with_lds else 0, ctypes.byref(r), _stream()))
     return r.value
 
 
@@ -561,6 +578,12 @@ def prox_outlier_ws(leaf, leaf_bound: int, workspace, labels=None, printed=None,
                                       _stream()))
 
 
+def pv_plan_rebuild(plan: "PvPlan", leaf):
+    """rfx_pv_plan_rebuild: regroup the plan for new leaf ids of the same shape, without allocating."""
+    import torch
+    _check(load().rfx_pv_plan_rebuild(plan._h, _dev(leaf, torch.int32, (plan.B, plan.N)), _stream()))
+
+
 def pv_plan_reserve(plan: "PvPlan", k: int):
     """rfx_pv_plan_reserve."""
     _check(load().rfx_pv_plan_reserve(plan._h, k))
@@ -606,3 +629,4 @@ def mds3d_ws(Q, scales, x0, iters: int, workspace, coords, eigvals, rel_change=N
     _check(load().rfx_mds3d_ws(_dev(Q, torch.int8), _dev(scales, torch.float32, (k,)), N, k, mode, m, iters,
                                _dev(x0, torch.float32, (N, m)), _dev(coords, torch.float32, (N, 3)),
                                _dev(eigvals, torch.float32, (3,)), _dev(rel_change, torch.float32, (1,)), wp, wb, _stream()))
+

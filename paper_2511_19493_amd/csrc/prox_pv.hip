@@ -38,6 +38,13 @@ struct rfx_pv_plan {
     uint32_t* d_big = nullptr;        // slots with more than kBigLeaf members, one list per group of trees
     float* d_S = nullptr;             // [B*Lb][k_cap]
     int32_t k_cap = 0;
+    // scratch of the grouping, kept so that the plan can be rebuilt for new leaf ids without allocating
+    uint32_t* d_count = nullptr;      // [B][Q][Lb] part histograms, then cursors
+    int* d_flags = nullptr;           // bad id seen; big slots per group
+    int32_t Q = 1;                    // parts per tree
+    int64_t part_len = 0;
+    int32_t lds_hist = 0;
+    bool built = false;               // false after a rebuild that failed: applications are refused
     // An application runs in n_chunks groups of trees: the leaf sums of a group on the caller's stream, its gather on
     // `side` as soon as they are done, so the gather of one group overlaps the sums of the next.
     static constexpr int kMaxChunks = 4;
@@ -98,6 +105,10 @@ __global__ __launch_bounds__(1024) void pv_hist_kernel(const uint32_t* __restric
         for (int l = threadIdx.x; l < Lb; l += blockDim.x)
             mine[l] = kLds == 2 ? (hist[l >> 1] >> (16 * (l & 1))) & 0xffffu : hist[l];
     }
+}
+
+__global__ __launch_bounds__(256) void pv_zero_kernel(uint32_t* __restrict__ p, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
 // Groups of trees (consecutive ranges) and where each group's list of big slots starts.
@@ -565,12 +576,66 @@ int rfx_pv_plan_destroy(rfx_pv_plan* p) {
     if (p->d_seg_start) (void)hipFree(p->d_seg_start);
     if (p->d_big) (void)hipFree(p->d_big);
     if (p->d_S) (void)hipFree(p->d_S);
+    if (p->d_count) (void)hipFree(p->d_count);
+    if (p->d_flags) (void)hipFree(p->d_flags);
     for (hipEvent_t e : p->ev_sum)
         if (e) (void)hipEventDestroy(e);
     if (p->ev_done) (void)hipEventDestroy(p->ev_done);
     delete p;
     return RFX_OK;
 }
+
+namespace {
+constexpr int kPlanFlags = 1 + rfx_pv_plan::kMaxChunks;  // bad id seen; big slots per group
+
+// Groups the samples of every tree by leaf into the plan's arrays (histograms, scan, stable scatter) and reads the
+// counts of big slots back.  Allocates nothing; waits for the stream.
+int build_plan(rfx_pv_plan* p, const uint32_t* leaf, hipStream_t st) {
+    const int64_t N = p->N;
+    const int32_t B = p->B, Lb = p->Lb, Q = p->Q;
+    const int64_t n_slots = (int64_t)B * Lb;
+    BigGroups groups;
+    groups.n = p->n_chunks;
+    for (int c = 0; c < rfx_pv_plan::kMaxChunks; ++c) {
+        groups.tree_end[c] = c < p->n_chunks ? p->tree_off[c + 1] : B;
+        groups.base[c] = p->big_base[c];
+    }
+    uint32_t* cnt = p->d_count;
+    int* bad = p->d_flags;
+    int* n_big = bad + 1;
+    const size_t hist16_lds = sizeof(uint32_t) * (size_t)((Lb + 1) / 2);
+    // the two clears are kernels, not memsets, so that a caller may capture the build into a graph
+    if (!p->lds_hist) {
+        hipLaunchKernelGGL(pv_zero_kernel, dim3((unsigned)std::min<int64_t>(rfx::ceil_div(n_slots * Q, 256), 65535)), dim3(256), 0,
+                           st, cnt, n_slots * Q);
+    }
+    hipLaunchKernelGGL(pv_zero_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<uint32_t*>(p->d_flags), (int64_t)kPlanFlags);
+    if (p->lds_hist == 1)
+        hipLaunchKernelGGL(pv_hist_kernel<1>, dim3(Q, B), dim3(1024), sizeof(uint32_t) * Lb, st, leaf, N, Lb, p->part_len,
+                           p->d_slot, cnt, bad);
+    else if (p->lds_hist == 2)
+        hipLaunchKernelGGL(pv_hist_kernel<2>, dim3(Q, B), dim3(1024), hist16_lds, st, leaf, N, Lb, p->part_len, p->d_slot, cnt,
+                           bad);
+    else
+        hipLaunchKernelGGL(pv_hist_kernel<0>, dim3(Q, B), dim3(1024), 0, st, leaf, N, Lb, p->part_len, p->d_slot, cnt, bad);
+    hipLaunchKernelGGL(pv_scan_kernel, dim3((unsigned)B), dim3(256), 0, st, cnt, N, B, Lb, Q, p->d_seg_start, p->d_big, n_big,
+                       groups);
+    if (Lb <= kScatterLdsLeaves)
+        hipLaunchKernelGGL(pv_scatter_lds_kernel, dim3(Q, B), dim3(64), sizeof(uint32_t) * Lb, st, p->d_slot, N, Lb, p->part_len,
+                           cnt, p->d_perm);
+    else
+        hipLaunchKernelGGL(pv_scatter_kernel, dim3(Q, B), dim3(64), 0, st, p->d_slot, N, Lb, p->part_len, cnt, p->d_perm);
+    int h_flags[kPlanFlags] = {};
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(h_flags, p->d_flags, kPlanFlags * sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return rfx::fail(RFX_ERR_HIP, "rfx_pv_plan: %s", hipGetErrorString(e));
+    if (h_flags[0]) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_plan: a leaf id is >= leaf_bound=%d", Lb);
+    for (int c = 0; c < p->n_chunks; ++c) p->big_cnt[c] = h_flags[1 + c];
+    p->built = true;
+    return RFX_OK;
+}
+}  // namespace
 
 int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, rfx_pv_plan** out, void* stream) {
     if (!leaf || !out) return rfx::fail(RFX_ERR_NULL, "rfx_pv_plan_create: null argument");
@@ -588,34 +653,27 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
     const int Lb = leaf_bound;
     const int64_t n_slots = (int64_t)B * Lb;
     // parts per tree: enough (part, tree) pairs to fill the chip, parts of at least 4096 samples
-    const int Q = (int)std::max<int64_t>(1, std::min<int64_t>(16, N / 4096));
-    const int64_t part_len = rfx::ceil_div(rfx::ceil_div(N, Q), 64) * 64;
+    const int Q = p->Q = (int)std::max<int64_t>(1, std::min<int64_t>(16, N / 4096));
+    const int64_t part_len = p->part_len = rfx::ceil_div(rfx::ceil_div(N, Q), 64) * 64;
     // groups of trees for the overlapped application, each with its own list of big slots
     p->n_chunks = (B >= 16 * kApplyChunks && (int64_t)B * N >= kApplyChunkMinPairs) ? kApplyChunks : 1;
-    BigGroups groups;
-    groups.n = p->n_chunks;
     int64_t max_big = 0;
     for (int c = 0; c <= p->n_chunks; ++c) p->tree_off[c] = (int32_t)((int64_t)c * B / p->n_chunks);
     for (int c = 0; c < rfx_pv_plan::kMaxChunks; ++c) {
         const int trees = c < p->n_chunks ? p->tree_off[c + 1] - p->tree_off[c] : 0;
-        groups.tree_end[c] = c < p->n_chunks ? p->tree_off[c + 1] : B;
-        groups.base[c] = p->big_base[c] = max_big;
+        p->big_base[c] = max_big;
         max_big += (int64_t)trees * N / kBigLeaf + 1;
     }
     // 1: 32-bit LDS counters; 2: 16-bit pairs (up to 65,536 leaves, parts below 65,536 samples); 0: global atomics
-    const int lds_hist = Lb <= kHistLdsLeaves ? 1 : ((Lb <= 65536 && part_len < 65536) ? 2 : 0);
-    constexpr int kFlags = 1 + rfx_pv_plan::kMaxChunks;  // bad id seen; big slots per group
-    rfx::DevBuf count, flags;
+    p->lds_hist = Lb <= kHistLdsLeaves ? 1 : ((Lb <= 65536 && part_len < 65536) ? 2 : 0);
     hipError_t e = hipMalloc((void**)&p->d_slot, sizeof(uint32_t) * (size_t)B * (size_t)N);
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_perm, sizeof(uint32_t) * (size_t)B * (size_t)N);
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_seg_start, sizeof(uint32_t) * (size_t)(n_slots + 1));
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_big, sizeof(uint32_t) * (size_t)max_big);
-    if (e == hipSuccess) e = count.alloc(sizeof(uint32_t) * (size_t)n_slots * Q);
-    if (e == hipSuccess) e = flags.alloc(kFlags * sizeof(int));
-    if (e == hipSuccess && !lds_hist) e = hipMemsetAsync(count.p, 0, sizeof(uint32_t) * (size_t)n_slots * Q, st);
-    if (e == hipSuccess) e = hipMemsetAsync(flags.p, 0, kFlags * sizeof(int), st);
+    if (e == hipSuccess) e = hipMalloc((void**)&p->d_count, sizeof(uint32_t) * (size_t)n_slots * Q);
+    if (e == hipSuccess) e = hipMalloc((void**)&p->d_flags, kPlanFlags * sizeof(int));
     const size_t hist16_lds = sizeof(uint32_t) * (size_t)((Lb + 1) / 2);
-    if (e == hipSuccess && lds_hist == 2 && hist16_lds > 64 * 1024)
+    if (e == hipSuccess && p->lds_hist == 2 && hist16_lds > 64 * 1024)
         e = hipFuncSetAttribute((const void*)pv_hist_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)hist16_lds);
     if (e == hipSuccess && p->n_chunks > 1) {
         e = side_stream(&p->side);
@@ -627,36 +685,20 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
         rfx_pv_plan_destroy(p);
         return rfx::fail(e == hipErrorOutOfMemory ? RFX_ERR_OOM : RFX_ERR_HIP, "rfx_pv_plan_create: %s", hipGetErrorString(e));
     }
-    uint32_t* cnt = count.as<uint32_t>();
-    int* bad = flags.as<int>();
-    int* n_big = bad + 1;
-    if (lds_hist == 1)
-        hipLaunchKernelGGL(pv_hist_kernel<1>, dim3(Q, B), dim3(1024), sizeof(uint32_t) * Lb, st, leaf, N, Lb, part_len,
-                           p->d_slot, cnt, bad);
-    else if (lds_hist == 2)
-        hipLaunchKernelGGL(pv_hist_kernel<2>, dim3(Q, B), dim3(1024), hist16_lds, st, leaf, N, Lb, part_len, p->d_slot, cnt,
-                           bad);
-    else
-        hipLaunchKernelGGL(pv_hist_kernel<0>, dim3(Q, B), dim3(1024), 0, st, leaf, N, Lb, part_len, p->d_slot, cnt, bad);
-    hipLaunchKernelGGL(pv_scan_kernel, dim3((unsigned)B), dim3(256), 0, st, cnt, N, B, Lb, Q, p->d_seg_start, p->d_big, n_big,
-                       groups);
-    if (Lb <= kScatterLdsLeaves)
-        hipLaunchKernelGGL(pv_scatter_lds_kernel, dim3(Q, B), dim3(64), sizeof(uint32_t) * Lb, st, p->d_slot, N, Lb, part_len,
-                           cnt, p->d_perm);
-    else
-        hipLaunchKernelGGL(pv_scatter_kernel, dim3(Q, B), dim3(64), 0, st, p->d_slot, N, Lb, part_len, cnt, p->d_perm);
-    int h_flags[kFlags] = {};
-    e = hipGetLastError();
-    if (e == hipSuccess) e = hipMemcpyAsync(h_flags, flags.p, kFlags * sizeof(int), hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess || h_flags[0]) {
+    int rc = build_plan(p, leaf, st);
+    if (rc != RFX_OK) {
         rfx_pv_plan_destroy(p);
-        if (e != hipSuccess) return rfx::fail(RFX_ERR_HIP, "rfx_pv_plan_create: %s", hipGetErrorString(e));
-        return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_plan_create: a leaf id is >= leaf_bound=%d", leaf_bound);
+        return rc;
     }
-    for (int c = 0; c < p->n_chunks; ++c) p->big_cnt[c] = h_flags[1 + c];
     *out = p;
     return RFX_OK;
+}
+
+int rfx_pv_plan_rebuild(rfx_pv_plan* p, const uint32_t* leaf, void* stream) {
+    if (!p || !leaf) return rfx::fail(RFX_ERR_NULL, "rfx_pv_plan_rebuild: null argument");
+    // applications of the old grouping on other streams must have finished; the caller orders that
+    p->built = false;
+    return build_plan(p, leaf, rfx::as_stream(stream));
 }
 
 int rfx_pv_plan_reserve(rfx_pv_plan* p, int32_t k) {
@@ -685,6 +727,7 @@ int rfx_pv_apply(rfx_pv_plan* p, const float* V, int32_t k, float* Y, void* stre
     if (!p || !V || !Y) return rfx::fail(RFX_ERR_NULL, "rfx_pv_apply: null argument");
     if (k < 1 || k > 256) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_apply: k=%d outside 1..256", k);
     if (V == Y) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_apply: V and Y must not overlap");
+    if (!p->built) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_apply: the plan's last rebuild failed");
     hipStream_t st = rfx::as_stream(stream);
     if (k > p->k_cap) {
         int rc = rfx_pv_plan_reserve(p, k);

@@ -13,7 +13,10 @@ import numpy as np
 from .mixture import FOREST_ISEED, WorkloadConfig, gaussian_mixture
 
 _HERE = Path(__file__).resolve().parent
-_LIB_PATH = _HERE / "libforest_grower.so"
+# RFX_SANITIZE=1 selects a build with AddressSanitizer and UndefinedBehaviorSanitizer (its own file name); the process
+# that loads it must have the sanitizer runtimes preloaded.
+_SANITIZE = os.environ.get("RFX_SANITIZE", "") == "1"
+_LIB_PATH = _HERE / ("libforest_grower_san.so" if _SANITIZE else "libforest_grower.so")
 _lib = None
 
 
@@ -50,7 +53,8 @@ def build_grower(force: bool = False) -> Path:
     """Compiles forest_grower.cpp with g++ (in-tree)."""
     src = _HERE / "forest_grower.cpp"
     if force or not _LIB_PATH.exists() or _LIB_PATH.stat().st_mtime < src.stat().st_mtime:
-        subprocess.run(["g++", "-O2", "-std=c++17", "-fopenmp", "-shared", "-fPIC", str(src), "-o", str(_LIB_PATH)],
+        san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-g"] if _SANITIZE else []
+        subprocess.run(["g++", "-O2", "-std=c++17", "-fopenmp", "-shared", "-fPIC", *san, str(src), "-o", str(_LIB_PATH)],
                        check=True)
     return _LIB_PATH
 

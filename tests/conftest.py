@@ -50,3 +50,19 @@ def brute_counts(leaf):
                     c += 1
             out[i, j] = c
     return out
+
+
+def converged_prefix(lam, V, lam_ref, U_ref, rtol=1e-4, angle=1e-3):
+    """The reported layer of the eigen check: the longest prefix j of Ritz pairs (lam, V) whose values are all
+    within rtol (relative) of the reference eigenvalues and whose j-dimensional span is within `angle` radians
+    of the span of the first j reference eigenvectors; and the residuals |P v - lam v| / lam cannot be formed
+    here (no P), so the caller adds them.  Returns j (0 if not even the leading pair qualifies)."""
+    import oracle
+    kk = min(len(lam), len(lam_ref))
+    rel = np.abs(np.asarray(lam[:kk], np.float64) - lam_ref[:kk]) / np.abs(lam_ref[:kk])
+    j = 0
+    while j < kk and rel[j] <= rtol:
+        j += 1
+    while j > 0 and oracle.principal_angle(V[:, :j], U_ref[:, :j]) >= angle:
+        j -= 1
+    return j

@@ -172,11 +172,50 @@ def test_lowrank_on_a_plan_equals_the_one_shot_call_and_reports_lost_rank(torch_
     torch.cuda.synchronize()
     assert int(status[0]) == 0
     assert torch.equal(lam, lam0) and torch.equal(V, Vr0) and torch.equal(Q, Q0) and torch.equal(s, s0)
-    # a start block with two equal columns loses rank: reported in the status word, not by an exception
+    # a start block with a zero column loses rank: reported in the status word, not by an exception
     bad = V0.clone()
-    bad[:, 5] = bad[:, 2]
+    bad[:, 5] = 0.0
     rfx.prox_lowrank_plan(plan, bad, T, ws, lam, V, Q, s, status)
     torch.cuda.synchronize()
     assert int(status[0]) == 1
     with pytest.raises(rfx.RfxError):
         rfx.prox_lowrank(leaf, Lb, bad, T)
+
+
+def test_plan_rebuilt_for_other_leaf_ids_equals_a_fresh_plan(torch_cuda, small2):
+    """rfx_pv_plan_rebuild regroups an existing plan without allocating: the product it then applies is bit-identical
+    to the product of a plan created from the same leaf ids, and a rebuild with an id out of range is refused and
+    leaves the plan unusable until a good rebuild."""
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    torch = torch_cuda
+    leaf_ref = small2["leaf"]
+    B, N = leaf_ref.shape
+    dev = torch.device("cuda:0")
+    Lb = int(small2["F"].n_leaves.max())
+    leaf_a = torch.from_numpy(leaf_ref.view(np.int32)).to(dev)
+    leaf_b = leaf_a.flip(0).contiguous()                     # the same trees in reverse order: other slots everywhere
+    leaf_c = (leaf_a * 7 + 3) % Lb                           # other ids altogether
+    V = torch.from_numpy(ri.start_block(N, 24)).to(dev)
+    plan = rfx.PvPlan(leaf_a, Lb)
+    Ya = plan.apply(V).clone()
+    for other in (leaf_b, leaf_c, leaf_a):
+        before = torch.cuda.memory_allocated()
+        rfx.pv_plan_rebuild(plan, other)
+        got = plan.apply(V)
+        fresh = rfx.PvPlan(other, Lb)
+        want = fresh.apply(V)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want)
+        fresh.close()
+        del got, want
+        assert torch.cuda.memory_allocated() <= before + V.numel() * 4 * 2
+    assert torch.equal(plan.apply(V), Ya)
+    bad = leaf_a.clone()
+    bad[3, 5] = Lb
+    with pytest.raises(rfx.RfxError):
+        rfx.pv_plan_rebuild(plan, bad)
+    with pytest.raises(rfx.RfxError):
+        plan.apply(V)
+    rfx.pv_plan_rebuild(plan, leaf_a)
+    assert torch.equal(plan.apply(V), Ya)

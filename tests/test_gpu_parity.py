@@ -203,6 +203,46 @@ def test_lowrank_against_the_same_iteration_in_float64(torch_cuda, request, whic
     assert err <= 2e-2, err
 
 
+@pytest.mark.parametrize("which,k", [("cfg1", 16), ("small2", 32)])
+def test_reported_layer_against_the_dense_eigendecomposition(torch_cuda, request, which, k):
+    """The binding check compares the library with the oracle running the same T = 20 applications in float64.
+    This is the reported layer: the library's Ritz pairs against LAPACK's eigendecomposition of the materialised
+    P.  After 20 applications only the leading, well-separated pairs have converged to 1e-4 (Ritz value j
+    converges like (lambda_{k+1} / lambda_j)^(2T)); the test prints the longest converged prefix j*, the
+    spectrum around it and the residuals, and requires that the prefix is not empty and that no library Ritz
+    value exceeds its eigenvalue (Ritz values of a positive semi-definite matrix approach from below)."""
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    from conftest import converged_prefix
+    torch = torch_cuda
+    d = request.getfixturevalue(which)
+    leaf = d["leaf"]
+    B, N = leaf.shape
+    T = 20
+    Lb = int(d["F"].n_leaves.max())
+    V0 = ri.start_block(N, k)
+    lam, V, _, _ = rfx.prox_lowrank(torch.from_numpy(leaf.view(np.int32)).cuda(), Lb, torch.from_numpy(V0).cuda(), T,
+                                    quantise=False)
+    lam, V = lam.cpu().numpy().astype(np.float64), V.cpu().numpy().astype(np.float64)
+    P = oracle.counts_full(leaf).astype(np.float64) / B
+    lam_d, U_d = oracle.dense_eig(P, min(N, k + 8))
+    j = converged_prefix(lam, V, lam_d, U_d)
+    res = np.linalg.norm(P @ V - V * lam[None, :], axis=0) / lam
+    rel = np.abs(lam - lam_d[:k]) / lam_d[:k]
+    print(f"reported layer {which} N={N} B={B} k={k} T={T}: converged prefix j*={j}; "
+          f"rel. eigenvalue error at j*, j*+1, k: {rel[max(j - 1, 0)]:.1e}, {rel[min(j, k - 1)]:.1e}, {rel[k - 1]:.1e}; "
+          f"residuals at 1, j*, k: {res[0]:.1e}, {res[max(j - 1, 0)]:.1e}, {res[k - 1]:.1e}; "
+          f"lambda_1={lam_d[0]:.3f} lambda_j*={lam_d[max(j - 1, 0)]:.3f} lambda_k={lam_d[k - 1]:.3f} "
+          f"lambda_k+1={lam_d[k]:.3f} (ratio^2T={(lam_d[k] / lam_d[k - 1]) ** (2 * T):.1e})", flush=True)
+    assert j >= 1
+    assert (lam <= lam_d[:k] * (1 + 1e-5)).all()
+    assert res[0] <= 1e-3
+    # the library is as close to the dense spectrum as the float64 iteration is: same prefix
+    lam_o, V_o = oracle.block_iteration(leaf, V0, T)
+    assert abs(converged_prefix(lam_o, V_o, lam_d, U_d) - j) <= 1
+
+
 def _align(coords, ref, lam):
     """Ritz vectors of (nearly) equal eigenvalues are defined up to a rotation inside their
     eigenspace; align with orthogonal Procrustes in that case, otherwise compare as is."""

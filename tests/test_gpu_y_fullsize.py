@@ -291,7 +291,7 @@ def _check_matvec(d, k, n_rows, prox=None):
     plan.close()
 
 
-def _check_lowrank_and_mds(d, k, T, mds_reference="arpack"):
+def _check_lowrank_and_mds(d, k, T, mds_reference="arpack", reported_pairs=0):
     import torch
     import oracle
     import paper_2511_19493_amd as rfx
@@ -309,6 +309,21 @@ def _check_lowrank_and_mds(d, k, T, mds_reference="arpack"):
     ang = oracle.principal_angle(V, V_ref)
     say(f"Ritz values: max relative difference {rel.max():.2e}; largest principal angle {ang:.2e} rad")
     assert rel.max() <= 1e-4 and ang < 1e-3
+    if reported_pairs:
+        # the reported layer: the library's Ritz pairs against the eigendecomposition itself (ARPACK on the float64
+        # operator, P being too large for LAPACK): longest converged prefix, spectrum around it, residuals
+        from conftest import converged_prefix
+        t0 = time.time()
+        lam_e, U_e = oracle.implicit_eig(d["ref_leaf"], reported_pairs, tol=1e-10)
+        j = converged_prefix(lam.astype(np.float64), V.astype(np.float64), lam_e, U_e)
+        PV = oracle.pv_implicit(d["ref_leaf"], V.astype(np.float64))
+        res = np.linalg.norm(PV - V * lam[None, :], axis=0) / lam
+        rel_e = np.abs(lam[:reported_pairs] - lam_e) / lam_e
+        say(f"reported layer: top {reported_pairs} eigenpairs by ARPACK in {time.time() - t0:.0f}s; converged prefix j*={j}; "
+            f"relative eigenvalue errors {np.array2string(rel_e, precision=1)}; residuals of pairs 1, j*, k: {res[0]:.1e}, "
+            f"{res[max(j - 1, 0)]:.1e}, {res[k - 1]:.1e}; eigenvalues {np.array2string(lam_e, precision=2)}; Ritz values "
+            f"{k - 1}, {k}: {lam[k - 2]:.3f}, {lam[k - 1]:.3f}")
+        assert j >= 1 and (lam[:reported_pairs] <= lam_e * (1 + 1e-5)).all()
     Qr, sr = oracle.quantise_int8(V, lam)
     np.testing.assert_array_equal(s.cpu().numpy(), sr)
     np.testing.assert_array_equal(Q.cpu().numpy(), Qr)
@@ -362,7 +377,7 @@ def test_cfg3_dense_and_rank32(w3):
     _check_sparse(w3, 16)
     _check_consumers(w3, 12)
     _check_oob(w3, 12)
-    _check_lowrank_and_mds(w3, 32, 20)
+    _check_lowrank_and_mds(w3, 32, 20, reported_pairs=14)
 
 
 def test_cfg4_leaf_and_dense(w4):
@@ -388,6 +403,122 @@ def test_cfg5_rows_with_reduced_trees(w5_reduced):
     _check_matvec(w5_reduced, 64, 8)
     _check_sparse(w5_reduced, 8)
     _check_lowrank_and_mds(w5_reduced, 64, 20, mds_reference="residual")
+
+
+def test_cfg5_full_tree_count():
+    """Workload 5 as bench.py runs it: 500,000 rows x 64 features, 20 classes, all 1,000 trees (about 90 M nodes,
+    46k leaves per tree, 5e8 (tree, sample) slots).  The CPU input generator would need tens of minutes for this
+    forest, so it is grown by rfx_forest_grow (bit-identical to the oracle's grower on the 8-tree check above; for
+    everything downstream a forest is only an input).  Covered: leaf ids of all 5e8 walks bit-exact against the
+    oracle's traversal; the sparse pass on sampled rows and columns plus its exact sum identity; one implicit product
+    against the oracle's float64 product IN FULL (all N rows); the factorisation against the oracle's float64 block
+    iteration from the same start block (Ritz values, subspace angle); INT8 codes bit-exact; INT8 product error; the
+    scaling eigenpairs through the float64 operator.  Not covered at this size: the dense outputs (1 TB, they do not
+    exist) and an eigen-solver reference for the scaling step (residuals instead)."""
+    import torch
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    c = ri.CONFIGS[5]
+    N, B, k, T = c.N, c.B, 64, 20
+    X, y = ri.gaussian_mixture(c)
+    dX, dy = torch.from_numpy(X).cuda(), torch.from_numpy(y.astype(np.int32)).cuda()
+    t0 = time.time()
+    g = rfx.forest_grow(dX, dy, c.C, B, c.mtry, ri.mixture.FOREST_ISEED)
+    say(f"cfg5 at {B} trees: forest grown on the GPU in {time.time() - t0:.1f}s, {int(g['node_offset'][-1])} nodes, "
+        f"most leaves {int(g['n_leaves'].max())}, deepest level {int(g['depth'].max())}")
+    F = ri.Forest(B, c.M, g["node_offset"], g["feature"], g["threshold"], g["left"], g["right"], g["leaf_id"], g["depth"],
+                  g["n_leaves"], g["inbag"], None)
+    gf = _forest(F)
+    Lb = gf.leaf_bound
+    leaf = rfx.leaf_assign(gf, dX)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    ref_leaf, plen = oracle.leaf_assign(F, X)
+    say(f"oracle leaf assignment of {B * N:.1e} walks in {time.time() - t0:.0f}s, mean path {plen / ref_leaf.size:.2f}")
+    for b0 in range(0, B, 125):                            # 250 MB at a time
+        np.testing.assert_array_equal(_u32(leaf[b0:b0 + 125]), ref_leaf[b0:b0 + 125])
+    say("cfg5 leaf ids bit-exact (all trees, all samples)")
+    d = dict(c=c, X=X, F=F, ref_leaf=ref_leaf, gf=gf, leaf=leaf, Lb=Lb)
+
+    # sparse pass (the tile kernel bench.py times at this workload): count, sum identity, sampled rows and columns
+    t0 = time.time()
+    nnz = rfx.prox_sparse_count(leaf, Lb, 1)
+    say(f"sparse: {nnz} non-zero pairs ({nnz / (N * (N - 1) / 2):.2%} of the triangle), counted in {time.time() - t0:.2f}s")
+    sq = 0
+    for b in range(B):
+        sq += int((np.bincount(ref_leaf[b]).astype(np.int64) ** 2).sum())
+    say(f"sum over trees and leaves of size^2 = {sq:.6e} = {sq / B:.4e} per tree, against N^2/2 = {N * N / 2:.3e} pair tests per tree "
+        f"({N * N / 2 / (sq / B):.0f}x)")
+    rows, cols, counts, _ = rfx.prox_sparse(leaf, Lb, 1, capacity=nnz, count_dtype=rfx.U16)
+    torch.cuda.synchronize()
+    assert rows.numel() == nnz and bool((rows < cols).all()) and int(cols.max()) < N
+    total = 0
+    for s0 in range(0, nnz, 1 << 28):
+        total += int(counts[s0:s0 + (1 << 28)].to(torch.int32).bitwise_and(0xFFFF).sum(dtype=torch.int64))
+    assert 2 * total + N * B == sq
+    say("sparse: 2 sum(counts) + N B equals the summed squared leaf sizes exactly")
+    for i in _sample_rows(N, 4, 14):
+        ref = oracle.counts_rows(ref_leaf, i, i + 1)[0]
+        for own, other, lo, hi in ((rows, cols, i + 1, N), (cols, rows, 0, i)):
+            js, vs = [], []
+            for s0 in range(0, nnz, 1 << 30):               # masks over more than 2^31 entries are taken in pieces
+                at = (own[s0:s0 + (1 << 30)] == i).nonzero().flatten() + s0
+                js.append(other[at].cpu().numpy().astype(np.int64))
+                vs.append(counts[at].cpu().numpy().view(np.uint16).astype(np.uint32))
+            j, v = np.concatenate(js), np.concatenate(vs)
+            order = np.argsort(j)
+            want_j = np.nonzero(ref[lo:hi] >= 1)[0] + lo
+            np.testing.assert_array_equal(j[order], want_j, err_msg=f"sample {i}")
+            np.testing.assert_array_equal(v[order], ref[want_j], err_msg=f"sample {i}")
+    say("sparse: sampled rows and columns exact")
+    del rows, cols, counts
+    torch.cuda.empty_cache()
+
+    # implicit product, in full, and the factorisation against the float64 iteration from the same start block
+    V0 = ri.start_block(N, k)
+    plan = rfx.PvPlan(leaf, Lb)
+    Y = plan.apply(torch.from_numpy(V0).cuda()).cpu().numpy().astype(np.float64)
+    plan.close()
+    t0 = time.time()
+    Yref = oracle.pv_implicit(ref_leaf, V0.astype(np.float64))
+    err = np.linalg.norm(Y - Yref) / np.linalg.norm(Yref)
+    say(f"P.V k={k} against the oracle's float64 product on all {N} rows ({time.time() - t0:.0f}s): relative Frobenius error {err:.2e}")
+    assert err <= 1e-5
+    del Y, Yref
+    lam, V, Q, s = rfx.prox_lowrank(leaf, Lb, torch.from_numpy(V0).cuda(), T)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    lam_ref, V_ref = oracle.block_iteration(ref_leaf, V0, T, progress=lambda t: say(f"  oracle block iteration: application {t}/{T} after {time.time() - t0:.0f}s"))
+    lam_h, V_h = lam.cpu().numpy(), V.cpu().numpy()
+    rel = np.abs(lam_h - lam_ref) / lam_ref
+    ang = oracle.principal_angle(V_h, V_ref)
+    say(f"Ritz values: max relative difference {rel.max():.2e}; largest principal angle {ang:.2e} rad")
+    assert rel.max() <= 1e-4 and ang < 1e-3
+    Qr, sr = oracle.quantise_int8(V_h, lam_h)
+    np.testing.assert_array_equal(s.cpu().numpy(), sr)
+    np.testing.assert_array_equal(Q.cpu().numpy(), Qr)
+    say("INT8 codes and scales bit-exact")
+    A = oracle.dequantise(Qr, sr)
+    PX = oracle.pv_implicit(ref_leaf, V_ref)
+    err = np.linalg.norm(A @ (A.T @ V_ref) - PX) / np.linalg.norm(PX)
+    say(f"INT8-dequantised P.V on the converged block: relative Frobenius error {err:.2e}")
+    assert err <= 2e-2
+    del PX, V_ref
+
+    m = 16
+    x0 = ri.start_block(N, m, seed=778)
+    coords, ev, iters = rfx.mds3d(Q, s, torch.from_numpy(x0).cuda(), rfx.MDS_SQUARED, max_iters=300, tol=1e-7)
+    coords, ev = coords.cpu().numpy().astype(np.float64), ev.cpu().numpy().astype(np.float64)
+    op = oracle.mds_operator(A, oracle.SQUARED)
+    Vn = coords / np.sqrt(ev)[None, :]
+    GV = op(Vn)
+    rq = (Vn * GV).sum(axis=0)
+    res = np.linalg.norm(GV - Vn * ev[None, :], axis=0) / ev[0]
+    say(f"scaling: {iters} iterations; eigenvalues {ev}; Rayleigh quotients {rq}; residuals {res}")
+    np.testing.assert_allclose(rq, ev, rtol=1e-4)
+    assert res.max() <= 5e-3
+    assert np.abs(coords.sum(axis=0)).max() <= 1e-3 * np.abs(coords).max() * np.sqrt(N)
 
 
 # ------------------------------------------------------------------------------------------ forest growth

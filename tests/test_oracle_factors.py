@@ -285,3 +285,17 @@ def test_scaling_of_a_factor_of_rank_below_three():
     coords, lam = oracle.mds3d_dense(Q, s, oracle.LINEAR)
     assert lam[1] > 1e-3 * lam[0] and abs(lam[2]) < 1e-10 * lam[0]
     assert np.abs(coords[:, 2]).max() < 1e-4 * np.abs(coords[:, 0]).max()
+
+
+def test_implicit_eigensolver_equals_the_dense_eigendecomposition(cfg1, small2):
+    """The ARPACK route on the implicit float64 operator (used where P cannot be materialised) against LAPACK on
+    the materialised matrix: same leading eigenvalues, same invariant subspace."""
+    for d, k in ((cfg1, 6), (small2, 8)):
+        leaf = d["leaf"]
+        B, N = leaf.shape
+        P = oracle.counts_full(leaf).astype(np.float64) / B
+        lam_d, U_d = oracle.dense_eig(P, k)
+        lam_i, U_i = oracle.implicit_eig(leaf, k)
+        np.testing.assert_allclose(lam_i, lam_d, rtol=1e-10)
+        assert oracle.principal_angle(U_i, U_d) < 1e-6
+        np.testing.assert_allclose(P @ U_i, U_i * lam_i[None, :], atol=1e-8 * lam_d[0])
