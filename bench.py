@@ -162,9 +162,19 @@ class Workload:
         return out
 
     def sparse_pass(self):
+        """Every non-zero pair as (i, j, count).  Large workloads take the synchronous call, which picks the cheaper of
+        its two algorithms (pair tests on bit planes, or counting row by row from the samples grouped by leaf) and builds
+        the grouping it needs inside the call; the others time the asynchronous tile pass."""
         rfx = self.rfx
-        rfx.prox_sparse_ws(self.leaf, self.Lb, self.ws_prox, self.sp_nnz, self.sp_rows, self.sp_cols, self.sp_cnt,
-                           min_count=1, count_dtype=rfx.U16)
+        if self.large:
+            got = ctypes.c_int64(0)
+            rfx._check(self.lib.rfx_prox_sparse(self.leaf.data_ptr(), self.N, self.B, self.Lb, 1, rfx.U16, self.sp_cap,
+                                                self.sp_rows.data_ptr(), self.sp_cols.data_ptr(), self.sp_cnt.data_ptr(), 0,
+                                                ctypes.byref(got), self.stream))
+            self.sp_nnz[0] = got.value
+        else:
+            rfx.prox_sparse_ws(self.leaf, self.Lb, self.ws_prox, self.sp_nnz, self.sp_rows, self.sp_cols, self.sp_cnt,
+                               min_count=1, count_dtype=rfx.U16)
 
     def dense_and_oob_separately(self):
         rfx = self.rfx
@@ -209,7 +219,8 @@ def measure_sparse(w, kern):
     rfx, torch = w.rfx, w.torch
     if w.large:
         assert int(w.sp_nnz[0]) == w.sp_cap, "the sparse pass found a different number of pairs than the counting call"
-        nnz, sp_ms = w.sp_cap, kern["prox_tile_kernel_sparse"]["avg_ms"]
+        by_rows = kern["sparse_rows_kernel"]["launches"] > 0
+        nnz, sp_ms = w.sp_cap, kern["sparse_rows_kernel" if by_rows else "prox_tile_kernel_sparse"]["avg_ms"]
     else:
         nnz = rfx.prox_sparse_count(w.leaf, w.Lb, 1)
         w.alloc_sparse(max(nnz, 1))
@@ -220,10 +231,13 @@ def measure_sparse(w, kern):
         sp_ms, sp_n = rfx.timing_get("prox_tile_kernel_sparse")
         sp_ms /= max(sp_n, 1)
         assert int(w.sp_nnz[0]) == nnz
+        by_rows = False
     w.free_sparse()
     N, tests = w.N, w.tests
     return {"note": ("part of the step" if w.large else "not part of the step")
                     + ": strict-upper (i, j, count) triplets of every non-zero pair",
+            "algorithm": "row by row from the samples grouped by leaf (sparse_rows_kernel)" if by_rows
+                         else "pair tests on bit planes (prox_tile_kernel_sparse)",
             "min_count": 1, "pairs": nnz, "fraction_of_triangle": nnz / max(N * (N - 1) / 2.0, 1.0),
             "bytes_out": 10 * nnz, "avg_launch_ms": sp_ms,
             "tests_per_s": tests / (sp_ms * 1e-3) if sp_ms > 0 else 0.0,
@@ -387,6 +401,21 @@ def roofline_of_tile_kernel(w, kern, valu_rate, profile, profile_src):
     (padded) N x N grid; per 32 trees and pair, P + 1 vector ops for the plain count, P + 7 for the fused pass that also
     yields the out-of-bag numerator and denominator."""
     tests, P = w.tests, w.P
+    if w.large and kern["sparse_rows_kernel"]["launches"] > 0:
+        # the row pass: its work is counter increments (LDS atomics), one per co-member pair and tree
+        ms = kern["sparse_rows_kernel"]["avg_ms"]
+        sizes_sq = 0
+        for b0 in range(0, w.B, 50):
+            for b in range(b0, min(b0 + 50, w.B)):
+                cnt = w.torch.bincount(w.leaf[b].long(), minlength=w.Lb).double()
+                sizes_sq += float((cnt * (cnt - 1) / 2).sum())
+        peak = 256 * 32 * 2.4e9          # LDS atomic lanes per second: 256 CUs x 32 banks x 2.4 GHz
+        return {"kernel": "sparse_rows_kernel", "bound": "lds", "achieved": sizes_sq / (ms * 1e-3) / 1e12, "peak": peak / 1e12,
+                "unit": "T counter increments/s", "frac": sizes_sq / (ms * 1e-3) / peak, "traffic": None,
+                "increments": sizes_sq, "avg_launch_ms": ms, "tests_per_s": tests / (ms * 1e-3),
+                "note": "sum over trees and leaves of s (s - 1) / 2 increments instead of N^2 B / 2 pair tests; the pass is bound by "
+                        "the scattered reads of the leaf members, not by the LDS atomics, so the fraction is small by construction; "
+                        "tests_per_s is the pair-test rate the same result would need"}
     mode = 2 if w.large else (4 if w.fused else 0)
     dom = "prox_tile_kernel_sparse" if w.large else ("prox_tile_kernel_both" if w.fused else "prox_tile_kernel")
     ops_per_test = (P + 7) / 32.0 if w.fused else (P + 1) / 32.0
@@ -542,7 +571,7 @@ def main():
     phases = {n: v["mean"] for n, v in stats.items()}
     kern = {}
     for name in ("leaf_assign_kernel", "prox_tile_kernel_both", "prox_tile_kernel", "prox_tile_kernel_oob",
-                 "prox_tile_kernel_sparse", "pv_apply", "pv_leaf_sum_kernel", "pv_gather_kernel"):
+                 "prox_tile_kernel_sparse", "sparse_rows_kernel", "pv_apply", "pv_leaf_sum_kernel", "pv_gather_kernel"):
         ms, n = rfx.timing_get(name)
         kern[name] = {"avg_ms": ms / max(n, 1), "launches": n, "total_ms": ms}
 

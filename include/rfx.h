@@ -256,6 +256,17 @@ int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
                     int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox, int64_t* nnz,
                     void* stream);
 
+/* The same list computed row by row from the samples grouped by leaf instead of by testing all pairs: for every
+ * sample i and tree b the members j > i of i's leaf are counted into a row of 16-bit counters, sum over trees and
+ * leaves of s (s - 1) / 2 increments in all instead of N^2 B / 2 tests, which pays on deep forests whose leaves are
+ * small (N = 500,000, B = 1,000: three orders of magnitude fewer).  Arguments, outputs and errors as rfx_prox_sparse;
+ * the entries come out grouped by row.  B <= 4096, B * N < 2^32 and B * leaf_bound < 2^32, else RFX_ERR_UNSUPPORTED.
+ * Builds and destroys a grouping (rfx_pv_plan) and 4 B N bytes of scratch inside the call.  Synchronous.
+ * rfx_prox_sparse itself chooses between the two by their estimated cost. */
+int rfx_prox_sparse_rows(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count,
+                         int count_dtype, int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox,
+                         int64_t* nnz, void* stream);
+
 /* Case-wise outlier measures from the proximity rows ("Case-wise Proximity"), computed tile by
  * tile without storing the matrix.  With p(i,j) = cnt(i,j) / B:
  *   printed[i] = (1/(N-1)) sum_{j != i, p(i,j) > 0} 1 / p(i,j)^2   the paper's equation; pairs with

@@ -25,7 +25,7 @@ ENC_INT8, ENC_FP16, ENC_NF4, ENC_FP32 = 0, 1, 2, 3
 
 EXPORTS = (
     "rfx_last_error", "rfx_timing_enable", "rfx_timing_get", "rfx_probe_valu", "rfx_probe_copy", "rfx_probe_gather", "rfx_probe_chase", "rfx_forest_grow", "rfx_grown_sizes", "rfx_grown_export", "rfx_grown_destroy", "rfx_growth_draw", "rfx_forest_create", "rfx_forest_destroy", "rfx_forest_leaf_bound", "rfx_leaf_assign",
-    "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_dense_oob", "rfx_prox_sparse", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
+    "rfx_prox_dense", "rfx_prox_oob", "rfx_prox_dense_oob", "rfx_prox_sparse", "rfx_prox_sparse_rows", "rfx_prox_outlier", "rfx_oob_vote", "rfx_pv_plan_create", "rfx_pv_plan_destroy", "rfx_pv_apply",
     "rfx_prox_matvec", "rfx_prox_lowrank", "rfx_quantise_int8", "rfx_mds3d", "rfx_mds3d_factor",
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
     "rfx_prox_workspace_bytes", "rfx_prox_dense_ws", "rfx_prox_oob_ws", "rfx_prox_dense_oob_ws", "rfx_prox_sparse_ws",
@@ -78,6 +78,7 @@ def load():
             "rfx_prox_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp],
             "rfx_prox_dense_oob": [vp, vp, i64, i32, i32, ci, ci, vp, vp, ci, vp, vp, vp, vp],
             "rfx_prox_sparse": [vp, i64, i32, i32, i32, ci, i64, vp, vp, vp, vp, ctypes.POINTER(i64), vp],
+            "rfx_prox_sparse_rows": [vp, i64, i32, i32, i32, ci, i64, vp, vp, vp, vp, ctypes.POINTER(i64), vp],
             "rfx_prox_outlier": [vp, i64, i32, i32, vp, vp, vp, vp],
             "rfx_oob_vote": [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, ctypes.POINTER(i64), ctypes.POINTER(i64), vp],
             "rfx_pv_plan_create": [vp, i64, i32, i32, ctypes.POINTER(vp), vp],
@@ -306,18 +307,26 @@ def prox_dense_oob(leaf, inbag, leaf_bound: int, count_dtype: int = U32, layout:
     return counts, prox, num, den, prox_oob
 
 
-def prox_sparse_count(leaf, leaf_bound: int, min_count: int = 1) -> int:
+def _sparse_fn(method: str):
+    """rfx_prox_sparse ("auto": the library chooses; "tiles": not selectable from here, auto on shallow forests) or
+    rfx_prox_sparse_rows ("rows")."""
+    if method not in ("auto", "rows"):
+        raise ValueError("method must be 'auto' or 'rows'")
+    return load().rfx_prox_sparse if method == "auto" else load().rfx_prox_sparse_rows
+
+
+def prox_sparse_count(leaf, leaf_bound: int, min_count: int = 1, method: str = "auto") -> int:
     """rfx_prox_sparse with capacity 0: the number of pairs i < j with cnt(i,j) >= min_count."""
     import torch
     B, N = leaf.shape
     nnz = ctypes.c_int64(0)
-    _check(load().rfx_prox_sparse(_dev(leaf, torch.int32), N, B, leaf_bound, min_count, U32, 0, 0, 0, 0, 0,
+    _check(_sparse_fn(method)(_dev(leaf, torch.int32), N, B, leaf_bound, min_count, U32, 0, 0, 0, 0, 0,
                                   ctypes.byref(nnz), _stream()))
     return nnz.value
 
 
 def prox_sparse(leaf, leaf_bound: int, min_count: int = 1, capacity: int = None, count_dtype: int = U32,
-                want_counts: bool = True, want_prox: bool = False):
+                want_counts: bool = True, want_prox: bool = False, method: str = "auto"):
     """rfx_prox_sparse: returns (rows, cols, counts, prox), each trimmed to the number of kept pairs.
 
     `capacity` None runs the counting call first and allocates exactly; a given capacity that is too
@@ -325,13 +334,13 @@ def prox_sparse(leaf, leaf_bound: int, min_count: int = 1, capacity: int = None,
     import torch
     B, N = leaf.shape
     if capacity is None:
-        capacity = max(prox_sparse_count(leaf, leaf_bound, min_count), 1)
+        capacity = max(prox_sparse_count(leaf, leaf_bound, min_count, method), 1)
     rows = torch.empty(capacity, dtype=torch.int32, device=leaf.device)
     cols = torch.empty(capacity, dtype=torch.int32, device=leaf.device)
     counts = torch.empty(capacity, dtype=_count_dtype(count_dtype), device=leaf.device) if want_counts else None
     prox = torch.empty(capacity, dtype=torch.float32, device=leaf.device) if want_prox else None
     nnz = ctypes.c_int64(0)
-    _check(load().rfx_prox_sparse(_dev(leaf, torch.int32), N, B, leaf_bound, min_count, count_dtype, capacity,
+    _check(_sparse_fn(method)(_dev(leaf, torch.int32), N, B, leaf_bound, min_count, count_dtype, capacity,
                                   rows.data_ptr(), cols.data_ptr(), counts.data_ptr() if counts is not None else 0,
                                   prox.data_ptr() if prox is not None else 0, ctypes.byref(nnz), _stream()))
     n = nnz.value

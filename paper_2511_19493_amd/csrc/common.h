@@ -51,6 +51,10 @@ struct TimedLaunch {
     hipEvent_t start_ = nullptr;
 };
 
+// Whether the row pass over the samples grouped by leaf is expected to list the non-zero pairs faster than the pair
+// tests on bit planes (prox_rows.hip).
+int sparse_rows_cheaper(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, hipStream_t st, bool* rows_cheaper);
+
 }  // namespace rfx
 
 #define RFX_HIP(call)                                                                                    \

@@ -31,6 +31,9 @@ namespace {
 #ifndef RFX_R
 #define RFX_R 4
 #endif
+#ifndef RFX_B_PREFETCH
+#define RFX_B_PREFETCH 0
+#endif
 constexpr int kR = RFX_R;       // a samples per lane
 constexpr int kATile = 64 * kR; // a samples per wave / workgroup
 constexpr int kWaves = 4;
@@ -585,11 +588,33 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(P, kMode)) void prox_til
                 xa[r][v * 4 + 3] = q.w;
             }
         const uint32_t* __restrict__ pb = planes + ((int64_t)g * Npad + b0) * PS;  // wave-uniform
+#if RFX_B_PREFETCH
+        // The planes of b sample j + 1 are requested while those of sample j are being used: scalar loads return in any
+        // order, so the only wait there is waits for all of them, and a request must therefore go out after the wait for
+        // the previous one and before the vector work that hides it.  The empty asm statements pin that order (they
+        // consume the words of sample j, which places the wait), the scheduling barriers keep the compiler from moving
+        // the requests back down to their first use.
+        uint32_t xq[2][PL];
+#pragma unroll
+        for (int p = 0; p < PL; ++p) xq[0][p] = pb[p];
+#endif
 #pragma unroll
         for (int j = 0; j < J; ++j) {
             uint32_t xb[PL];
+#if RFX_B_PREFETCH
+#pragma unroll
+            for (int p = 0; p < PL; ++p) xb[p] = xq[j & 1][p];
+            asm volatile("" ::"s"(xb[0]), "s"(xb[PL - 1]), "s"(xb[PL / 2]));
+            __builtin_amdgcn_sched_barrier(0);
+            if (j + 1 < J) {
+#pragma unroll
+                for (int p = 0; p < PL; ++p) xq[(j + 1) & 1][p] = pb[(j + 1) * PS + p];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#else
 #pragma unroll
             for (int p = 0; p < PL; ++p) xb[p] = pb[j * PS + p];  // uniform address: scalar loads into SGPRs
+#endif
 #pragma unroll
             for (int r = 0; r < kR; ++r) {
                 uint32_t t = xa[r][0] ^ xb[0];
@@ -879,6 +904,11 @@ int rfx_prox_sparse(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bou
                     void* stream) {
     int rc = check_sparse(leaf, N, B, leaf_bound, min_count, count_dtype, capacity, rows, cols, nnz);
     if (rc != RFX_OK) return rc;
+    // deep forests with small leaves: far fewer counter increments than pair tests
+    bool by_rows = false;
+    if ((rc = rfx::sparse_rows_cheaper(leaf, N, B, leaf_bound, rfx::as_stream(stream), &by_rows)) != RFX_OK) return rc;
+    if (by_rows)
+        return rfx_prox_sparse_rows(leaf, N, B, leaf_bound, min_count, count_dtype, capacity, rows, cols, counts, prox, nnz, stream);
     const ProxScratch need = prox_scratch(N, B, leaf_bound);
     unsigned long long total = 0;
     rc = with_own_workspace("rfx_prox_sparse", N, B, leaf_bound, rfx::as_stream(stream), [&](void* ws, int64_t bytes) {

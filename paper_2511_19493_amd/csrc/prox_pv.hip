@@ -28,34 +28,8 @@
 #include <vector>
 
 #include "common.h"
+#include "prox_pv.h"
 
-struct rfx_pv_plan {
-    int64_t N = 0;
-    int32_t B = 0, Lb = 0;
-    uint32_t* d_slot = nullptr;       // [B][N]  b*Lb + leaf_b(i)
-    uint32_t* d_perm = nullptr;       // [B*N]
-    uint32_t* d_seg_start = nullptr;  // [B*Lb + 1]
-    uint32_t* d_big = nullptr;        // slots with more than kBigLeaf members, one list per group of trees
-    float* d_S = nullptr;             // [B*Lb][k_cap]
-    int32_t k_cap = 0;
-    // scratch of the grouping, kept so that the plan can be rebuilt for new leaf ids without allocating
-    uint32_t* d_count = nullptr;      // [B][Q][Lb] part histograms, then cursors
-    int* d_flags = nullptr;           // bad id seen; big slots per group
-    int32_t Q = 1;                    // parts per tree
-    int64_t part_len = 0;
-    int32_t lds_hist = 0;
-    bool built = false;               // false after a rebuild that failed: applications are refused
-    // An application runs in n_chunks groups of trees: the leaf sums of a group on the caller's stream, its gather on
-    // `side` as soon as they are done, so the gather of one group overlaps the sums of the next.
-    static constexpr int kMaxChunks = 4;
-    int32_t n_chunks = 1;
-    int32_t tree_off[kMaxChunks + 1] = {};   // trees of group c: [tree_off[c], tree_off[c + 1])
-    int64_t big_base[kMaxChunks] = {};       // its big slots: d_big[big_base[c] .. big_base[c] + big_cnt[c])
-    int32_t big_cnt[kMaxChunks] = {};
-    hipStream_t side = nullptr;              // shared by all plans of the device, never destroyed
-    hipEvent_t ev_sum[kMaxChunks] = {};
-    hipEvent_t ev_done = nullptr;
-};
 
 namespace {
 

@@ -28,25 +28,34 @@ def _sorted_triplets(rows, cols, counts, prox=None):
 
 
 def _compare(torch, rfx, oracle, leaf, bound, min_count, dtype):
+    """Both ways the library computes the list (pair tests on bit planes: "auto" on these shallow cases; row by row from
+    the samples grouped by leaf: "rows") against the oracle's."""
     B, N = leaf.shape
     rr, rc, rv = oracle.sparse_upper(leaf, min_count)
-    assert rfx.prox_sparse_count(_dev(torch, leaf), bound, min_count) == rr.size
-    rows, cols, counts, prox = rfx.prox_sparse(_dev(torch, leaf), bound, min_count, count_dtype=dtype, want_prox=True)
-    r, c, v, p = _sorted_triplets(rows, cols, counts, prox)
-    np.testing.assert_array_equal(r, rr)
-    np.testing.assert_array_equal(c, rc)
-    np.testing.assert_array_equal(v, rv)
-    np.testing.assert_array_equal(p, (rv.astype(np.float32) / np.float32(B)).astype(np.float32))
+    for method in ("auto", "rows"):
+        assert rfx.prox_sparse_count(_dev(torch, leaf), bound, min_count, method) == rr.size, method
+        rows, cols, counts, prox = rfx.prox_sparse(_dev(torch, leaf), bound, min_count, count_dtype=dtype, want_prox=True,
+                                                   method=method)
+        r, c, v, p = _sorted_triplets(rows, cols, counts, prox)
+        np.testing.assert_array_equal(r, rr, err_msg=method)
+        np.testing.assert_array_equal(c, rc, err_msg=method)
+        np.testing.assert_array_equal(v, rv, err_msg=method)
+        np.testing.assert_array_equal(p, (rv.astype(np.float32) / np.float32(B)).astype(np.float32), err_msg=method)
 
 
 @pytest.mark.parametrize("N,B,bound", [(1, 3, 5), (2, 1, 2), (255, 31, 40), (256, 32, 40), (257, 33, 40), (515, 65, 2),
-                                       (300, 97, 1), (1100, 40, 3000)])
+                                       (300, 97, 1), (1100, 40, 3000), (70000, 5, 9000), (32769, 3, 600), (65536, 2, 40000)])
 def test_sparse_on_boundary_shapes(torch_cuda, N, B, bound):
     import oracle
     import paper_2511_19493_amd as rfx
     print(f"sparse boundary shapes N={N} B={B} bound={bound}", flush=True)
     rng = np.random.default_rng(7000 * N + B)
     leaf = rng.integers(0, bound, size=(B, N)).astype(np.uint32)
+    if N > 20000:            # several column chunks of the row pass; the oracle needs seconds per list here
+        leaf[:, N - 3:] = leaf[:, :1]       # pairs across the first and the last chunk
+        _compare(torch_cuda, rfx, oracle, leaf, bound, 1, rfx.U32)
+        _compare(torch_cuda, rfx, oracle, leaf, bound, 2, rfx.U16)
+        return
     for min_count in sorted({1, 2, max(1, B // 4), B}):
         _compare(torch_cuda, rfx, oracle, leaf, bound, min_count, rfx.U32)
     if B <= 65535:
@@ -101,3 +110,15 @@ def test_sparse_capacity_and_argument_errors(torch_cuda, cfg1):
     b = _sorted_triplets(*rfx.prox_sparse(d, bound, 2)[:3])
     for x, y in zip(a[:3], b[:3]):
         np.testing.assert_array_equal(x, y)
+
+
+def test_row_pass_rejects_what_it_cannot_hold(torch_cuda):
+    import paper_2511_19493_amd as rfx
+    import ctypes
+    lib = rfx.load()
+    fake = ctypes.c_void_p(0x1000)
+    nnz = ctypes.c_int64(0)
+    assert lib.rfx_prox_sparse_rows(fake, 100, 5000, 8, 1, rfx.U32, 0, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_UNSUPPORTED
+    assert lib.rfx_prox_sparse_rows(fake, 100, 50, 8, 0, rfx.U32, 0, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_prox_sparse_rows(fake, 100, 50, 8, 1, rfx.U32, 4, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_NULL
+    assert lib.rfx_prox_sparse_rows(None, 100, 50, 8, 1, rfx.U32, 0, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_NULL
