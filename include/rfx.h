@@ -202,6 +202,19 @@ int rfx_prox_dense_ws(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_b
 int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
                    void* counts, float* prox, void* stream);
 
+/* rfx_prox_dense for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc).  Same arguments, outputs and errors as rfx_prox_dense,
+ * but the bit-plane scratch is a 16 MiB array inside the library (one copy per GPU, held until the
+ * process ends), so the call allocates nothing, frees nothing, creates no events (the timing aid does not
+ * cover it) and is asynchronous.  Limit: 4 * ceil(B/32) * roundup(N, 256) * roundup4(bits + 1) <= 16 MiB
+ * with bits = max(8, ceil(log2(leaf_bound))), e.g. N = 10,000 with B = 500 and leaf_bound <= 2048, or
+ * N = 4,096 with B = 1,000 and leaf_bound <= 32,768; a larger problem returns RFX_ERR_CAPACITY and
+ * launches nothing.  Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU
+ * (different streams or threads) race on it; calls on one stream are ordered and safe.  The array needs no
+ * clearing between calls (every word a call reads it has written first). */
+int rfx_prox_dense_noalloc(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
+                           void* counts, float* prox, void* stream);
+
 /* Out-of-bag-only proximity.  With c_b(i) the bootstrap in-bag count of sample i in tree b
  * and OOB_i = {b : c_b(i) = 0} ("Case-wise Bootstrap Tracking"):
  *   num(i,j) = #{b in OOB_i and OOB_j : leaf_b(i) = leaf_b(j)},  den(i,j) = |OOB_i and OOB_j|,

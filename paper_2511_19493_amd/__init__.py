@@ -30,7 +30,7 @@ EXPORTS = (
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
     "rfx_prox_workspace_bytes", "rfx_prox_dense_ws", "rfx_prox_oob_ws", "rfx_prox_dense_oob_ws", "rfx_prox_sparse_ws",
     "rfx_prox_outlier_ws", "rfx_pv_plan_reserve", "rfx_pv_plan_rebuild", "rfx_pv_plan_info", "rfx_lowrank_workspace_bytes", "rfx_prox_lowrank_plan",
-    "rfx_mds3d_workspace_bytes", "rfx_mds3d_ws",
+    "rfx_mds3d_workspace_bytes", "rfx_mds3d_ws", "rfx_prox_dense_noalloc",
 )
 
 
@@ -94,6 +94,7 @@ def load():
             "rfx_dequantise_factor": [vp, vp, i64, i32, ci, vp, vp],
             "rfx_prox_workspace_bytes": [i64, i32, i32, ctypes.POINTER(i64)],
             "rfx_prox_dense_ws": [vp, i64, i32, i32, ci, ci, vp, vp, vp, i64, vp],
+            "rfx_prox_dense_noalloc": [vp, i64, i32, i32, ci, ci, vp, vp, vp],
             "rfx_prox_oob_ws": [vp, vp, i64, i32, i32, ci, ci, vp, vp, vp, vp, i64, vp],
             "rfx_prox_dense_oob_ws": [vp, vp, i64, i32, i32, ci, ci, vp, vp, ci, vp, vp, vp, vp, i64, vp],
             "rfx_prox_sparse_ws": [vp, i64, i32, i32, i32, ci, i64, vp, vp, vp, vp, vp, vp, i64, vp],
@@ -639,3 +640,13 @@ def mds3d_ws(Q, scales, x0, iters: int, workspace, coords, eigvals, rel_change=N
                                _dev(x0, torch.float32, (N, m)), _dev(coords, torch.float32, (N, 3)),
                                _dev(eigvals, torch.float32, (3,)), _dev(rel_change, torch.float32, (1,)), wp, wb, _stream()))
 
+
+def prox_dense_noalloc(leaf, leaf_bound: int, count_dtype: int = U32, layout: int = FULL, counts=None, prox=None):
+    """rfx_prox_dense_noalloc: writes the given outputs (at least one) using the library's built-in scratch;
+    allocates nothing; asynchronous."""
+    import torch
+    B, N = leaf.shape
+    shp = _sym_shape(N, layout)
+    _check(load().rfx_prox_dense_noalloc(_dev(leaf, torch.int32), N, B, leaf_bound, count_dtype, layout,
+                                         _dev(counts, _count_dtype(count_dtype), shp), _dev(prox, torch.float32, shp),
+                                         _stream()))

@@ -804,6 +804,31 @@ int with_own_workspace(const char* who, int64_t N, int32_t B, int32_t leaf_bound
 
 // RFX_TILE_MODE (0..4), when defined, compiles the entry points of one mode only, so that the build can
 // compile the five sets of kernel instantiations side by side.
+#if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 0
+// Bit-plane scratch of rfx_prox_dense_noalloc: one array per GPU for the life of the process.
+constexpr size_t kStaticPlaneWords = (size_t)4 << 20;  // 16 MiB
+static __device__ __align__(256) uint32_t scratch[kStaticPlaneWords];
+
+namespace {
+// Device address of `scratch` on the current device (the host-side symbol is not an address a kernel can use).
+int static_planes(uint32_t** out) {
+    static std::mutex mu;
+    static uint32_t* addr[64] = {};
+    int dev = 0;
+    RFX_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_dense_noalloc: device %d", dev);
+    std::lock_guard<std::mutex> lk(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        RFX_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        addr[dev] = static_cast<uint32_t*>(p);
+    }
+    *out = addr[dev];
+    return RFX_OK;
+}
+}  // namespace
+#endif
+
 extern "C" {
 
 #if !defined(RFX_TILE_MODE) || RFX_TILE_MODE == 0
@@ -839,6 +864,22 @@ int rfx_prox_dense(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_boun
     return with_own_workspace("rfx_prox_dense", N, B, leaf_bound, rfx::as_stream(stream), [&](void* ws, int64_t bytes) {
         return rfx_prox_dense_ws(leaf, N, B, leaf_bound, count_dtype, layout, counts, prox, ws, bytes, stream);
     });
+}
+
+int rfx_prox_dense_noalloc(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int count_dtype, int layout,
+                           void* counts, float* prox, void* stream) {
+    int rc = check_dense(leaf, N, B, leaf_bound, count_dtype, layout, counts, prox);
+    if (rc != RFX_OK) return rc;
+    const ProxScratch need = prox_scratch(N, B, leaf_bound);
+    if (need.plane_bytes > sizeof(uint32_t) * kStaticPlaneWords)
+        return rfx::fail(RFX_ERR_CAPACITY,
+                         "rfx_prox_dense_noalloc: N=%lld, B=%d, leaf_bound=%d need %zu bytes of bit planes, the built-in "
+                         "scratch holds %zu (use rfx_prox_dense or rfx_prox_dense_ws)",
+                         (long long)N, B, leaf_bound, need.plane_bytes, sizeof(uint32_t) * kStaticPlaneWords);
+    uint32_t* planes = nullptr;
+    if ((rc = static_planes(&planes)) != RFX_OK) return rc;
+    TileOut out{counts, nullptr, prox, N, B, count_dtype == RFX_U16, layout == RFX_UPPER_PACKED, 0, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr};
+    return enqueue<kModePlain>(leaf, nullptr, N, B, leaf_bound, out, rfx::as_stream(stream), planes, TileOut{}, /*timing=*/false);
 }
 #endif
 
