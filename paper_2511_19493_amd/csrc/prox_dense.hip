@@ -32,7 +32,7 @@ namespace {
 #define RFX_R 4
 #endif
 #ifndef RFX_B_PREFETCH
-#define RFX_B_PREFETCH 0
+#define RFX_B_PREFETCH 1
 #endif
 constexpr int kR = RFX_R;       // a samples per lane
 constexpr int kATile = 64 * kR; // a samples per wave / workgroup
