@@ -12,6 +12,11 @@ struct rfx_pv_plan {
     uint32_t* d_big = nullptr;        // slots with more than kBigLeaf members, one list per group of trees
     float* d_S = nullptr;             // [B*Lb][k_cap]
     int32_t k_cap = 0;
+    // big slots summed in kRanges pieces by sample range (each XCD then gathers from its own eighth of V)
+    uint32_t* d_big_bounds = nullptr; // [as d_big][kRanges + 1] positions in perm where the sample ranges begin
+    float* d_part = nullptr;          // [part_cap][kRanges][k_cap] partial sums of the pieces
+    int64_t part_cap = 0;             // big slots d_part has room for
+    static constexpr int kRanges = 8;
     // scratch of the grouping, kept so that the plan can be rebuilt for new leaf ids without allocating
     uint32_t* d_count = nullptr;      // [B][Q][Lb] part histograms, then cursors
     int* d_flags = nullptr;           // bad id seen; big slots per group

@@ -39,7 +39,15 @@ constexpr int kGatherTile = 32;   // Y rows per wave in the gather
 // launches and the cross-stream events (N = 10,000, B = 500: 0.57 ms in one group, 0.67 ms in four).
 constexpr int kApplyChunks = rfx_pv_plan::kMaxChunks;
 constexpr int64_t kApplyChunkMinPairs = 10000000;   // B * N from which the groups pay
-constexpr int kBigLeaf = 256;     // slots with more members are summed by a whole workgroup
+#ifndef RFX_PV_BIG_LEAF
+#define RFX_PV_BIG_LEAF 256
+#endif
+constexpr int kBigLeaf = RFX_PV_BIG_LEAF;     // slots with more members are summed by a whole workgroup
+#ifndef RFX_PV_SPLIT
+#define RFX_PV_SPLIT 1
+#endif
+constexpr bool kSplitBigLeaves = RFX_PV_SPLIT != 0;
+constexpr int64_t kSplitMaxRangeBytes = 3584 * 1024;  // an eighth of V must fit a 4 MB second-level cache with room to spare
 constexpr int kBigWaves = 16;
 constexpr int kHistLdsLeaves = 16384;  // largest Lb whose histogram fits LDS (64 KB)
 
@@ -408,6 +416,81 @@ __global__ __launch_bounds__(64 * kBigWaves) void pv_leaf_sum_big_kernel(const u
     }
 }
 
+// The same sums in pieces.  The members of a slot are ascending sample indices, so the samples of range x (the x-th of
+// kRanges equal parts of 0..N-1) are one contiguous piece of the segment; bounds[idx][x] is where it begins.  Workgroup
+// 8 idx + x sums piece x of big slot idx: consecutive workgroup ids go to the 8 XCDs in turn, so the XCD that runs
+// pieces x only ever gathers rows from the x-th eighth of V, which stays in its second-level cache when that eighth
+// is smaller than the cache (the rows of a whole segment are spread over all of V and come from the last-level cache).
+// The pieces' sums go to `part` and are added in range order by pv_combine_kernel, so the result does not depend on timing.
+#ifndef RFX_PV_SPLIT_WAVES
+#define RFX_PV_SPLIT_WAVES 4
+#endif
+constexpr int kSplitWaves = RFX_PV_SPLIT_WAVES;
+
+__global__ __launch_bounds__(256) void pv_big_bounds_kernel(const uint32_t* __restrict__ big, int32_t n_big,
+                                                           const uint32_t* __restrict__ seg_start,
+                                                           const uint32_t* __restrict__ perm, int64_t N,
+                                                           uint32_t* __restrict__ bounds) {
+    constexpr int R = rfx_pv_plan::kRanges;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n_big * (R + 1)) return;
+    const int idx = t / (R + 1), x = t % (R + 1);
+    const uint32_t slot = big[idx];
+    uint32_t lo = seg_start[slot], hi = seg_start[slot + 1];
+    const uint32_t first = (uint32_t)(((int64_t)x * N + R - 1) / R);  // first sample of range x (x = R: N)
+    while (lo < hi) {  // first position whose sample is >= first
+        const uint32_t mid = lo + (hi - lo) / 2;
+        if (perm[mid] < first)
+            lo = mid + 1;
+        else
+            hi = mid;
+    }
+    bounds[(int64_t)idx * (R + 1) + x] = lo;
+}
+
+template <int KCH, int RPW>
+__global__ __launch_bounds__(64 * kSplitWaves) void pv_leaf_sum_split_kernel(const uint32_t* __restrict__ bounds,
+                                                                            const uint32_t* __restrict__ perm,
+                                                                            const float* __restrict__ V, int32_t k,
+                                                                            float* __restrict__ part) {
+    constexpr int R = rfx_pv_plan::kRanges;
+    __shared__ float sm[kSplitWaves][KCH * 64];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t idx = blockIdx.x / R;
+    const int x = blockIdx.x % R;
+    const uint32_t lo = bounds[idx * (R + 1) + x], hi = bounds[idx * (R + 1) + x + 1];
+    const uint32_t share = ((hi - lo + kSplitWaves - 1) / kSplitWaves + kSumBatch * RPW - 1) / (kSumBatch * RPW) * (kSumBatch * RPW);
+    const uint32_t wlo = min(hi, lo + w * share), whi = min(hi, wlo + share);
+    float acc[KCH];
+    sum_members<KCH, RPW>(perm, wlo, whi, V, k, lane, acc);
+    if (lane < 64 / RPW) {
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) sm[w][lane + 64 * c] = acc[c];
+    }
+    __syncthreads();
+    for (int cc = threadIdx.x; cc < k; cc += 64 * kSplitWaves) {
+        float tot = sm[0][cc];
+#pragma unroll
+        for (int u = 1; u < kSplitWaves; ++u) tot += sm[u][cc];
+        part[((int64_t)blockIdx.x) * k + cc] = tot;
+    }
+}
+
+// S[big[idx]] = sum over the ranges, in range order, of the pieces' sums
+__global__ __launch_bounds__(256) void pv_combine_kernel(const uint32_t* __restrict__ big, int32_t n_big,
+                                                        const float* __restrict__ part, int32_t k, float* __restrict__ S) {
+    constexpr int R = rfx_pv_plan::kRanges;
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (int64_t)n_big * k) return;
+    const int64_t idx = e / k;
+    const int cc = (int)(e % k);
+    float tot = part[(idx * R) * k + cc];
+#pragma unroll
+    for (int x = 1; x < R; ++x) tot += part[(idx * R + x) * k + cc];
+    S[(int64_t)big[idx] * k + cc] = tot;
+}
+
 // Gather.  A wave owns kGatherTile consecutive samples and sweeps the trees b_begin .. b_end - 1 in order, two
 // trees per step; all row loads of a step are issued before any is consumed.  The sums start from zero for the
 // first group of trees (kFirst) and from the values the previous group left in Y otherwise (the same additions in the same
@@ -501,6 +584,12 @@ int launch_apply(const rfx_pv_plan* p, const float* V, int32_t k, float* Y, hipS
     // with one group the two kernel brackets below add up to the application; no third pair of events then
     std::optional<rfx::TimedLaunch> whole;
     if (p->n_chunks > 1) whole.emplace("pv_apply", st);
+    // Big slots in pieces by sample range when an eighth of V fits the second-level cache of an XCD with room to spare and
+    // the pieces' buffer holds them all (every group of trees has its own part of that buffer)
+    int64_t n_big_all = 0, part_off = 0;
+    for (int c = 0; c < p->n_chunks; ++c) n_big_all += p->big_cnt[c];
+    const bool split = kSplitBigLeaves && p->d_part && n_big_all <= p->part_cap &&
+                       (int64_t)p->N * k * 4 / rfx_pv_plan::kRanges <= kSplitMaxRangeBytes;
     for (int c = 0; c < p->n_chunks; ++c) {
         const int b0 = p->tree_off[c], b1 = p->tree_off[c + 1];
         const int64_t slot_begin = (int64_t)b0 * p->Lb, slot_end = (int64_t)b1 * p->Lb;
@@ -510,9 +599,18 @@ int launch_apply(const rfx_pv_plan* p, const float* V, int32_t k, float* Y, hipS
             hipLaunchKernelGGL((pv_leaf_sum_kernel<KCH, RPW>),
                                dim3((unsigned)rfx::ceil_div(slot_end - slot_begin, 4 * kSlotsPerWave)), dim3(256), 0, st,
                                p->d_seg_start, p->d_perm, slot_begin, slot_end, (uint32_t)((int64_t)p->B * p->N), V, k, p->d_S);
-            if (n_big > 0)
+            if (n_big > 0 && split) {
+                float* part = p->d_part + part_off * rfx_pv_plan::kRanges * k;
+                hipLaunchKernelGGL((pv_leaf_sum_split_kernel<KCH, RPW>), dim3((unsigned)n_big * rfx_pv_plan::kRanges),
+                                   dim3(64 * kSplitWaves), 0, st, p->d_big_bounds + p->big_base[c] * (rfx_pv_plan::kRanges + 1),
+                                   p->d_perm, V, k, part);
+                hipLaunchKernelGGL(pv_combine_kernel, dim3((unsigned)rfx::ceil_div((int64_t)n_big * k, 256)), dim3(256), 0, st,
+                                   p->d_big + p->big_base[c], n_big, part, k, p->d_S);
+                part_off += n_big;
+            } else if (n_big > 0) {
                 hipLaunchKernelGGL((pv_leaf_sum_big_kernel<KCH, RPW>), dim3((unsigned)n_big), dim3(64 * kBigWaves), 0, st,
                                    p->d_big + p->big_base[c], p->d_seg_start, p->d_perm, V, k, p->d_S);
+            }
         }
         RFX_LAUNCH_CHECK("pv_leaf_sum_kernel");
         // one group of trees: everything stays on the caller's stream
@@ -549,6 +647,8 @@ int rfx_pv_plan_destroy(rfx_pv_plan* p) {
     if (p->d_perm) (void)hipFree(p->d_perm);
     if (p->d_seg_start) (void)hipFree(p->d_seg_start);
     if (p->d_big) (void)hipFree(p->d_big);
+    if (p->d_big_bounds) (void)hipFree(p->d_big_bounds);
+    if (p->d_part) (void)hipFree(p->d_part);
     if (p->d_S) (void)hipFree(p->d_S);
     if (p->d_count) (void)hipFree(p->d_count);
     if (p->d_flags) (void)hipFree(p->d_flags);
@@ -606,6 +706,14 @@ int build_plan(rfx_pv_plan* p, const uint32_t* leaf, hipStream_t st) {
     if (e != hipSuccess) return rfx::fail(RFX_ERR_HIP, "rfx_pv_plan: %s", hipGetErrorString(e));
     if (h_flags[0]) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_pv_plan: a leaf id is >= leaf_bound=%d", Lb);
     for (int c = 0; c < p->n_chunks; ++c) p->big_cnt[c] = h_flags[1 + c];
+    for (int c = 0; c < p->n_chunks; ++c) {
+        if (p->big_cnt[c] == 0) continue;
+        const int threads = p->big_cnt[c] * (rfx_pv_plan::kRanges + 1);
+        hipLaunchKernelGGL(pv_big_bounds_kernel, dim3((unsigned)rfx::ceil_div(threads, 256)), dim3(256), 0, st,
+                           p->d_big + p->big_base[c], p->big_cnt[c], p->d_seg_start, p->d_perm, N,
+                           p->d_big_bounds + p->big_base[c] * (rfx_pv_plan::kRanges + 1));
+    }
+    RFX_LAUNCH_CHECK("pv_big_bounds_kernel");
     p->built = true;
     return RFX_OK;
 }
@@ -644,6 +752,7 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_perm, sizeof(uint32_t) * (size_t)B * (size_t)N);
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_seg_start, sizeof(uint32_t) * (size_t)(n_slots + 1));
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_big, sizeof(uint32_t) * (size_t)max_big);
+    if (e == hipSuccess) e = hipMalloc((void**)&p->d_big_bounds, sizeof(uint32_t) * (size_t)max_big * (rfx_pv_plan::kRanges + 1));
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_count, sizeof(uint32_t) * (size_t)n_slots * Q);
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_flags, kPlanFlags * sizeof(int));
     const size_t hist16_lds = sizeof(uint32_t) * (size_t)((Lb + 1) / 2);
@@ -685,6 +794,14 @@ int rfx_pv_plan_reserve(rfx_pv_plan* p, int32_t k) {
     p->d_S = nullptr;
     p->k_cap = 0;
     RFX_HIP(hipMalloc((void**)&p->d_S, sizeof(float) * (size_t)p->B * (size_t)p->Lb * (size_t)k));
+    // room for the pieces of a quarter more big slots than the current grouping has (a regrouped plan with more than that
+    // sums its big slots whole)
+    if (p->d_part) (void)hipFree(p->d_part);
+    p->d_part = nullptr;
+    int64_t n_big_all = 0;
+    for (int c = 0; c < p->n_chunks; ++c) n_big_all += p->big_cnt[c];
+    p->part_cap = n_big_all + n_big_all / 4 + 64;
+    RFX_HIP(hipMalloc((void**)&p->d_part, sizeof(float) * (size_t)p->part_cap * rfx_pv_plan::kRanges * (size_t)k));
     p->k_cap = k;
     return RFX_OK;
 }
