@@ -21,10 +21,15 @@
 
 namespace {
 
-constexpr int kChunk = 32768;            // columns per pass: 64 KB of LDS counters
+#ifndef RFX_ROWS_CHUNK
+#define RFX_ROWS_CHUNK 32768
+#endif
+constexpr int kChunk = RFX_ROWS_CHUNK;   // columns per pass: 16-bit LDS counters, two per word
 constexpr int kRowThreads = 1024;        // 16 waves
 constexpr int kRowWaves = kRowThreads / 64;
 constexpr int kTreesPerWave = 4;         // member loads a wave keeps in flight
+constexpr int kGroupTrees = 8;           // quarter-wave load instructions (four trees each) a wave keeps in flight
+constexpr int kGroupLoads = 2;           // 16-member loads of a tree and chunk by a quarter wave before the wave-wide loads
 constexpr int kNarrowLoads = 2;          // 64-member loads of a tree and chunk before the segment counts as long
 constexpr uint32_t kDone = 0xffffffffu;  // cursor of a tree whose segment is used up
 constexpr uint32_t kEndFlag = 0x80000000u;
@@ -108,16 +113,19 @@ struct RowOut {
     int32_t u16;
 };
 
-__global__ __launch_bounds__(kRowThreads, 8) void sparse_rows_kernel(const uint32_t* __restrict__ permx,
+__global__ __launch_bounds__(kRowThreads, kChunk > 32768 ? 4 : 8) void sparse_rows_kernel(const uint32_t* __restrict__ permx,
                                                                     const uint32_t* __restrict__ start, int64_t N, int32_t B,
                                                                     RowOut out) {
     extern __shared__ uint32_t lds[];
     uint32_t* cnt = lds;                       // [kChunk / 2] two 16-bit counters per word
     uint32_t* cur = lds + kChunk / 2;          // [B] position in permx of the next member of the row's leaf, per tree
-    uint32_t* act = cur + B;                   // [16][ceil(B / 16)] per wave: its trees that are not finished
+    uint32_t* act = cur + B;                   // [2][16][ceil(B / 16)] per wave: its trees that are not finished, and the long ones
     __shared__ uint32_t wave_tot[kRowWaves];
     __shared__ unsigned long long base_sh;
-    const int64_t i = blockIdx.x;
+    // Rows are taken in the order of tree 0's grouping (the first N entries of the member list): samples that share a leaf
+    // there share leaves in many other trees, so workgroups that run at the same time read the same segments and find them
+    // in the caches.
+    const int64_t i = permx[blockIdx.x] & ~kEndFlag;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t last_pos = (uint32_t)((int64_t)B * N - 1);
@@ -129,6 +137,7 @@ __global__ __launch_bounds__(kRowThreads, 8) void sparse_rows_kernel(const uint3
     // members ahead; most trees put the row's sample in a small leaf and drop out after the first chunk.
     const int cap = (B + kRowWaves - 1) / kRowWaves;
     uint32_t* mine_act = act + wave * cap;
+    uint32_t* mine_long = act + (kRowWaves + wave) * cap;  // its trees with many members left in the current chunk
     const uint64_t lt_mask = (1ull << lane) - 1ull;
     int n_act = 0;
     auto compact_list = [&](bool first) {
@@ -155,13 +164,69 @@ __global__ __launch_bounds__(kRowThreads, 8) void sparse_rows_kernel(const uint3
         // loads of a tree bring 64 members each (most segments have fewer inside a chunk, and wider loads would mostly
         // fetch members of later chunks); a segment that fills kNarrowLoads of them is long, and from then on one load
         // brings 256 consecutive members (four per lane) and the next 256 are requested before the current ones are counted.
-        for (int t0 = 0; t0 < n_act; t0 += kTreesPerWave) {
+        //
+        // Before that, every tree gets kGroupLoads loads of 16 members by a quarter of the wave (four trees per load
+        // instruction, sixteen per round): in a deep forest a tree has some twenty members of a row's leaf inside a chunk,
+        // and a 64-member load would fetch three times what it counts.  Only trees that fill those loads go on to the
+        // wave-wide loads below.
+        int n_long = 0;
+        {
+            const int g = lane >> 4, l = lane & 15;
+            for (int t0 = 0; t0 < n_act; t0 += 4 * kGroupTrees) {
+                // kGroupTrees load instructions (four trees each) in flight; tree and cursor are read again from LDS
+                // when a load is consumed, which is cheaper than holding them in registers
+                uint32_t v[kGroupTrees];
+#pragma unroll
+                for (int q = 0; q < kGroupTrees; ++q) {
+                    const int t = t0 + 4 * q + g;
+                    const uint32_t p0 = t < n_act ? cur[mine_act[t]] : kDone;
+                    v[q] = permx[p0 == kDone ? 0u : min(p0 + (uint32_t)l, last_pos)];
+                }
+#pragma unroll
+                for (int q = 0; q < kGroupTrees; ++q) {
+                    const int t = t0 + 4 * q + g;
+                    const uint32_t tree = t < n_act ? mine_act[t] : 0u;
+                    const uint32_t p0 = t < n_act ? cur[tree] : kDone;
+                    bool active = p0 != kDone, is_long = false;
+                    uint32_t p = p0, val = v[q];
+                    for (int step = 0; step < kGroupLoads; ++step) {
+                        if (!__ballot(active)) break;  // wave-uniform
+                        const uint32_t j = val & ~kEndFlag;
+                        const uint64_t ends = __ballot(active && (val & kEndFlag));
+                        const uint32_t e16 = (uint32_t)(ends >> (16 * g)) & 0xffffu;
+                        const int end_l = e16 ? __ffs((int)e16) - 1 : 16;
+                        const bool take = active && l <= end_l && j < limit;
+                        if (take) atomicAdd(&cnt[(j - col0) >> 1], 1u << (16 * (j & 1u)));
+                        const int n_take = __popc((uint32_t)(__ballot(take) >> (16 * g)) & 0xffffu);
+                        if (active) {
+                            if (n_take == end_l + 1) {  // the whole rest of the segment lay in this chunk
+                                p = kDone;
+                                active = false;
+                            } else {
+                                p += (uint32_t)n_take;
+                                if (n_take < 16) active = false;  // stopped at the chunk's limit
+                            }
+                        }
+                        if (step + 1 < kGroupLoads) {
+                            if (active) val = permx[min(p + (uint32_t)l, last_pos)];
+                        } else if (active) {
+                            is_long = true;
+                        }
+                    }
+                    if (p0 != kDone && l == 0) cur[tree] = p;
+                    const uint64_t lm = __ballot(is_long && l == 0);
+                    if (is_long && l == 0) mine_long[n_long + __popcll(lm & lt_mask)] = tree;
+                    n_long += __popcll(lm);
+                }
+            }
+        }
+        for (int t0 = 0; t0 < n_long; t0 += kTreesPerWave) {
             uint32_t tree[kTreesPerWave], pos[kTreesPerWave], v[kTreesPerWave];
 #pragma unroll
             for (int q = 0; q < kTreesPerWave; ++q) {
                 // the same for all lanes; entries past the list's end repeat its last tree and are skipped below
-                tree[q] = (uint32_t)__builtin_amdgcn_readfirstlane((int)mine_act[min(t0 + q, n_act - 1)]);
-                pos[q] = t0 + q < n_act ? (uint32_t)__builtin_amdgcn_readfirstlane((int)cur[tree[q]]) : kDone;
+                tree[q] = (uint32_t)__builtin_amdgcn_readfirstlane((int)mine_long[min(t0 + q, n_long - 1)]);
+                pos[q] = t0 + q < n_long ? (uint32_t)__builtin_amdgcn_readfirstlane((int)cur[tree[q]]) : kDone;
             }
 #pragma unroll
             for (int q = 0; q < kTreesPerWave; ++q) {
@@ -256,28 +321,60 @@ __global__ __launch_bounds__(kRowThreads, 8) void sparse_rows_kernel(const uint3
         }
         if (total) {  // uniform over the workgroup
             if (threadIdx.x == 0) base_sh = atomicAdd(out.cursor, (unsigned long long)total);
+            // The kept pairs are first packed into the counter array itself (every thread holds its words in registers
+            // by now, and entry e of the chunk goes to word e: column offset in the upper, count in the lower half), so
+            // that the list leaves as contiguous runs, one entry per thread and store, instead of every thread writing
+            // a short run of its own.
             __syncthreads();
             const unsigned long long base = base_sh;
-            if (base + total <= out.capacity) {
-                unsigned long long e = base + before + incl - mine;
+            if (base + total > out.capacity) {
+                // counted, not stored
+            } else if (total > (uint32_t)(kChunk / 2)) {
+                // more kept pairs than the counter array has words (a row that shares leaves with most of the chunk):
+                // every thread writes its own run
+                unsigned long long at = base + before + incl - mine;
 #pragma unroll
                 for (int u = 0; u < kWordsPerThread; ++u) {
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const uint32_t c16 = h ? w[u] >> 16 : w[u] & 0xffffu;
                         if (c16 >= out.min_count) {
-                            out.rows[e] = (uint32_t)i;
-                            out.cols[e] = col0 + 2u * (uint32_t)(u * kRowThreads + threadIdx.x) + (uint32_t)h;
+                            out.rows[at] = (uint32_t)i;
+                            out.cols[at] = col0 + 2u * (uint32_t)(u * kRowThreads + threadIdx.x) + (uint32_t)h;
                             if (out.counts) {
                                 if (out.u16)
-                                    static_cast<uint16_t*>(out.counts)[e] = (uint16_t)c16;
+                                    static_cast<uint16_t*>(out.counts)[at] = (uint16_t)c16;
                                 else
-                                    static_cast<uint32_t*>(out.counts)[e] = c16;
+                                    static_cast<uint32_t*>(out.counts)[at] = c16;
                             }
-                            if (out.prox) out.prox[e] = (float)c16 / Bf;
-                            ++e;
+                            if (out.prox) out.prox[at] = (float)c16 / Bf;
+                            ++at;
                         }
                     }
+                }
+            } else {
+                uint32_t e = before + incl - mine;
+#pragma unroll
+                for (int u = 0; u < kWordsPerThread; ++u) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t c16 = h ? w[u] >> 16 : w[u] & 0xffffu;
+                        if (c16 >= out.min_count) cnt[e++] = ((2u * (uint32_t)(u * kRowThreads + threadIdx.x) + (uint32_t)h) << 16) | c16;
+                    }
+                }
+                __syncthreads();
+                for (uint32_t t = threadIdx.x; t < total; t += kRowThreads) {
+                    const uint32_t x = cnt[t], c16 = x & 0xffffu;
+                    const unsigned long long at = base + t;
+                    out.rows[at] = (uint32_t)i;
+                    out.cols[at] = col0 + (x >> 16);
+                    if (out.counts) {
+                        if (out.u16)
+                            static_cast<uint16_t*>(out.counts)[at] = (uint16_t)c16;
+                        else
+                            static_cast<uint32_t*>(out.counts)[at] = c16;
+                    }
+                    if (out.prox) out.prox[at] = (float)c16 / Bf;
                 }
             }
         }
@@ -351,7 +448,7 @@ int sparse_rows_enqueue(rfx_pv_plan* plan, uint32_t* start, int32_t min_count, i
                        plan->d_seg_start, N, B, start);
     RFX_LAUNCH_CHECK("row_starts_kernel");
     RowOut out{rows, cols, counts, prox, cursor, (unsigned long long)capacity, (uint32_t)min_count, u16};
-    const size_t lds = sizeof(uint32_t) * ((size_t)kChunk / 2 + (size_t)B + (size_t)kRowWaves * ((B + kRowWaves - 1) / kRowWaves));
+    const size_t lds = sizeof(uint32_t) * ((size_t)kChunk / 2 + (size_t)B + 2 * (size_t)kRowWaves * ((B + kRowWaves - 1) / kRowWaves));
     RFX_HIP(hipFuncSetAttribute((const void*)sparse_rows_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     TimedLaunch timed("sparse_rows_kernel", st);
     hipLaunchKernelGGL(sparse_rows_kernel, dim3((unsigned)N), dim3(kRowThreads), lds, st, plan->d_perm, start, N, B, out);

@@ -45,6 +45,8 @@ def _compare(torch, rfx, oracle, leaf, bound, min_count, dtype):
 
 @pytest.mark.parametrize("N,B,bound", [(1, 3, 5), (2, 1, 2), (255, 31, 40), (256, 32, 40), (257, 33, 40), (515, 65, 2),
                                        (300, 97, 1), (1100, 40, 3000), (70000, 5, 9000), (32769, 3, 600), (65536, 2, 40000)])
+# (a dense case with N > 32768, where a chunk of the row pass keeps more pairs than it has counter words, is
+# test_row_pass_on_a_nearly_dense_matrix below: the oracle's list would be too long there)
 def test_sparse_on_boundary_shapes(torch_cuda, N, B, bound):
     import oracle
     import paper_2511_19493_amd as rfx
@@ -122,3 +124,36 @@ def test_row_pass_rejects_what_it_cannot_hold(torch_cuda):
     assert lib.rfx_prox_sparse_rows(fake, 100, 50, 8, 0, rfx.U32, 0, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_INVALID_ARG
     assert lib.rfx_prox_sparse_rows(fake, 100, 50, 8, 1, rfx.U32, 4, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_NULL
     assert lib.rfx_prox_sparse_rows(None, 100, 50, 8, 1, rfx.U32, 0, None, None, None, None, ctypes.byref(nnz), None) == rfx.ERR_NULL
+
+
+def test_row_pass_on_a_nearly_dense_matrix(torch_cuda):
+    """Two leaves per tree: three quarters of all pairs are non-zero, so a 32,768-column chunk of the row pass keeps more
+    pairs than its counter array has words and every thread writes its own run.  The list is too long for the oracle's
+    triplet form (3e8 entries), so it is checked through what fixes it: the pair count and the sum of the counts from the
+    leaf sizes (sum over trees and leaves of s (s - 1) / 2), i < j, every count in range, no pair twice (the tile pass,
+    itself checked against the oracle on every other case, gives the same number of pairs), and sampled rows against
+    the oracle's dense rows."""
+    import oracle
+    import paper_2511_19493_amd as rfx
+    torch = torch_cuda
+    N, B, bound = 33000, 3, 2
+    rng = np.random.default_rng(99)
+    leaf = rng.integers(0, bound, size=(B, N)).astype(np.uint32)
+    d = _dev(torch, leaf)
+    rows, cols, counts, _ = rfx.prox_sparse(d, bound, 1, method="rows")
+    n = rows.numel()
+    assert n == rfx.prox_sparse_count(d, bound, 1)                      # tile pass ("auto" picks it here: few visits saved)
+    expect = sum(int((np.bincount(leaf[b]).astype(np.int64) * (np.bincount(leaf[b]).astype(np.int64) - 1) // 2).sum()) for b in range(B))
+    assert int(counts.sum(dtype=torch.int64)) == expect
+    assert bool((rows < cols).all()) and int(cols.max()) < N and int(counts.min()) >= 1 and int(counts.max()) <= B
+    key = rows.long() * N + cols.long()
+    assert int(torch.unique(key).numel()) == n
+    for i in (0, 1, 12345, 32767, 32768, N - 2):
+        ref = oracle.counts_rows(leaf, i, i + 1)[0]
+        m = rows == i
+        j = cols[m].cpu().numpy().astype(np.int64)
+        v = counts[m].cpu().numpy().view(np.uint32)
+        order = np.argsort(j)
+        want = np.nonzero(ref[i + 1:] >= 1)[0] + i + 1
+        np.testing.assert_array_equal(j[order], want)
+        np.testing.assert_array_equal(v[order], ref[want])
