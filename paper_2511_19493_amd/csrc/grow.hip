@@ -661,6 +661,25 @@ struct Scratch {
     }
 };
 
+// lists of the segmented sort: medium segment ids, begin / end of the long segments, two counters
+struct SortLists {
+    rfx::DevBuf buf;
+    size_t cap = 0;
+    hipError_t reserve(size_t n_seg, hipStream_t st) {
+        if (n_seg <= cap) return hipSuccess;
+        hipError_t e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return e;
+        cap = n_seg + n_seg / 4 + 64;
+        e = buf.alloc(sizeof(uint32_t) * (3 * cap + 64));
+        if (e != hipSuccess) cap = 0;
+        return e;
+    }
+};
+
+__global__ void zero_counts_kernel(uint32_t* counts) {
+    if (threadIdx.x < 2) counts[threadIdx.x] = 0;
+}
+
 int scan_u32(Scratch& tmp, const uint32_t* in, uint32_t* out, uint32_t n, hipStream_t st) {
     size_t need = 0;
     RFX_HIP(rocprim::exclusive_scan(nullptr, need, in, out, 0u, (size_t)n, rocprim::plus<uint32_t>(), st));
@@ -669,14 +688,203 @@ int scan_u32(Scratch& tmp, const uint32_t* in, uint32_t* out, uint32_t n, hipStr
     return RFX_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Segmented sort of the (key, row) pairs.  After the first few levels almost every segment is short (the nodes of a
+// level are many and small).  All sizes up to kSortBlockMax go through bitonic networks on the 64-bit value
+// key << 32 | row (the rows of a segment are distinct and arrive ascending, so this is the order a stable sort by key
+// gives): up to 16 pairs in a quarter wave, up to 64 in a wave, up to kSortBlockMax in a workgroup that keeps up to 16
+// pairs per thread in registers and exchanges through LDS only at distances of a wave or more.  Only the few long
+// segments of the top levels are left to the library's radix sort.
+constexpr int kSortBlockMax = 4096;
+
+__device__ __forceinline__ u64 shfl_xor_u64(u64 x, int m) {
+    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)x, m), hi = (uint32_t)__shfl_xor((int)(uint32_t)(x >> 32), m);
+    return ((u64)hi << 32) | lo;
+}
+
+// compare-exchange with the lane at distance j; this lane keeps the smaller value if keep_min
+__device__ __forceinline__ u64 exchange_step(u64 x, int j, bool keep_min) {
+    const u64 other = shfl_xor_u64(x, j);
+    return (x < other) == keep_min ? x : other;
+}
+
+// Four segments per wave, one per quarter.  A quarter sorts a segment of up to 16 pairs by itself; segments of 17 .. 64
+// pairs are then taken one after the other by the whole wave; longer ones are appended to the list of medium segments
+// or to the begin / end arrays of the long ones.  counts[0] = medium, counts[1] = long segments.
+__global__ __launch_bounds__(256) void sort_short_segments_kernel(uint32_t n_seg, const uint32_t* __restrict__ seg_begin,
+                                                                 const uint32_t* __restrict__ seg_end,
+                                                                 const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
+                                                                 uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out,
+                                                                 uint32_t* __restrict__ medium, uint32_t* __restrict__ long_begin,
+                                                                 uint32_t* __restrict__ long_end, uint32_t* __restrict__ counts) {
+    const int lane = threadIdx.x & 63, gl = lane & 15;
+    const uint32_t seg = ((blockIdx.x * 4 + (threadIdx.x >> 6)) << 2) + (lane >> 4);
+    const bool valid = seg < n_seg;
+    const uint32_t b = valid ? seg_begin[seg] : 0u, len = valid ? seg_end[seg] - b : 0u;
+    {
+        const bool mine = (uint32_t)gl < len && len <= 16;
+        u64 x = ~0ull;
+        if (mine) x = ((u64)keys_in[b + gl] << 32) | vals_in[b + gl];
+#pragma unroll
+        for (int k = 2; k <= 16; k <<= 1) {
+#pragma unroll
+            for (int j = k >> 1; j > 0; j >>= 1) x = exchange_step(x, j, ((gl & j) == 0) == ((gl & k) == 0));
+        }
+        if (mine) {
+            keys_out[b + gl] = (uint32_t)(x >> 32);
+            vals_out[b + gl] = (uint32_t)x;
+        }
+    }
+    if (gl == 0 && len > 64) {
+        if (len <= (uint32_t)kSortBlockMax) {
+            medium[atomicAdd(&counts[0], 1u)] = seg;
+        } else {
+            const uint32_t at = atomicAdd(&counts[1], 1u);
+            long_begin[at] = b;
+            long_end[at] = b + len;
+        }
+    }
+    u64 todo = __ballot(gl == 0 && len > 16 && len <= 64);
+    while (todo) {
+        const int src = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        const uint32_t wb = (uint32_t)__shfl((int)b, src), wl = (uint32_t)__shfl((int)len, src);
+        u64 x = ~0ull;
+        if ((uint32_t)lane < wl) x = ((u64)keys_in[wb + lane] << 32) | vals_in[wb + lane];
+#pragma unroll
+        for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+            for (int j = k >> 1; j > 0; j >>= 1) x = exchange_step(x, j, ((lane & j) == 0) == ((lane & k) == 0));
+        }
+        if ((uint32_t)lane < wl) {
+            keys_out[wb + lane] = (uint32_t)(x >> 32);
+            vals_out[wb + lane] = (uint32_t)x;
+        }
+    }
+}
+
+// Bitonic sort of 256 E values over one workgroup: thread t holds the values at positions t E .. t E + E - 1.  Steps at
+// distances below E stay in the thread's registers, distances below 64 E are lane exchanges, the rest goes through LDS
+// (laid out [r][t], so consecutive lanes touch consecutive words).
+template <int E>
+__device__ __forceinline__ void sort_block(u64 (&x)[E], u64* sm, int t) {
+#pragma unroll
+    for (int k = 2; k < E; k <<= 1) {  // direction fixed by the position inside the thread
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+#pragma unroll
+            for (int r = 0; r < E; ++r) {
+                if ((r & j) == 0) {
+                    const u64 a = x[r], c = x[r | j];
+                    const bool sw = (a > c) == ((r & k) == 0);
+                    x[r] = sw ? c : a;
+                    x[r | j] = sw ? a : c;
+                }
+            }
+        }
+    }
+    for (int k = (E > 1 ? E : 2); k <= 256 * E; k <<= 1) {
+        const bool asc = ((t * E) & k) == 0;
+        for (int j = k >> 1; j >= E; j >>= 1) {
+            const int d = j / E;
+            const bool keep_min = ((t & d) == 0) == asc;
+            if (d < 64) {
+#pragma unroll
+                for (int r = 0; r < E; ++r) x[r] = exchange_step(x[r], d, keep_min);
+            } else {
+#pragma unroll
+                for (int r = 0; r < E; ++r) sm[r * 256 + t] = x[r];
+                __syncthreads();
+#pragma unroll
+                for (int r = 0; r < E; ++r) {
+                    const u64 other = sm[r * 256 + (t ^ d)];
+                    x[r] = (x[r] < other) == keep_min ? x[r] : other;
+                }
+                __syncthreads();
+            }
+        }
+#pragma unroll
+        for (int j = E >> 1; j > 0; j >>= 1) {
+#pragma unroll
+            for (int r = 0; r < E; ++r) {
+                if ((r & j) == 0) {
+                    const u64 a = x[r], c = x[r | j];
+                    const bool sw = (a > c) == asc;
+                    x[r] = sw ? c : a;
+                    x[r | j] = sw ? a : c;
+                }
+            }
+        }
+    }
+}
+
+template <int E>
+__device__ __forceinline__ void sort_medium_segment(uint32_t b, uint32_t len, const uint32_t* __restrict__ keys_in,
+                                                    const uint32_t* __restrict__ vals_in, uint32_t* __restrict__ keys_out,
+                                                    uint32_t* __restrict__ vals_out, u64* sm) {
+    const int t = threadIdx.x;
+    u64 x[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) {  // where a value starts does not matter: read coalesced
+        const uint32_t i = (uint32_t)(r * 256 + t);
+        x[r] = i < len ? ((u64)keys_in[b + i] << 32) | vals_in[b + i] : ~0ull;
+    }
+    sort_block<E>(x, sm, t);
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        const uint32_t i = (uint32_t)(t * E + r);
+        if (i < len) {
+            keys_out[b + i] = (uint32_t)(x[r] >> 32);
+            vals_out[b + i] = (uint32_t)x[r];
+        }
+    }
+}
+
+// One workgroup per listed segment of 65 .. kSortBlockMax pairs.
+__global__ __launch_bounds__(256) void sort_medium_segments_kernel(const uint32_t* __restrict__ medium,
+                                                                  const uint32_t* __restrict__ seg_begin,
+                                                                  const uint32_t* __restrict__ seg_end,
+                                                                  const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
+                                                                  uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out) {
+    __shared__ u64 sm[kSortBlockMax];
+    const uint32_t seg = medium[blockIdx.x];
+    const uint32_t b = seg_begin[seg], len = seg_end[seg] - b;
+    if (len <= 256) sort_medium_segment<1>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
+    else if (len <= 512) sort_medium_segment<2>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
+    else if (len <= 1024) sort_medium_segment<4>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
+    else if (len <= 2048) sort_medium_segment<8>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
+    else sort_medium_segment<16>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
+}
+
 int sort_segments(Scratch& tmp, const uint32_t* keys_in, uint32_t* keys_out, const uint32_t* vals_in, uint32_t* vals_out,
-                  uint32_t size, uint32_t n_seg, const uint32_t* seg_begin, const uint32_t* seg_end, hipStream_t st) {
-    size_t need = 0;
-    RFX_HIP(rocprim::segmented_radix_sort_pairs(nullptr, need, keys_in, keys_out, vals_in, vals_out, size, n_seg, seg_begin,
-                                                seg_end, 0, 32, st));
-    RFX_HIP(tmp.reserve(need, st));
-    RFX_HIP(rocprim::segmented_radix_sort_pairs(tmp.buf.p, need, keys_in, keys_out, vals_in, vals_out, size, n_seg, seg_begin,
-                                                seg_end, 0, 32, st));
+                  uint32_t size, uint32_t n_seg, const uint32_t* seg_begin, const uint32_t* seg_end, SortLists& lists,
+                  hipStream_t st) {
+    if (n_seg == 0) return RFX_OK;
+    RFX_HIP(lists.reserve(n_seg, st));
+    uint32_t* medium = lists.buf.as<uint32_t>();
+    uint32_t* long_begin = medium + lists.cap;
+    uint32_t* long_end = long_begin + lists.cap;
+    uint32_t* counts = long_end + lists.cap;
+    hipLaunchKernelGGL(zero_counts_kernel, dim3(1), dim3(64), 0, st, counts);
+    hipLaunchKernelGGL(sort_short_segments_kernel, dim3((n_seg + 15) / 16), dim3(256), 0, st, n_seg, seg_begin, seg_end, keys_in, vals_in,
+                       keys_out, vals_out, medium, long_begin, long_end, counts);
+    RFX_LAUNCH_CHECK("sort_short_segments_kernel");
+    uint32_t h[2] = {0, 0};
+    RFX_HIP(hipMemcpyAsync(h, counts, sizeof(h), hipMemcpyDeviceToHost, st));
+    RFX_HIP(hipStreamSynchronize(st));
+    if (h[0] > 0) {
+        hipLaunchKernelGGL(sort_medium_segments_kernel, dim3(h[0]), dim3(256), 0, st, medium, seg_begin, seg_end, keys_in, vals_in,
+                           keys_out, vals_out);
+        RFX_LAUNCH_CHECK("sort_medium_segments_kernel");
+    }
+    if (h[1] > 0) {
+        size_t need = 0;
+        RFX_HIP(rocprim::segmented_radix_sort_pairs(nullptr, need, keys_in, keys_out, vals_in, vals_out, size, h[1], long_begin,
+                                                    long_end, 0, 32, st));
+        RFX_HIP(tmp.reserve(need, st));
+        RFX_HIP(rocprim::segmented_radix_sort_pairs(tmp.buf.p, need, keys_in, keys_out, vals_in, vals_out, size, h[1], long_begin,
+                                                    long_end, 0, 32, st));
+    }
     return RFX_OK;
 }
 
@@ -710,6 +918,7 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
     const int64_t TN = (int64_t)Tb * N;
     rfx::DevBuf cnt32, inbag, ib_flag, ib_pos, root_tot, root_active, next_id, counters;
     Scratch tmp;
+    SortLists sort_lists;
     RFX_HIP(alloc_n<uint32_t>(cnt32, TN));
     RFX_HIP(alloc_n<uint16_t>(inbag, TN));
     RFX_HIP(alloc_n<uint32_t>(ib_flag, TN + 1));
@@ -830,7 +1039,7 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
                            seg_feat.as<int32_t>(), seg_begin.as<uint32_t>(), keys[0].as<uint32_t>(), vals[0].as<uint32_t>());
         RFX_LAUNCH_CHECK("segment kernels");
         int rc = sort_segments(tmp, keys[0].as<uint32_t>(), keys[1].as<uint32_t>(), vals[0].as<uint32_t>(), vals[1].as<uint32_t>(),
-                               S * (uint32_t)mtry, n_seg, seg_begin.as<uint32_t>(), seg_end.as<uint32_t>(), st);
+                               S * (uint32_t)mtry, n_seg, seg_begin.as<uint32_t>(), seg_end.as<uint32_t>(), sort_lists, st);
         if (rc != RFX_OK) return rc;
         {
             rfx::TimedLaunch timed("grow_eval_segments_kernel", st);
@@ -867,7 +1076,7 @@ int grow_batch(rfx_grown& g, const float* X, const int32_t* y, int64_t N, int32_
                                    vals[0].as<uint32_t>());
                 RFX_LAUNCH_CHECK("build_keys_kernel");
                 rc = sort_segments(tmp, keys[0].as<uint32_t>(), keys[1].as<uint32_t>(), vals[0].as<uint32_t>(), vals[1].as<uint32_t>(),
-                                   h[1], h[0], fb_seg_begin.as<uint32_t>(), fb_seg_end.as<uint32_t>(), st);
+                                   h[1], h[0], fb_seg_begin.as<uint32_t>(), fb_seg_end.as<uint32_t>(), sort_lists, st);
                 if (rc != RFX_OK) return rc;
                 hipLaunchKernelGGL(eval_segments_kernel, blocks_for(h[0], kEvalWaves), dim3(64 * kEvalWaves), 0, st, h[0], C, N,
                                    fb_seg_node.as<int32_t>(), fb_seg_begin.as<uint32_t>(), lv, keys[1].as<uint32_t>(),
