@@ -137,6 +137,14 @@ __device__ __forceinline__ void store4_float(float* base, int64_t at, const floa
 // Writes one wave tile.  acc[r][j] belongs to the pair (a_tile + 4*lane + r, b0 + j): the mismatch
 // count (plain), or the out-of-bag numerator in bits 0..15 and denominator in bits 16..31.  `tr` is
 // this wave's LDS transposition buffer: 64 rows of J + 4 words.
+// (x << kShift) + y in one vector instruction
+template <int kShift>
+__device__ __forceinline__ uint32_t shift_add(uint32_t x, uint32_t y) {
+    uint32_t d;
+    asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "n"(kShift), "v"(y));
+    return d;
+}
+
 // What a raw counter means.  kField 0: the mismatch count (plain), or out-of-bag numerator | denominator
 // << 16.  The fused kernel keeps three 10-bit fields in one counter (mismatches | numerator << 10 |
 // denominator << 20); kField 1 reads its plain part, kField 2 its out-of-bag part.
@@ -624,15 +632,17 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(P, kMode)) void prox_til
                     // three 10-bit fields (B <= 1023): mismatches | numerator << 10 | denominator << 20
                     const uint32_t both_same = __builtin_amdgcn_bitop3_b32(t, xa[r][P], xb[P], 0x08);
                     const uint32_t both = xa[r][P] & xb[P];
+                    // (two shift-and-add instructions; left to itself the compiler shifts both counts and adds the three
+                    // terms, one instruction more per pair and group of trees)
                     acc[r][j] += __builtin_popcount(t);
-                    acc[r][j] += (uint32_t)__builtin_popcount(both_same) << 10;
-                    acc[r][j] += (uint32_t)__builtin_popcount(both) << 20;
+                    acc[r][j] = shift_add<10>((uint32_t)__builtin_popcount(both_same), acc[r][j]);
+                    acc[r][j] = shift_add<20>((uint32_t)__builtin_popcount(both), acc[r][j]);
                 } else if (kOob) {
                     // trees where both are out-of-bag and the leaves agree: ~t & oa & ob
                     const uint32_t both_same = __builtin_amdgcn_bitop3_b32(t, xa[r][P], xb[P], 0x08);
                     const uint32_t both = xa[r][P] & xb[P];
                     acc[r][j] += __builtin_popcount(both_same);
-                    acc[r][j] += (uint32_t)__builtin_popcount(both) << 16;
+                    acc[r][j] = shift_add<16>((uint32_t)__builtin_popcount(both), acc[r][j]);
                 } else {
                     acc[r][j] += __builtin_popcount(t);
                 }
