@@ -414,7 +414,8 @@ def roofline_of_tile_kernel(w, kern, valu_rate, profile, profile_src):
                 "unit": "T counter increments/s", "frac": sizes_sq / (ms * 1e-3) / peak, "traffic": None,
                 "increments": sizes_sq, "avg_launch_ms": ms, "tests_per_s": tests / (ms * 1e-3),
                 "note": "sum over trees and leaves of s (s - 1) / 2 increments instead of N^2 B / 2 pair tests; the pass is bound by "
-                        "the scattered reads of the leaf members, not by the LDS atomics, so the fraction is small by construction; "
+                        "the instructions that fetch and place a leaf's members (cursor and address arithmetic per tree visit, one LDS atomic per member), "
+                        "not by the rate of the LDS atomics, so the fraction against that rate is small by construction; "
                         "tests_per_s is the pair-test rate the same result would need"}
     mode = 2 if w.large else (4 if w.fused else 0)
     dom = "prox_tile_kernel_sparse" if w.large else ("prox_tile_kernel_both" if w.fused else "prox_tile_kernel")
