@@ -367,10 +367,11 @@ def load_pmc_profile(cfg):
     return table, os.path.relpath(path, ROOT), hashlib.sha256(text.encode()).hexdigest()[:16]
 
 
-def fabric_bytes(profile, kernels):
+def fabric_bytes(profile, kernels, optional=()):
     """HBM-side bytes per launch of the named kernels from the profile: FETCH_SIZE and WRITE_SIZE (KiB per dispatch),
     each scaled by what the same counter reads for the library's plain copy kernel of known size (copy_probe_kernel:
-    4 GiB read, 4 GiB written per dispatch).  None if a kernel or the calibration row is missing."""
+    4 GiB read, 4 GiB written per dispatch).  None if a kernel or the calibration row is missing; the `optional` kernels
+    (those a workload may or may not launch) are added where the profile has them."""
     if not profile or "copy_probe_kernel" not in profile:
         return None
 
@@ -393,6 +394,10 @@ def fabric_bytes(profile, kernels):
         if f is None or wr is None:
             return None
         total += (f * known_kib / cal_f + wr * known_kib / cal_w) * 1024.0
+    for kname in optional:
+        f, wr = average(kname, "FETCH_SIZE"), average(kname, "WRITE_SIZE")
+        if f is not None and wr is not None:
+            total += (f * known_kib / cal_f + wr * known_kib / cal_w) * 1024.0
     return total
 
 
@@ -472,7 +477,8 @@ def pv_figures(w, kern, copy_rate, profile):
     gat_rate = rows_bytes / (gat_ms * 1e-3) if gat_ms > 0 else 0.0
     ceil_both = 2.0 / (1.0 / ceil_v + 1.0 / ceil_s)                    # both phases one after the other, each at its ceiling
     both_rate = 2.0 * rows_bytes / ((sum_ms + gat_ms) * 1e-3) if sum_ms + gat_ms > 0 else 0.0
-    fabric = None if w.reduced else fabric_bytes(profile, ["pv_leaf_sum_kernel<", "pv_leaf_sum_big_kernel<", "pv_gather_kernel<"])
+    fabric = None if w.reduced else fabric_bytes(profile, ["pv_leaf_sum_kernel<", "pv_gather_kernel<"],
+                                                  optional=["pv_leaf_sum_big_kernel<", "pv_leaf_sum_split_kernel<", "pv_combine_kernel"])
     if fabric is not None:
         # the profile's rows are per dispatch, one dispatch per group of trees
         fabric *= max(kern["pv_gather_kernel"]["launches"] // applications, 1)
