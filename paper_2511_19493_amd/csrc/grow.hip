@@ -7,8 +7,9 @@
 //   1. every node draws its mtry features (counter-based generator keyed by tree and node number,
 //      so the draws do not depend on the processing order);
 //   2. for every (node, feature) pair the node's rows are copied as (order-preserving key of the
-//      float value, row) pairs and all those segments are sorted in one segmented radix sort
-//      (rocPRIM, the one library primitive of this file);
+//      float value, row) pairs and every segment is sorted: bitonic networks for up to 4096 pairs,
+//      rocPRIM's segmented radix sort (the one library primitive left in this file) for the longer
+//      ones of the first levels;
 //   3. one wave per segment sweeps its sorted rows 64 at a time, keeping the left-side class weights
 //      as prefix sums, and scores every boundary between two different values;
 //   4. the best boundary of a node is taken over its features; rows are split, children that hold
@@ -661,30 +662,94 @@ struct Scratch {
     }
 };
 
-// lists of the segmented sort: medium segment ids, begin / end of the long segments, two counters
-struct SortLists {
-    rfx::DevBuf buf;
-    size_t cap = 0;
-    hipError_t reserve(size_t n_seg, hipStream_t st) {
-        if (n_seg <= cap) return hipSuccess;
-        hipError_t e = hipStreamSynchronize(st);
-        if (e != hipSuccess) return e;
-        cap = n_seg + n_seg / 4 + 64;
-        e = buf.alloc(sizeof(uint32_t) * (3 * cap + 64));
-        if (e != hipSuccess) cap = 0;
-        return e;
-    }
-};
 
-__global__ void zero_counts_kernel(uint32_t* counts) {
-    if (threadIdx.x < 2) counts[threadIdx.x] = 0;
+// Exclusive prefix sum of n 32-bit values in three launches: totals of tiles of kScanTile values, the prefix of those
+// totals by one workgroup, and the tiles again with their offsets.  A thread owns 16 consecutive values.
+constexpr int kScanTile = 4096;
+
+// exclusive prefix of v over the 256 threads of the workgroup (sm: 4 words); *total = sum over the workgroup
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* sm, uint32_t* total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(inc, off);
+        if (lane >= off) inc += up;
+    }
+    __syncthreads();  // sm may still be read by the previous call
+    if (lane == 63) sm[w] = inc;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int u = 0; u < w; ++u) before += sm[u];
+    *total = sm[0] + sm[1] + sm[2] + sm[3];
+    return before + inc - v;
+}
+
+__global__ __launch_bounds__(256) void scan_tile_sums_kernel(const uint32_t* __restrict__ in, uint32_t n,
+                                                            uint32_t* __restrict__ tile_sum) {
+    __shared__ uint32_t sm[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + threadIdx.x * 16;
+    uint32_t v = 0;
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+        if (base + u < (int64_t)n) v += in[base + u];
+    uint32_t total;
+    (void)block_excl_scan(v, sm, &total);
+    if (threadIdx.x == 0) tile_sum[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(256) void scan_tile_offsets_kernel(uint32_t* __restrict__ tile_sum, uint32_t n_tiles) {
+    __shared__ uint32_t sm[4];
+    uint32_t carry = 0;
+    for (uint32_t t0 = 0; t0 < n_tiles; t0 += 256 * 16) {
+        const uint32_t base = t0 + threadIdx.x * 16;
+        uint32_t x[16];
+        uint32_t v = 0;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            x[u] = base + u < n_tiles ? tile_sum[base + u] : 0u;
+            v += x[u];
+        }
+        uint32_t total;
+        uint32_t run = carry + block_excl_scan(v, sm, &total);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            if (base + u < n_tiles) tile_sum[base + u] = run;
+            run += x[u];
+        }
+        carry += total;
+    }
+}
+
+__global__ __launch_bounds__(256) void scan_tiles_kernel(const uint32_t* __restrict__ in, uint32_t n,
+                                                        const uint32_t* __restrict__ tile_off, uint32_t* __restrict__ out) {
+    __shared__ uint32_t sm[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + threadIdx.x * 16;
+    uint32_t x[16];
+    uint32_t v = 0;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        x[u] = base + u < (int64_t)n ? in[base + u] : 0u;
+        v += x[u];
+    }
+    uint32_t total;
+    uint32_t run = tile_off[blockIdx.x] + block_excl_scan(v, sm, &total);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        if (base + u < (int64_t)n) out[base + u] = run;
+        run += x[u];
+    }
 }
 
 int scan_u32(Scratch& tmp, const uint32_t* in, uint32_t* out, uint32_t n, hipStream_t st) {
-    size_t need = 0;
-    RFX_HIP(rocprim::exclusive_scan(nullptr, need, in, out, 0u, (size_t)n, rocprim::plus<uint32_t>(), st));
-    RFX_HIP(tmp.reserve(need, st));
-    RFX_HIP(rocprim::exclusive_scan(tmp.buf.p, need, in, out, 0u, (size_t)n, rocprim::plus<uint32_t>(), st));
+    if (n == 0) return RFX_OK;
+    const uint32_t n_tiles = (uint32_t)(((uint64_t)n + kScanTile - 1) / kScanTile);
+    RFX_HIP(tmp.reserve(sizeof(uint32_t) * (size_t)n_tiles, st));
+    uint32_t* tile_sum = static_cast<uint32_t*>(tmp.buf.p);
+    hipLaunchKernelGGL(scan_tile_sums_kernel, dim3(n_tiles), dim3(256), 0, st, in, n, tile_sum);
+    hipLaunchKernelGGL(scan_tile_offsets_kernel, dim3(1), dim3(256), 0, st, tile_sum, n_tiles);
+    hipLaunchKernelGGL(scan_tiles_kernel, dim3(n_tiles), dim3(256), 0, st, in, n, tile_sum, out);
+    RFX_LAUNCH_CHECK("scan_tiles_kernel");
     return RFX_OK;
 }
 
@@ -696,6 +761,7 @@ int scan_u32(Scratch& tmp, const uint32_t* in, uint32_t* out, uint32_t n, hipStr
 // pairs per thread in registers and exchanges through LDS only at distances of a wave or more.  Only the few long
 // segments of the top levels are left to the library's radix sort.
 constexpr int kSortBlockMax = 4096;
+constexpr int kSortWaveMax = 256;   // up to here a single wave sorts the segment, four pairs per lane
 
 __device__ __forceinline__ u64 shfl_xor_u64(u64 x, int m) {
     const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)x, m), hi = (uint32_t)__shfl_xor((int)(uint32_t)(x >> 32), m);
@@ -710,12 +776,13 @@ __device__ __forceinline__ u64 exchange_step(u64 x, int j, bool keep_min) {
 
 // Four segments per wave, one per quarter.  A quarter sorts a segment of up to 16 pairs by itself; segments of 17 .. 64
 // pairs are then taken one after the other by the whole wave; longer ones are appended to the list of medium segments
-// or to the begin / end arrays of the long ones.  counts[0] = medium, counts[1] = long segments.
+// (those a wave can take from the front of the list, those for a workgroup from its back) or to the begin / end arrays of the
+// long ones.  counts[0] = medium for a wave, counts[3] = medium for a workgroup, counts[1] = long segments.
 __global__ __launch_bounds__(256) void sort_short_segments_kernel(uint32_t n_seg, const uint32_t* __restrict__ seg_begin,
                                                                  const uint32_t* __restrict__ seg_end,
-                                                                 const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
-                                                                 uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out,
-                                                                 uint32_t* __restrict__ medium, uint32_t* __restrict__ long_begin,
+                                                                 const uint32_t* keys_in, const uint32_t* vals_in, uint32_t* keys_out, uint32_t* vals_out,
+                                                                 uint32_t* __restrict__ medium, uint32_t medium_cap,
+                                                                 uint32_t* __restrict__ long_begin,
                                                                  uint32_t* __restrict__ long_end, uint32_t* __restrict__ counts) {
     const int lane = threadIdx.x & 63, gl = lane & 15;
     const uint32_t seg = ((blockIdx.x * 4 + (threadIdx.x >> 6)) << 2) + (lane >> 4);
@@ -736,8 +803,10 @@ __global__ __launch_bounds__(256) void sort_short_segments_kernel(uint32_t n_seg
         }
     }
     if (gl == 0 && len > 64) {
-        if (len <= (uint32_t)kSortBlockMax) {
-            medium[atomicAdd(&counts[0], 1u)] = seg;
+        if (len <= (uint32_t)kSortWaveMax) {
+            medium[atomicAdd(&counts[0], 1u)] = seg;                       // from the front: one wave each
+        } else if (len <= (uint32_t)kSortBlockMax) {
+            medium[medium_cap - 1u - atomicAdd(&counts[3], 1u)] = seg;     // from the back: one workgroup each
         } else {
             const uint32_t at = atomicAdd(&counts[1], 1u);
             long_begin[at] = b;
@@ -763,10 +832,10 @@ __global__ __launch_bounds__(256) void sort_short_segments_kernel(uint32_t n_seg
     }
 }
 
-// Bitonic sort of 256 E values over one workgroup: thread t holds the values at positions t E .. t E + E - 1.  Steps at
-// distances below E stay in the thread's registers, distances below 64 E are lane exchanges, the rest goes through LDS
-// (laid out [r][t], so consecutive lanes touch consecutive words).
-template <int E>
+// Bitonic sort of T E values over T threads (a wave, or a workgroup of 256): thread t holds the values at positions
+// t E .. t E + E - 1.  Steps at distances below E stay in the thread's registers, distances below 64 E are lane exchanges,
+// the rest (workgroup only) goes through LDS, laid out [r][t] so that consecutive lanes touch consecutive words.
+template <int E, int T>
 __device__ __forceinline__ void sort_block(u64 (&x)[E], u64* sm, int t) {
 #pragma unroll
     for (int k = 2; k < E; k <<= 1) {  // direction fixed by the position inside the thread
@@ -783,21 +852,21 @@ __device__ __forceinline__ void sort_block(u64 (&x)[E], u64* sm, int t) {
             }
         }
     }
-    for (int k = (E > 1 ? E : 2); k <= 256 * E; k <<= 1) {
+    for (int k = (E > 1 ? E : 2); k <= T * E; k <<= 1) {
         const bool asc = ((t * E) & k) == 0;
         for (int j = k >> 1; j >= E; j >>= 1) {
             const int d = j / E;
             const bool keep_min = ((t & d) == 0) == asc;
-            if (d < 64) {
+            if (T <= 64 || d < 64) {
 #pragma unroll
                 for (int r = 0; r < E; ++r) x[r] = exchange_step(x[r], d, keep_min);
             } else {
 #pragma unroll
-                for (int r = 0; r < E; ++r) sm[r * 256 + t] = x[r];
+                for (int r = 0; r < E; ++r) sm[r * T + t] = x[r];
                 __syncthreads();
 #pragma unroll
                 for (int r = 0; r < E; ++r) {
-                    const u64 other = sm[r * 256 + (t ^ d)];
+                    const u64 other = sm[r * T + (t ^ d)];
                     x[r] = (x[r] < other) == keep_min ? x[r] : other;
                 }
                 __syncthreads();
@@ -818,10 +887,37 @@ __device__ __forceinline__ void sort_block(u64 (&x)[E], u64* sm, int t) {
     }
 }
 
+// One wave per listed segment of 65 .. kSortWaveMax pairs, four segments per workgroup.
+__global__ __launch_bounds__(256) void sort_wave_segments_kernel(const uint32_t* __restrict__ medium, uint32_t n_listed,
+                                                                const uint32_t* __restrict__ seg_begin,
+                                                                const uint32_t* __restrict__ seg_end, const uint32_t* keys_in,
+                                                                const uint32_t* vals_in, uint32_t* keys_out, uint32_t* vals_out) {
+    constexpr int E = kSortWaveMax / 64;
+    const int lane = threadIdx.x & 63;
+    const uint32_t at = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (at >= n_listed) return;
+    const uint32_t seg = medium[at];
+    const uint32_t b = seg_begin[seg], len = seg_end[seg] - b;
+    u64 x[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        const uint32_t i = (uint32_t)(r * 64 + lane);
+        x[r] = i < len ? ((u64)keys_in[b + i] << 32) | vals_in[b + i] : ~0ull;
+    }
+    sort_block<E, 64>(x, nullptr, lane);
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        const uint32_t i = (uint32_t)(lane * E + r);
+        if (i < len) {
+            keys_out[b + i] = (uint32_t)(x[r] >> 32);
+            vals_out[b + i] = (uint32_t)x[r];
+        }
+    }
+}
+
 template <int E>
-__device__ __forceinline__ void sort_medium_segment(uint32_t b, uint32_t len, const uint32_t* __restrict__ keys_in,
-                                                    const uint32_t* __restrict__ vals_in, uint32_t* __restrict__ keys_out,
-                                                    uint32_t* __restrict__ vals_out, u64* sm) {
+__device__ __forceinline__ void sort_medium_segment(uint32_t b, uint32_t len, const uint32_t* keys_in, const uint32_t* vals_in,
+                                                    uint32_t* keys_out, uint32_t* vals_out, u64* sm) {
     const int t = threadIdx.x;
     u64 x[E];
 #pragma unroll
@@ -829,7 +925,7 @@ __device__ __forceinline__ void sort_medium_segment(uint32_t b, uint32_t len, co
         const uint32_t i = (uint32_t)(r * 256 + t);
         x[r] = i < len ? ((u64)keys_in[b + i] << 32) | vals_in[b + i] : ~0ull;
     }
-    sort_block<E>(x, sm, t);
+    sort_block<E, 256>(x, sm, t);
 #pragma unroll
     for (int r = 0; r < E; ++r) {
         const uint32_t i = (uint32_t)(t * E + r);
@@ -844,46 +940,76 @@ __device__ __forceinline__ void sort_medium_segment(uint32_t b, uint32_t len, co
 __global__ __launch_bounds__(256) void sort_medium_segments_kernel(const uint32_t* __restrict__ medium,
                                                                   const uint32_t* __restrict__ seg_begin,
                                                                   const uint32_t* __restrict__ seg_end,
-                                                                  const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
-                                                                  uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out) {
+                                                                  const uint32_t* keys_in, const uint32_t* vals_in, uint32_t* keys_out,
+                                                                  uint32_t* vals_out) {
     __shared__ u64 sm[kSortBlockMax];
-    const uint32_t seg = medium[blockIdx.x];
+    const uint32_t seg = medium[blockIdx.x];  // (the caller passes the end of the list that holds the workgroup-sized ones)
     const uint32_t b = seg_begin[seg], len = seg_end[seg] - b;
-    if (len <= 256) sort_medium_segment<1>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
-    else if (len <= 512) sort_medium_segment<2>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
+    if (len <= 512) sort_medium_segment<2>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
     else if (len <= 1024) sort_medium_segment<4>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
     else if (len <= 2048) sort_medium_segment<8>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
     else sort_medium_segment<16>(b, len, keys_in, vals_in, keys_out, vals_out, sm);
 }
 
+__global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// Lists of the segmented sort: ids of the medium segments (those for a wave from the front, those for a workgroup from the
+// back), begin / end of the long ones, and the counters ([0] medium for a wave, [1] long, [3] medium for a workgroup).
+struct SortLists {
+    rfx::DevBuf buf;
+    size_t cap = 0;
+    uint32_t *medium = nullptr, *long_begin = nullptr, *long_end = nullptr, *counts = nullptr;
+    hipError_t reserve(size_t n, hipStream_t st) {
+        if (n > cap) {
+            hipError_t e = hipStreamSynchronize(st);
+            if (e != hipSuccess) return e;
+            cap = 0;
+            const size_t c = n + n / 4 + 64;
+            e = buf.alloc(sizeof(uint32_t) * (3 * c + 64));
+            if (e != hipSuccess) return e;
+            cap = c;
+        }
+        medium = buf.as<uint32_t>();
+        long_begin = medium + cap;
+        long_end = long_begin + cap;
+        counts = long_end + cap;
+        return hipSuccess;
+    }
+};
+
+// Every segment up to kSortBlockMax pairs by the networks; the long ones, listed by the first kernel, by the library's
+// segmented radix sort (stable, and the rows arrive ascending, so equal keys keep ascending rows there too).
 int sort_segments(Scratch& tmp, const uint32_t* keys_in, uint32_t* keys_out, const uint32_t* vals_in, uint32_t* vals_out,
-                  uint32_t size, uint32_t n_seg, const uint32_t* seg_begin, const uint32_t* seg_end, SortLists& lists,
+                  uint32_t size, uint32_t n_seg, const uint32_t* seg_begin, const uint32_t* seg_end, SortLists& r,
                   hipStream_t st) {
     if (n_seg == 0) return RFX_OK;
-    RFX_HIP(lists.reserve(n_seg, st));
-    uint32_t* medium = lists.buf.as<uint32_t>();
-    uint32_t* long_begin = medium + lists.cap;
-    uint32_t* long_end = long_begin + lists.cap;
-    uint32_t* counts = long_end + lists.cap;
-    hipLaunchKernelGGL(zero_counts_kernel, dim3(1), dim3(64), 0, st, counts);
-    hipLaunchKernelGGL(sort_short_segments_kernel, dim3((n_seg + 15) / 16), dim3(256), 0, st, n_seg, seg_begin, seg_end, keys_in, vals_in,
-                       keys_out, vals_out, medium, long_begin, long_end, counts);
+    RFX_HIP(r.reserve(n_seg, st));
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, st, r.counts, (size_t)4);
+    hipLaunchKernelGGL(sort_short_segments_kernel, dim3((n_seg + 15) / 16), dim3(256), 0, st, n_seg, seg_begin, seg_end, keys_in,
+                       vals_in, keys_out, vals_out, r.medium, (uint32_t)r.cap, r.long_begin, r.long_end, r.counts);
     RFX_LAUNCH_CHECK("sort_short_segments_kernel");
-    uint32_t h[2] = {0, 0};
-    RFX_HIP(hipMemcpyAsync(h, counts, sizeof(h), hipMemcpyDeviceToHost, st));
+    uint32_t h[4];
+    RFX_HIP(hipMemcpyAsync(h, r.counts, sizeof(h), hipMemcpyDeviceToHost, st));
     RFX_HIP(hipStreamSynchronize(st));
     if (h[0] > 0) {
-        hipLaunchKernelGGL(sort_medium_segments_kernel, dim3(h[0]), dim3(256), 0, st, medium, seg_begin, seg_end, keys_in, vals_in,
-                           keys_out, vals_out);
+        hipLaunchKernelGGL(sort_wave_segments_kernel, dim3((h[0] + 3) / 4), dim3(256), 0, st, r.medium, h[0], seg_begin, seg_end,
+                           keys_in, vals_in, keys_out, vals_out);
+        RFX_LAUNCH_CHECK("sort_wave_segments_kernel");
+    }
+    if (h[3] > 0) {
+        hipLaunchKernelGGL(sort_medium_segments_kernel, dim3(h[3]), dim3(256), 0, st, r.medium + (r.cap - h[3]), seg_begin, seg_end,
+                           keys_in, vals_in, keys_out, vals_out);
         RFX_LAUNCH_CHECK("sort_medium_segments_kernel");
     }
     if (h[1] > 0) {
         size_t need = 0;
-        RFX_HIP(rocprim::segmented_radix_sort_pairs(nullptr, need, keys_in, keys_out, vals_in, vals_out, size, h[1], long_begin,
-                                                    long_end, 0, 32, st));
+        RFX_HIP(rocprim::segmented_radix_sort_pairs(nullptr, need, keys_in, keys_out, vals_in, vals_out, size, h[1], r.long_begin,
+                                                    r.long_end, 0, 32, st));
         RFX_HIP(tmp.reserve(need, st));
-        RFX_HIP(rocprim::segmented_radix_sort_pairs(tmp.buf.p, need, keys_in, keys_out, vals_in, vals_out, size, h[1], long_begin,
-                                                    long_end, 0, 32, st));
+        RFX_HIP(rocprim::segmented_radix_sort_pairs(tmp.buf.p, need, keys_in, keys_out, vals_in, vals_out, size, h[1], r.long_begin,
+                                                    r.long_end, 0, 32, st));
     }
     return RFX_OK;
 }

@@ -64,6 +64,25 @@ def test_growth_on_degenerate_inputs(torch_cuda):
     _compare(torch_cuda, X, y, 64, 8, 2, 80)
 
 
+def test_growth_with_long_segments_of_few_values(torch_cuda):
+    """Segments far longer than the sorting networks take, whose values are a handful of distinct numbers (every pair of a
+    segment lands in a few buckets that stay long through both bucket passes), next to continuous features and one whose
+    values all share sign and exponent (spread over the buckets only by the second pass)."""
+    rng = np.random.default_rng(21)
+    N = 30000
+    X = np.empty((N, 6), np.float32)
+    X[:, 0] = rng.integers(0, 3, N)                       # three values
+    X[:, 1] = 7.0                                         # one value
+    X[:, 2] = rng.standard_normal(N)
+    X[:, 3] = 1.0 + rng.random(N)                         # all in [1, 2): one exponent
+    X[:, 4] = np.round(rng.standard_normal(N) * 2.0) * 0.5
+    X[:, 5] = rng.standard_normal(N) * 1e-3
+    y = ((X[:, 0] > 0) + (X[:, 2] > 0.3) + (X[:, 3] > 1.5)).astype(np.int32)
+    y[::17] = rng.integers(0, 4, len(y[::17]))
+    _compare(torch_cuda, X, y, 4, 6, 3, 4242)
+    _compare(torch_cuda, X, y, 4, 3, 6, 4243)
+
+
 def test_growth_with_the_largest_feature_subsets(torch_cuda):
     rng = np.random.default_rng(11)
     for M, mtry in ((64, 64), (70, 64), (200, 64), (1000, 31)):
