@@ -128,6 +128,8 @@ class Workload:
             # capacity of the sparse list: one counting call on the leaf ids of this forest
             self.sp_cap = max(rfx.prox_sparse_count(self.leaf, self.Lb, 1), 1)
             self.sp_nnz = torch.zeros(1, dtype=torch.int64, device=dev)
+            # the row pass works from the grouping the factorisation needs anyway (4 B N bytes of scratch of its own)
+            self.ws_sparse = rfx.new_workspace(rfx.prox_sparse_plan_workspace_bytes(self.plan)) if B <= 4096 else None
             self.alloc_sparse(self.sp_cap)
         else:
             self.prox = torch.empty((N, N), dtype=torch.float32, device=dev)
@@ -162,11 +164,15 @@ class Workload:
         return out
 
     def sparse_pass(self):
-        """Every non-zero pair as (i, j, count).  Large workloads take the synchronous call, which picks the cheaper of
-        its two algorithms (pair tests on bit planes, or counting row by row from the samples grouped by leaf) and builds
-        the grouping it needs inside the call; the others time the asynchronous tile pass."""
+        """Every non-zero pair as (i, j, count).  Large workloads count row by row from the samples grouped by leaf, out of
+        the grouping this step has just built for the implicit product (asynchronous, nothing allocated; beyond 4,096
+        trees the synchronous call, which picks the cheaper of the two algorithms and builds a grouping of its own); the
+        others time the asynchronous tile pass."""
         rfx = self.rfx
-        if self.large:
+        if self.large and self.ws_sparse is not None:
+            rfx.prox_sparse_plan(self.plan, self.ws_sparse, self.sp_nnz, self.sp_rows, self.sp_cols, self.sp_cnt, min_count=1,
+                                 count_dtype=rfx.U16)
+        elif self.large:
             got = ctypes.c_int64(0)
             rfx._check(self.lib.rfx_prox_sparse(self.leaf.data_ptr(), self.N, self.B, self.Lb, 1, rfx.U16, self.sp_cap,
                                                 self.sp_rows.data_ptr(), self.sp_cols.data_ptr(), self.sp_cnt.data_ptr(), 0,
@@ -183,13 +189,16 @@ class Workload:
                                                        rfx.UPPER_PACKED, prox=self.prox_oob))
 
     def step(self):
-        """One pass of the whole path, enqueued on one stream: traversal, the dense pass (fused plain + out-of-bag, or
-        the exact sparse list where the dense outputs do not fit), the grouping of the samples by leaf for the
-        implicit product (it depends on this step's leaf ids; the only call that waits for the device: it reads the
-        number of big leaves back), the factorisation with INT8 factors, the scaling."""
+        """One pass of the whole path, enqueued on one stream: traversal, the dense pass (fused plain + out-of-bag), the
+        grouping of the samples by leaf for the implicit product (it depends on this step's leaf ids; the only call that
+        waits for the device: it reads the number of big leaves back), the factorisation with INT8 factors, the scaling.
+        Where the dense outputs do not fit, the exact sparse list takes the place of the dense pass and is counted out of
+        that grouping, which therefore comes first."""
         rfx = self.rfx
         self.timed("leaf_assign", lambda: rfx.leaf_assign(self.gf, self.dX, self.leaf))
         if self.large:
+            # the sparse list is counted out of the grouping, so the grouping comes first here
+            self.timed("pv_plan", lambda: rfx.pv_plan_rebuild(self.plan, self.leaf))
             self.timed("prox_sparse", self.sparse_pass)
         elif self.fused:
             self.timed("prox_dense_oob", lambda: rfx.prox_dense_oob_ws(
@@ -197,7 +206,8 @@ class Workload:
                 prox_oob=self.prox_oob))
         else:
             self.dense_and_oob_separately()
-        self.timed("pv_plan", lambda: rfx.pv_plan_rebuild(self.plan, self.leaf))
+        if not self.large:
+            self.timed("pv_plan", lambda: rfx.pv_plan_rebuild(self.plan, self.leaf))
         self.timed("prox_lowrank", lambda: rfx.prox_lowrank_plan(self.plan, self.dV0, self.T, self.ws_lr, self.lam, self.V,
                                                                  self.Q, self.scales, self.status))
         if self.mds_iters == 0:

@@ -280,6 +280,22 @@ int rfx_prox_sparse_rows(const uint32_t* leaf, int64_t N, int32_t B, int32_t lea
                          int count_dtype, int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts, float* prox,
                          int64_t* nnz, void* stream);
 
+/* The row-by-row list from an existing grouping (the plan of the implicit product, see rfx_pv_plan_create below), for
+ * callers that keep one anyway: no grouping is built and nothing is allocated.  Asynchronous.
+ *   plan       built for the leaf ids in question; the call marks entries of its member lists while it runs and takes
+ *              the marks out again at the end, so until the call has finished on `stream` the plan must not be used by
+ *              work on other streams; work queued on `stream` afterwards finds it as before.
+ *   nnz        [device] uint64, 8-byte aligned: cleared by the call, counts every qualifying pair (the caller reads it
+ *              after synchronising and compares it with the capacity; beyond the capacity nothing is written).
+ *   workspace  [device] rfx_prox_sparse_plan_workspace_bytes (4 B N) bytes, 256-byte aligned.
+ * Other arguments and outputs as rfx_prox_sparse_rows.
+ * Errors: RFX_ERR_NULL, RFX_ERR_INVALID_ARG, RFX_ERR_UNSUPPORTED (B > 4096), RFX_ERR_CAPACITY (workspace too small). */
+typedef struct rfx_pv_plan rfx_pv_plan; /* the grouping of the samples by tree and leaf, see rfx_pv_plan_create */
+int rfx_prox_sparse_plan_workspace_bytes(const rfx_pv_plan* plan, int64_t* bytes);
+int rfx_prox_sparse_plan(rfx_pv_plan* plan, int32_t min_count, int count_dtype, int64_t capacity, uint32_t* rows,
+                         uint32_t* cols, void* counts, float* prox, uint64_t* nnz, void* workspace, int64_t workspace_bytes,
+                         void* stream);
+
 /* Case-wise outlier measures from the proximity rows ("Case-wise Proximity"), computed tile by
  * tile without storing the matrix.  With p(i,j) = cnt(i,j) / B:
  *   printed[i] = (1/(N-1)) sum_{j != i, p(i,j) > 0} 1 / p(i,j)^2   the paper's equation; pairs with
@@ -339,7 +355,6 @@ int rfx_oob_vote(const uint32_t* leaf, const uint16_t* inbag, const int32_t* lea
  *                       with events, so work queued on `stream` afterwards sees Y complete; calls
  *                       on one plan from several streams at once race on its scratch.
  *   rfx_prox_matvec:    one-shot convenience: create plan, apply, destroy.  Synchronous. */
-typedef struct rfx_pv_plan rfx_pv_plan;
 int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, rfx_pv_plan** out,
                        void* stream);
 int rfx_pv_plan_destroy(rfx_pv_plan* plan);

@@ -30,7 +30,7 @@ EXPORTS = (
     "rfx_factor_sizes", "rfx_quantise_factor", "rfx_dequantise_factor",
     "rfx_prox_workspace_bytes", "rfx_prox_dense_ws", "rfx_prox_oob_ws", "rfx_prox_dense_oob_ws", "rfx_prox_sparse_ws",
     "rfx_prox_outlier_ws", "rfx_pv_plan_reserve", "rfx_pv_plan_rebuild", "rfx_pv_plan_info", "rfx_lowrank_workspace_bytes", "rfx_prox_lowrank_plan",
-    "rfx_mds3d_workspace_bytes", "rfx_mds3d_ws", "rfx_prox_dense_noalloc",
+    "rfx_mds3d_workspace_bytes", "rfx_mds3d_ws", "rfx_prox_dense_noalloc", "rfx_prox_sparse_plan_workspace_bytes", "rfx_prox_sparse_plan",
 )
 
 
@@ -99,6 +99,8 @@ def load():
             "rfx_prox_dense_oob_ws": [vp, vp, i64, i32, i32, ci, ci, vp, vp, ci, vp, vp, vp, vp, i64, vp],
             "rfx_prox_sparse_ws": [vp, i64, i32, i32, i32, ci, i64, vp, vp, vp, vp, vp, vp, i64, vp],
             "rfx_prox_outlier_ws": [vp, i64, i32, i32, vp, vp, vp, vp, i64, vp],
+            "rfx_prox_sparse_plan_workspace_bytes": [vp, ctypes.POINTER(i64)],
+            "rfx_prox_sparse_plan": [vp, i32, ci, i64, vp, vp, vp, vp, vp, vp, i64, vp],
             "rfx_pv_plan_reserve": [vp, i32],
             "rfx_pv_plan_rebuild": [vp, vp, vp],
             "rfx_pv_plan_info": [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)],
@@ -576,6 +578,27 @@ def prox_sparse_ws(leaf, leaf_bound: int, workspace, nnz, rows=None, cols=None, 
                                      _dev(counts, _count_dtype(count_dtype), (cap,)) if counts is not None else 0,
                                      _dev(prox, torch.float32, (cap,)) if prox is not None else 0,
                                      _dev(nnz, torch.int64, (1,)), wp, wb, _stream()))
+
+
+def prox_sparse_plan_workspace_bytes(plan: "PvPlan") -> int:
+    """rfx_prox_sparse_plan_workspace_bytes."""
+    out = ctypes.c_int64(0)
+    _check(load().rfx_prox_sparse_plan_workspace_bytes(plan._h, ctypes.byref(out)))
+    return out.value
+
+
+def prox_sparse_plan(plan: "PvPlan", workspace, nnz, rows=None, cols=None, counts=None, prox=None, min_count: int = 1,
+                     count_dtype: int = U32):
+    """rfx_prox_sparse_plan: the row-by-row list from an existing plan; nnz is a CUDA int64 tensor of one element; the
+    capacity is the length of rows (0 without it: count only); asynchronous."""
+    import torch
+    cap = 0 if rows is None else rows.numel()
+    wp, wb = _ws_ptr(workspace)
+    _check(load().rfx_prox_sparse_plan(plan._h, min_count, count_dtype, cap,
+                                       _dev(rows, torch.int32), _dev(cols, torch.int32, (cap,)) if cols is not None else 0,
+                                       _dev(counts, _count_dtype(count_dtype), (cap,)) if counts is not None else 0,
+                                       _dev(prox, torch.float32, (cap,)) if prox is not None else 0,
+                                       _dev(nnz, torch.int64, (1,)), wp, wb, _stream()))
 
 
 def prox_outlier_ws(leaf, leaf_bound: int, workspace, labels=None, printed=None, classic=None):

@@ -49,6 +49,15 @@ __global__ __launch_bounds__(256) void row_starts_kernel(uint32_t* __restrict__ 
     if (last) perm[t] = i | kEndFlag;
 }
 
+// Takes the marks of row_starts_kernel out of perm again: the last entry of every segment that holds anything.
+__global__ __launch_bounds__(256) void row_ends_clear_kernel(uint32_t* __restrict__ perm, const uint32_t* __restrict__ seg_start,
+                                                            int64_t n_slots) {
+    const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= n_slots) return;
+    const uint32_t lo = seg_start[s], hi = seg_start[s + 1];
+    if (hi > lo) perm[hi - 1] &= ~kEndFlag;
+}
+
 // sum over all segments of len * (len - 1) / 2: the number of counter increments of the row pass
 __global__ __launch_bounds__(256) void pair_work_kernel(const uint32_t* __restrict__ seg_start, int64_t n_slots,
                                                        unsigned long long* __restrict__ out) {
@@ -457,6 +466,48 @@ int sparse_rows_enqueue(rfx_pv_plan* plan, uint32_t* start, int32_t min_count, i
 }
 
 }  // namespace rfx
+
+extern "C" int rfx_prox_sparse_plan_workspace_bytes(const rfx_pv_plan* plan, int64_t* bytes) {
+    if (!plan || !bytes) return rfx::fail(RFX_ERR_NULL, "rfx_prox_sparse_plan_workspace_bytes: null argument");
+    *bytes = (int64_t)((sizeof(uint32_t) * (size_t)plan->B * (size_t)plan->N + 255) / 256 * 256);
+    return RFX_OK;
+}
+
+extern "C" int rfx_prox_sparse_plan(rfx_pv_plan* plan, int32_t min_count, int count_dtype, int64_t capacity, uint32_t* rows,
+                                    uint32_t* cols, void* counts, float* prox, uint64_t* nnz, void* workspace,
+                                    int64_t workspace_bytes, void* stream) {
+    if (!plan || !nnz || !workspace) return rfx::fail(RFX_ERR_NULL, "rfx_prox_sparse_plan: null argument");
+    if (!plan->built) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_sparse_plan: the plan's last rebuild failed");
+    if (count_dtype != RFX_U16 && count_dtype != RFX_U32)
+        return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_sparse_plan: count_dtype=%d", count_dtype);
+    if (min_count < 1) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_sparse_plan: min_count=%d below 1", min_count);
+    if (capacity < 0) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_sparse_plan: capacity=%lld", (long long)capacity);
+    if (capacity > 0 && (!rows || !cols)) return rfx::fail(RFX_ERR_NULL, "rfx_prox_sparse_plan: rows / cols are null");
+    if (plan->B > rfx::kSparseRowsMaxTrees)
+        return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_sparse_plan: more than %d trees (use rfx_prox_sparse_ws)", rfx::kSparseRowsMaxTrees);
+    if (plan->N >= (1ll << 31)) return rfx::fail(RFX_ERR_UNSUPPORTED, "rfx_prox_sparse_plan: N=%lld", (long long)plan->N);
+    int64_t need = 0;
+    (void)rfx_prox_sparse_plan_workspace_bytes(plan, &need);
+    if (workspace_bytes < need)
+        return rfx::fail(RFX_ERR_CAPACITY, "rfx_prox_sparse_plan: workspace of %lld bytes, %lld needed", (long long)workspace_bytes,
+                         (long long)need);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0 || reinterpret_cast<uintptr_t>(nnz) % 8 != 0)
+        return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_prox_sparse_plan: workspace must be 256-byte aligned, nnz 8-byte aligned");
+    hipStream_t st = rfx::as_stream(stream);
+    static_assert(sizeof(unsigned long long) == sizeof(uint64_t), "the pair counter is a 64-bit atomic");
+    unsigned long long* cursor = reinterpret_cast<unsigned long long*>(nnz);
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, st, cursor);
+    int rc = rfx::sparse_rows_enqueue(plan, static_cast<uint32_t*>(workspace), min_count, count_dtype == RFX_U16, capacity, rows, cols,
+                                      counts, prox, cursor, st);
+    // whatever happened, the marks come out of the member lists again, so the plan serves the implicit product as before
+    const int64_t n_slots = (int64_t)plan->B * plan->Lb;
+    hipLaunchKernelGGL(row_ends_clear_kernel, dim3((unsigned)rfx::ceil_div(n_slots, 256)), dim3(256), 0, st, plan->d_perm,
+                       plan->d_seg_start, n_slots);
+    if (rc != RFX_OK) return rc;
+    RFX_LAUNCH_CHECK("row_ends_clear_kernel");
+    plan->built = true;
+    return RFX_OK;
+}
 
 extern "C" int rfx_prox_sparse_rows(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_bound, int32_t min_count,
                                     int count_dtype, int64_t capacity, uint32_t* rows, uint32_t* cols, void* counts,

@@ -114,6 +114,71 @@ def test_sparse_capacity_and_argument_errors(torch_cuda, cfg1):
         np.testing.assert_array_equal(x, y)
 
 
+def test_row_pass_from_an_existing_plan(torch_cuda, small2):
+    """rfx_prox_sparse_plan: the list from the plan of the implicit product, asynchronous, nothing allocated inside; the
+    triplets against the oracle's, and the plan serves the implicit product afterwards exactly as a fresh one does
+    (the marks the row pass leaves in its member lists are taken out again)."""
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    torch = torch_cuda
+    cases = [("small2", small2["leaf"][:48], int(small2["leaf"][:48].max()) + 1)]
+    rng = np.random.default_rng(31)
+    cases.append(("random ids, three column chunks", rng.integers(0, 7000, size=(4, 70001)).astype(np.uint32), 7000))
+    for name, leaf, bound in cases:
+        B, N = leaf.shape
+        print(f"row pass from a plan: {name} N={N} B={B}", flush=True)
+        d = _dev(torch, leaf)
+        plan = rfx.PvPlan(d, bound)
+        V = torch.from_numpy(ri.start_block(N, 24)).cuda()
+        y_before = plan.apply(V).clone()
+        ws = rfx.new_workspace(rfx.prox_sparse_plan_workspace_bytes(plan))
+        nnz = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+        for min_count, dtype in ((1, rfx.U32), (2, rfx.U16)):
+            rr, rc, rv = oracle.sparse_upper(leaf, min_count)
+            rfx.prox_sparse_plan(plan, ws, nnz, min_count=min_count, count_dtype=dtype)          # count only
+            assert int(nnz.item()) == rr.size
+            cap = rr.size + 5
+            rows = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+            cols = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+            counts = torch.zeros(cap, dtype=torch.int16 if dtype == rfx.U16 else torch.int32, device="cuda")
+            prox = torch.zeros(cap, dtype=torch.float32, device="cuda")
+            rfx.prox_sparse_plan(plan, ws, nnz, rows, cols, counts, prox, min_count=min_count, count_dtype=dtype)
+            y_after = plan.apply(V)                                  # queued right behind it on the same stream
+            torch.cuda.synchronize()
+            n = int(nnz.item())
+            assert n == rr.size
+            assert bool((rows[n:] == -1).all())                      # nothing beyond the list
+            r, c, v, pq = _sorted_triplets(rows[:n], cols[:n], counts[:n], prox[:n])
+            np.testing.assert_array_equal(r, rr)
+            np.testing.assert_array_equal(c, rc)
+            np.testing.assert_array_equal(v, rv)
+            np.testing.assert_array_equal(pq, (rv.astype(np.float32) / np.float32(B)).astype(np.float32))
+            assert torch.equal(y_after, y_before)
+        # too small a list: the count is still complete and nothing is written past the capacity
+        small = torch.full((3,), -1, dtype=torch.int32, device="cuda")
+        guard = torch.full((3,), -1, dtype=torch.int32, device="cuda")
+        rfx.prox_sparse_plan(plan, ws, nnz, small, guard.clone(), min_count=1)
+        torch.cuda.synchronize()
+        assert int(nnz.item()) == oracle.sparse_upper(leaf, 1)[0].size
+        fresh = rfx.PvPlan(d, bound)
+        assert torch.equal(plan.apply(V), fresh.apply(V))
+        plan.close()
+        fresh.close()
+    # host-side checks
+    lib = rfx.load()
+    import ctypes
+    plan = rfx.PvPlan(_dev(torch, cases[0][1]), cases[0][2])
+    ws = rfx.new_workspace(rfx.prox_sparse_plan_workspace_bytes(plan))
+    nnz = torch.zeros(1, dtype=torch.int64, device="cuda")
+    wp, wb = rfx._ws_ptr(ws)
+    assert lib.rfx_prox_sparse_plan(plan._h, 1, rfx.U32, 0, None, None, None, None, nnz.data_ptr(), wp, wb - 256, None) == rfx.ERR_CAPACITY
+    assert lib.rfx_prox_sparse_plan(plan._h, 0, rfx.U32, 0, None, None, None, None, nnz.data_ptr(), wp, wb, None) == rfx.ERR_INVALID_ARG
+    assert lib.rfx_prox_sparse_plan(plan._h, 1, rfx.U32, 4, None, None, None, None, nnz.data_ptr(), wp, wb, None) == rfx.ERR_NULL
+    assert lib.rfx_prox_sparse_plan(None, 1, rfx.U32, 0, None, None, None, None, nnz.data_ptr(), wp, wb, None) == rfx.ERR_NULL
+    plan.close()
+
+
 def test_row_pass_rejects_what_it_cannot_hold(torch_cuda):
     import paper_2511_19493_amd as rfx
     import ctypes
