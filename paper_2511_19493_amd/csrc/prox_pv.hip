@@ -149,15 +149,47 @@ __global__ __launch_bounds__(256) void pv_scan_kernel(uint32_t* __restrict__ cou
     if (b == B - 1 && t == 0) seg_start[(int64_t)B * Lb] = (uint32_t)((int64_t)B * N);
 }
 
+// Groups the lanes of a wave by key: my_leader = lowest lane with this lane's key, rank = lanes with the same key below this
+// one, gcount = size of the group.  In a deep forest nearly all 64 keys of a step differ, so the lanes first find out which
+// of them may share a key at all: every lane writes its number into a 1,024-entry LDS table at a hash of its key and reads
+// the entry back; a lane that reads its own number has a key no other lane holds, unless that other lane lost the entry to
+// it and is therefore among the rest.  Only the keys of the rest are then compared across the wave, one ballot per key.
+constexpr int kRankTable = 1024;
+
+__device__ __forceinline__ void rank_equal_keys(uint32_t key, bool valid, int lane, uint32_t* tab, int& my_leader, uint32_t& rank,
+                                                uint32_t& gcount) {
+    const uint32_t h = (key * 2654435761u) >> 22;
+    if (valid) tab[h] = (uint32_t)lane;
+    __builtin_amdgcn_wave_barrier();   // one wave: its LDS accesses complete in order
+    const bool lost = valid && tab[h] != (uint32_t)lane;
+    __builtin_amdgcn_wave_barrier();   // the next step's writes stay behind these reads
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    uint64_t remaining = __ballot(lost);
+    my_leader = lane;
+    rank = 0;
+    gcount = 1;
+    while (remaining) {
+        const int leader = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)remaining) - 1);
+        const uint32_t lk = __builtin_amdgcn_readlane(key, leader);
+        const uint64_t m = __ballot(valid && key == lk);
+        if (valid && key == lk) {
+            my_leader = __ffsll((unsigned long long)m) - 1;
+            rank = (uint32_t)__popcll(m & lt_mask);
+            gcount = (uint32_t)__popcll(m);
+        }
+        remaining &= ~m;
+    }
+}
+
 // Stable scatter: one wave per (part, tree) walks its samples 64 at a time in ascending order.  Lanes
 // with the same slot are ranked by lane index; the group's first lane reserves the group's range
 // with one atomic add on the part's cursor, so the order inside every leaf is ascending sample index.
 __global__ __launch_bounds__(64) void pv_scatter_kernel(const uint32_t* __restrict__ slot, int64_t N, int32_t Lb,
                                                        int64_t part_len, uint32_t* __restrict__ cursor,
                                                        uint32_t* __restrict__ perm) {
+    __shared__ uint32_t tab[kRankTable];
     const int q = blockIdx.x, Q = gridDim.x, b = blockIdx.y;
     const int lane = threadIdx.x;
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
     const uint32_t* s = slot + (int64_t)b * N;
     uint32_t* cur = cursor + ((int64_t)b * Q + q) * Lb - (int64_t)b * Lb;  // indexed by slot = b*Lb + leaf
     const int64_t lo = (int64_t)q * part_len, hi = min(N, lo + part_len);
@@ -165,20 +197,9 @@ __global__ __launch_bounds__(64) void pv_scatter_kernel(const uint32_t* __restri
         const int64_t i = i0 + lane;
         const bool valid = i < hi;
         const uint32_t key = valid ? s[i] : 0xffffffffu;
-        uint64_t remaining = __ballot(valid);
-        int my_leader = lane;
-        uint32_t rank = 0, gcount = 0;
-        while (remaining) {
-            const int leader = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)remaining) - 1);
-            const uint32_t lk = __builtin_amdgcn_readlane(key, leader);
-            const uint64_t m = __ballot(valid && key == lk);
-            if (valid && key == lk) {
-                my_leader = leader;
-                rank = (uint32_t)__popcll(m & lt_mask);
-                gcount = (uint32_t)__popcll(m);
-            }
-            remaining &= ~m;
-        }
+        int my_leader;
+        uint32_t rank, gcount;
+        rank_equal_keys(key, valid, lane, tab, my_leader, rank, gcount);
         uint32_t base = 0;
         if (valid && my_leader == lane) base = atomicAdd(&cur[key], gcount);
         base = __shfl(base, my_leader);
@@ -195,9 +216,9 @@ __global__ __launch_bounds__(64) void pv_scatter_lds_kernel(const uint32_t* __re
                                                            int64_t part_len, const uint32_t* __restrict__ cursor,
                                                            uint32_t* __restrict__ perm) {
     extern __shared__ uint32_t cur[];  // [Lb]
+    __shared__ uint32_t tab[kRankTable];
     const int q = blockIdx.x, Q = gridDim.x, b = blockIdx.y;
     const int lane = threadIdx.x;
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
     const uint32_t* s = slot + (int64_t)b * N;
     const uint32_t* mine = cursor + ((int64_t)b * Q + q) * Lb;
     for (int l = lane; l < Lb; l += 64) cur[l] = mine[l];
@@ -208,20 +229,9 @@ __global__ __launch_bounds__(64) void pv_scatter_lds_kernel(const uint32_t* __re
         const int64_t i = i0 + lane;
         const bool valid = i < hi;
         const uint32_t key = valid ? s[i] - slot0 : 0xffffffffu;
-        uint64_t remaining = __ballot(valid);
-        int my_leader = lane;
-        uint32_t rank = 0, gcount = 0;
-        while (remaining) {
-            const int leader = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)remaining) - 1);
-            const uint32_t lk = __builtin_amdgcn_readlane(key, leader);
-            const uint64_t m = __ballot(valid && key == lk);
-            if (valid && key == lk) {
-                my_leader = leader;
-                rank = (uint32_t)__popcll(m & lt_mask);
-                gcount = (uint32_t)__popcll(m);
-            }
-            remaining &= ~m;
-        }
+        int my_leader;
+        uint32_t rank, gcount;
+        rank_equal_keys(key, valid, lane, tab, my_leader, rank, gcount);
         uint32_t base = 0;
         if (valid && my_leader == lane) {
             base = cur[key];

@@ -478,7 +478,15 @@ def test_cfg5_full_tree_count():
     # implicit product, in full, and the factorisation against the float64 iteration from the same start block
     V0 = ri.start_block(N, k)
     plan = rfx.PvPlan(leaf, Lb)
+    # the row pass out of this plan first (count only; it marks the plan's member lists and takes the marks out again),
+    # then the product from the same plan: the way bench.py's step uses the two at this workload
+    ws = rfx.new_workspace(rfx.prox_sparse_plan_workspace_bytes(plan))
+    nz = torch.zeros(1, dtype=torch.int64, device="cuda")
+    rfx.prox_sparse_plan(plan, ws, nz)
     Y = plan.apply(torch.from_numpy(V0).cuda()).cpu().numpy().astype(np.float64)
+    assert int(nz.item()) == nnz
+    say("sparse: the row pass out of the product's plan counts the same pairs")
+    del ws
     plan.close()
     t0 = time.time()
     Yref = oracle.pv_implicit(ref_leaf, V0.astype(np.float64))
