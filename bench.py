@@ -456,6 +456,41 @@ def roofline_of_tile_kernel(w, kern, valu_rate, profile, profile_src):
             "measured_valu_lane_ops_per_s": valu_rate, "frac_of_measured_valu": achieved / valu_rate if valu_rate > 0 else 0.0}
 
 
+def pv_phases_alone(w, ceil_v, ceil_s):
+    """The two phases of the implicit product with nothing running next to them: a plan on the first trees only, few
+    enough (B N below 10^7) that the library keeps them in one group, so the leaf sums and the gather run one after the
+    other on one stream.  Same kernels, same leaf sizes per tree, same ceilings.  None where the whole forest is that small
+    anyway (then the main figures are already of this kind)."""
+    rfx, torch = w.rfx, w.torch
+    N, B, k = w.N, w.B, w.k
+    nb = int(min(B, 9_900_000 // N))
+    if nb < 8 or nb >= B:
+        return None
+    plan = rfx.PvPlan(w.leaf[:nb].contiguous(), w.Lb)
+    rfx.pv_plan_reserve(plan, k)
+    Y = torch.empty_like(w.dV0)
+    for _ in range(3):
+        plan.apply(w.dV0, Y)
+    torch.cuda.synchronize()
+    rfx.timing_enable(True)          # also clears the kernel timers (the step's have been read by now)
+    reps = 20
+    for _ in range(reps):
+        plan.apply(w.dV0, Y)
+    torch.cuda.synchronize()
+    sum_ms, n_sum = rfx.timing_get("pv_leaf_sum_kernel")
+    gat_ms, n_gat = rfx.timing_get("pv_gather_kernel")
+    plan.close()
+    assert n_sum == reps and n_gat == reps, "the reduced plan ran in more than one group"
+    rows_bytes = 4.0 * k * nb * N
+    sum_rate, gat_rate = rows_bytes / (sum_ms / reps * 1e-3), rows_bytes / (gat_ms / reps * 1e-3)
+    return {"trees": nb, "leaf_sum_ms_per_tree": sum_ms / reps / nb, "gather_ms_per_tree": gat_ms / reps / nb,
+            "leaf_sums": {"achieved": sum_rate / 1e9, "ceiling": ceil_v / 1e9, "frac": sum_rate / ceil_v},
+            "gather": {"achieved": gat_rate / 1e9, "ceiling": ceil_s / 1e9, "frac": gat_rate / ceil_s},
+            "both": {"achieved": 2.0 * rows_bytes / ((sum_ms + gat_ms) / reps * 1e-3) / 1e9,
+                     "ceiling": 2.0 / (1.0 / ceil_v + 1.0 / ceil_s) / 1e9,
+                     "frac": 2.0 * rows_bytes / ((sum_ms + gat_ms) / reps * 1e-3) / (2.0 / (1.0 / ceil_v + 1.0 / ceil_s))}}
+
+
 def pv_figures(w, kern, copy_rate, profile):
     """Implicit product: algorithmic bytes per application = B*N*(2*4k + 4) + 2*4*N*k.  One application (`pv_apply`: a
     bracket on the caller's stream around the whole call) runs in groups of trees, the gather of a group on a second
@@ -487,6 +522,7 @@ def pv_figures(w, kern, copy_rate, profile):
     gat_rate = rows_bytes / (gat_ms * 1e-3) if gat_ms > 0 else 0.0
     ceil_both = 2.0 / (1.0 / ceil_v + 1.0 / ceil_s)                    # both phases one after the other, each at its ceiling
     both_rate = 2.0 * rows_bytes / ((sum_ms + gat_ms) * 1e-3) if sum_ms + gat_ms > 0 else 0.0
+    alone = pv_phases_alone(w, ceil_v, ceil_s)
     fabric = None if w.reduced else fabric_bytes(profile, ["pv_leaf_sum_kernel<", "pv_gather_kernel<"],
                                                   optional=["pv_leaf_sum_big_kernel<", "pv_leaf_sum_split_kernel<", "pv_combine_kernel"])
     if fabric is not None:
@@ -502,7 +538,9 @@ def pv_figures(w, kern, copy_rate, profile):
                                        "ceiling_is": f"rfx_probe_gather on a table of {max(N, 64)} rows x {kp} floats (the size of V)"},
                          "gather": {"achieved": gat_rate / 1e9, "ceiling": ceil_s / 1e9, "frac": gat_rate / ceil_s,
                                     "ceiling_is": f"rfx_probe_gather on a table of {leaves_per_tree} rows x {kp} floats (one tree's leaf sums)"},
-                         "note": "kernel times of the two phases added up (in the step they overlap on two streams: avg_ms)"},
+                         "note": "kernel times of the two phases added up (in the step they overlap on two streams: avg_ms), "
+                                 "so each is slowed by the other; phases_alone has them one after the other",
+                         "phases_alone": alone},
             "measured_fabric_bytes": fabric,
             "measured_fabric_frac_of_hbm_peak": fabric / (pv_ms * 1e-3) / PEAK_HBM_BYTES if fabric and pv_ms > 0 else None,
             "measured_copy_bytes_per_s": copy_rate, "frac_of_measured_copy": rate / copy_rate if copy_rate > 0 else 0.0,
