@@ -532,6 +532,14 @@ __global__ __launch_bounds__(256) void outlier_finalise_kernel(const double* __r
 
 // P = number of leaf-id bit planes, J = b samples per wave, kMode = what is counted and how it leaves.
 enum { kModePlain = 0, kModeOob = 1, kModeSparse = 2, kModeOutlier = 3, kModeBoth = 4 };
+// Off: measured at N = 100,000, B = 1,000 it cuts the plane traffic between L2 and the fabric from 80 to 21 GB per launch
+// and costs 5 % (fused pass 78.2 -> 82.0 ms, plain 57.8 -> 61.6 ms): the four waves then read four different a tiles per
+// group of trees from L2 instead of sharing one through the first-level cache, and no registers are left to request
+// them a group ahead.  The traffic does not bind (1 TB/s), the vector pipes do.
+#ifndef RFX_TILE_SHARE_B
+#define RFX_TILE_SHARE_B 0
+#endif
+constexpr bool tile_shares_b(int mode) { return RFX_TILE_SHARE_B != 0 && mode != kModeOutlier; }
 template <int P, int J, int kMode>
 __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(P, kMode)) void prox_tile_kernel(const uint32_t* __restrict__ planes, int64_t Npad,
                                                                  int32_t G, int32_t n_tile_rows, TileOut out, TileOut out2) {
@@ -540,14 +548,20 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(P, kMode)) void prox_til
     constexpr int PS = plane_stride(P);
     constexpr int PL = (kOob || kBoth) ? P + 1 : P;  // words of a sample actually used
     constexpr int PV = (PL + 3) / 4;         // 16-byte loads per a sample
-    constexpr int kBTile = J * kWaves;
-    constexpr int kRatio = kATile / kBTile;  // b tiles per a tile
+    // The four waves of a workgroup either share their a samples and take four consecutive groups of J b samples
+    // (outlier sums: the a side is combined over the waves), or share their J b samples and take four consecutive
+    // a tiles: then they ask for the same b planes at the same time and the scalar cache hands one fetch to all four,
+    // a quarter of the plane traffic between L2 and the fabric.
+    constexpr bool kShareB = tile_shares_b(kMode);
+    constexpr int kARow = kShareB ? kATile * kWaves : kATile;  // a samples of a workgroup
+    constexpr int kBTile = kShareB ? J : J * kWaves;           // b samples of a workgroup
+    constexpr int kRatio = kARow / kBTile;                     // b tiles per tile row
 
-    // Tile index.  A tile row `ta` (256 a samples) pairs with b tiles 0 .. (ta+1)*kRatio - 1.
+    // Tile index.  A tile row `ta` (kARow a samples) pairs with b tiles 0 .. (ta+1)*kRatio - 1.
     // Consecutive workgroup ids go to the 8 XCDs in turn, so XCD x = id % 8 is given the tile rows
     // ta = x, x+8, x+16, ... and walks each of them from b tile 0 upwards: the workgroups an XCD runs
     // at any moment share their a planes in that XCD's L2 and write neighbouring column ranges of the
-    // same 256 output rows.  Before row number m of an XCD's list it has done
+    // same output rows.  Before row number m of an XCD's list it has done
     // kRatio * (m*(x+1) + 4*m*(m-1)) tiles.
     const int64_t x = blockIdx.x & 7, l = blockIdx.x >> 3;
     auto before = [&](int64_t m) { return (int64_t)kRatio * (m * (x + 1) + 4 * m * (m - 1)); };
@@ -561,8 +575,13 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(P, kMode)) void prox_til
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t a0 = ta * kATile + lane * kR;
-    const int64_t b0 = __builtin_amdgcn_readfirstlane((int)(tb * kBTile + wave * J));
+    // this wave's 256 a samples and J b samples
+    const int64_t ta_w = kShareB ? ta * kWaves + wave : ta;
+    const int64_t a0 = ta_w * kATile + lane * kR;
+    const int64_t b0 = __builtin_amdgcn_readfirstlane((int)(tb * kBTile + (kShareB ? 0 : wave * J)));
+    // with shared b samples a wave may have nothing to do: its a tile lies past the data, or wholly above the diagonal
+    // (every b of the tile >= every a of the wave)
+    const bool active = !kShareB || (ta_w * kATile < Npad && b0 < (ta_w + 1) * kATile);
 
     // LDS: per-wave transposition buffers for the epilogue, then the table of the quotients c / B,
     // c = 0..B (plain variant with a float32 output only)
@@ -582,7 +601,8 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(P, kMode)) void prox_til
 #pragma unroll
         for (int j = 0; j < J; ++j) acc[r][j] = 0;
 
-    for (int g = 0; g < G; ++g) {
+    const int n_groups = active ? G : 0;
+    for (int g = 0; g < n_groups; ++g) {
         const uint4* pa = reinterpret_cast<const uint4*>(planes + ((int64_t)g * Npad + a0) * PS);
         uint32_t xa[kR][PV * 4];
 #pragma unroll
@@ -650,28 +670,32 @@ __global__ __launch_bounds__(64 * kWaves, RFX_MIN_WAVES(P, kMode)) void prox_til
         }
     }
 
+    if (!active) return;  // (no barrier follows: only the outlier sums have one, and there every wave is active)
+    const int64_t a_tile = ta_w * kATile;
     if (kBoth) {
         if (out.use_tab)
-            write_tile<J, false, true, 1>(out, tab, tr, lane, ta * kATile, b0, acc);
+            write_tile<J, false, true, 1>(out, tab, tr, lane, a_tile, b0, acc);
         else
-            write_tile<J, false, false, 1>(out, tab, tr, lane, ta * kATile, b0, acc);
+            write_tile<J, false, false, 1>(out, tab, tr, lane, a_tile, b0, acc);
         __builtin_amdgcn_wave_barrier();
-        write_tile<J, true, false, 2>(out2, tab, tr, lane, ta * kATile, b0, acc);
+        write_tile<J, true, false, 2>(out2, tab, tr, lane, a_tile, b0, acc);
     } else if (kMode == kModeSparse)
-        emit_tile<J>(out, tr, lane, ta * kATile, b0, acc);
+        emit_tile<J>(out, tr, lane, a_tile, b0, acc);
     else if (kMode == kModeOutlier)
-        outlier_tile<J>(out, lds, lane, wave, ta * kATile, b0, acc);
+        outlier_tile<J>(out, lds, lane, wave, a_tile, b0, acc);
     else if (out.use_tab)
-        write_tile<J, kOob, true>(out, tab, tr, lane, ta * kATile, b0, acc);
+        write_tile<J, kOob, true>(out, tab, tr, lane, a_tile, b0, acc);
     else
-        write_tile<J, kOob, false>(out, tab, tr, lane, ta * kATile, b0, acc);
+        write_tile<J, kOob, false>(out, tab, tr, lane, a_tile, b0, acc);
 }
 
 template <int P, int J, int kMode>
 int launch_tiles(const uint32_t* planes, int64_t Npad, int32_t G, const TileOut& out, const TileOut& out2, hipStream_t st,
                  bool timing) {
-    constexpr int kRatio = kATile / (J * kWaves);
-    const int64_t rows = Npad / kATile;
+    constexpr bool kShareB = tile_shares_b(kMode);
+    constexpr int kARow = kShareB ? kATile * kWaves : kATile;
+    constexpr int kRatio = kARow / (kShareB ? J : J * kWaves);
+    const int64_t rows = rfx::ceil_div(Npad, kARow);
     // XCD x works through tile rows x, x+8, ...; the last XCD that has `cnt` rows has the longest list
     int64_t longest = 0;
     for (int64_t x = 0; x < 8 && x < rows; ++x) {
