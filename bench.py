@@ -40,6 +40,10 @@ def parse_args():
     ap.add_argument("--rows", type=int, default=0, help="override the row count (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mds-block", type=int, default=16)
+    ap.add_argument("--profile", action="store_true",
+                    help="a run under rocprofv3: leaves out the one measurement that launches the step's kernels on a reduced input "
+                         "(the phases of the implicit product one after the other), so that the per-dispatch averages of the profile "
+                         "hold launches of the full workload only")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 4 GiB device copy before the steps (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--summarise-kernel-trace", metavar="CSV",
@@ -67,6 +71,7 @@ class Workload:
         self.B = B = args.trees or c.B
         self.k, self.T, self.m = c.k, c.T, args.mds_block
         self.reduced = bool(args.rows or args.trees)
+        self.profile_run = bool(getattr(args, "profile", False))
         # Workloads whose dense float32 output does not fit the GPU (workload 5: 1 TB) take the exact sparse list instead
         # of the dense passes, and their forest is grown on the GPU (the CPU input generator needs tens of minutes there).
         self.large = large = 4.0 * N * N > 120e9
@@ -522,7 +527,7 @@ def pv_figures(w, kern, copy_rate, profile):
     gat_rate = rows_bytes / (gat_ms * 1e-3) if gat_ms > 0 else 0.0
     ceil_both = 2.0 / (1.0 / ceil_v + 1.0 / ceil_s)                    # both phases one after the other, each at its ceiling
     both_rate = 2.0 * rows_bytes / ((sum_ms + gat_ms) * 1e-3) if sum_ms + gat_ms > 0 else 0.0
-    alone = pv_phases_alone(w, ceil_v, ceil_s)
+    alone = None if w.profile_run else pv_phases_alone(w, ceil_v, ceil_s)
     fabric = None if w.reduced else fabric_bytes(profile, ["pv_leaf_sum_kernel<", "pv_gather_kernel<"],
                                                   optional=["pv_leaf_sum_big_kernel<", "pv_leaf_sum_split_kernel<", "pv_combine_kernel"])
     if fabric is not None:
