@@ -17,6 +17,9 @@ struct rfx_pv_plan {
     float* d_part = nullptr;          // [part_cap][kRanges][k_cap] partial sums of the pieces
     int64_t part_cap = 0;             // big slots d_part has room for
     static constexpr int kRanges = 8;
+    // few sample tiles: the gather cuts the trees of a group into pieces and adds their sums in order
+    int32_t gather_pieces = 1;
+    float* d_gather_part = nullptr;   // [gather_pieces][N][k_cap]
     // scratch of the grouping, kept so that the plan can be rebuilt for new leaf ids without allocating
     uint32_t* d_count = nullptr;      // [B][Q][Lb] part histograms, then cursors
     int* d_flags = nullptr;           // bad id seen; big slots per group

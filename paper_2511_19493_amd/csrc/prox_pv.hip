@@ -34,6 +34,10 @@
 namespace {
 
 constexpr int kGatherTile = 32;   // Y rows per wave in the gather
+#ifndef RFX_PV_GATHER_WAVES
+#define RFX_PV_GATHER_WAVES 4096
+#endif
+constexpr int kGatherWaves = RFX_PV_GATHER_WAVES;  // waves the gather of a group should at least have (one per wave slot of the chip)
 // Groups of trees per application.  Measured at N = 100,000, B = 1,000, k = 64: 5.66 ms in one group, 5.17 in two,
 // 5.07 in four, 5.30 in eight.  Small problems stay in one group: their kernels are too short to pay for the extra
 // launches and the cross-stream events (N = 10,000, B = 500: 0.57 ms in one group, 0.67 ms in four).
@@ -512,8 +516,17 @@ constexpr int kGatherTrees = 2;
 template <int KCH, int RPW, bool kFirst>
 __global__ __launch_bounds__(256, (KCH == 1 && RPW == 1) ? 4 : 1) void pv_gather_kernel(const uint32_t* __restrict__ slot, int64_t N, int32_t B,
                                                        int32_t b_begin, int32_t b_end,
-                                                       const float* __restrict__ S, int32_t k, float* __restrict__ Y) {
+                                                       const float* __restrict__ S, int32_t k, float* __restrict__ Y,
+                                                       int32_t trees_per_piece) {
     constexpr int kSteps = kGatherTile / RPW;  // load instructions per tree
+    // A small N gives too few tiles to fill the chip and each of them a long chain of dependent steps, so the trees are
+    // then cut into pieces (blockIdx.y) whose sums go to Y = part[piece][N][k] unscaled and are added in piece order afterwards.
+    const bool pieces = trees_per_piece > 0;
+    if (pieces) {
+        b_begin += (int32_t)blockIdx.y * trees_per_piece;
+        b_end = min(b_end, b_begin + trees_per_piece);
+        Y += (int64_t)blockIdx.y * N * k;
+    }
     const int lane = threadIdx.x & 63;
     const int64_t tile = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t i0 = tile * kGatherTile;
@@ -567,10 +580,21 @@ __global__ __launch_bounds__(256, (KCH == 1 && RPW == 1) ? 4 : 1) void pv_gather
 #pragma unroll
             for (int c = 0; c < KCH; ++c) {
                 const int cc = lane_col<RPW>(lane) + 64 * c;
-                if (cc < k) Y[(i0 + r) * k + cc] = b_end == B ? acc[s][c] / Bf : acc[s][c];
+                if (cc < k) Y[(i0 + r) * k + cc] = (b_end == B && !pieces) ? acc[s][c] / Bf : acc[s][c];
             }
         }
     }
+}
+
+// Y = (Y of the groups of trees before, unless this is the first group) + the pieces' sums in piece order, divided by the
+// number of trees after the last group
+__global__ __launch_bounds__(256) void pv_gather_combine_kernel(const float* __restrict__ part, int32_t n_pieces, int64_t n,
+                                                               int first, int last, float n_trees, float* __restrict__ Y) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n) return;
+    float acc = first ? 0.0f : Y[e];
+    for (int32_t c = 0; c < n_pieces; ++c) acc += part[(int64_t)c * n + e];
+    Y[e] = last ? acc / n_trees : acc;
 }
 
 // The second stream of the overlapped application: one per device for the life of the process, created on first use
@@ -631,12 +655,19 @@ int launch_apply(const rfx_pv_plan* p, const float* V, int32_t k, float* Y, hipS
         }
         {
             rfx::TimedLaunch timed("pv_gather_kernel", gs);
-            if (c == 0)
+            if (p->gather_pieces > 1) {
+                const int32_t per = (b1 - b0 + p->gather_pieces - 1) / p->gather_pieces;
+                const int32_t n_pieces = (b1 - b0 + per - 1) / per;   // no empty piece
+                hipLaunchKernelGGL((pv_gather_kernel<KCH, RPW, true>), dim3((unsigned)rfx::ceil_div(tiles, 4), (unsigned)n_pieces),
+                                   dim3(256), 0, gs, p->d_slot, p->N, p->B, b0, b1, p->d_S, k, p->d_gather_part, per);
+                hipLaunchKernelGGL(pv_gather_combine_kernel, dim3((unsigned)rfx::ceil_div(p->N * k, 256)), dim3(256), 0, gs,
+                                   p->d_gather_part, n_pieces, p->N * k, c == 0 ? 1 : 0, c == p->n_chunks - 1 ? 1 : 0, (float)p->B, Y);
+            } else if (c == 0)
                 hipLaunchKernelGGL((pv_gather_kernel<KCH, RPW, true>), dim3((unsigned)rfx::ceil_div(tiles, 4)), dim3(256), 0,
-                                   gs, p->d_slot, p->N, p->B, b0, b1, p->d_S, k, Y);
+                                   gs, p->d_slot, p->N, p->B, b0, b1, p->d_S, k, Y, 0);
             else
                 hipLaunchKernelGGL((pv_gather_kernel<KCH, RPW, false>), dim3((unsigned)rfx::ceil_div(tiles, 4)), dim3(256), 0,
-                                   gs, p->d_slot, p->N, p->B, b0, b1, p->d_S, k, Y);
+                                   gs, p->d_slot, p->N, p->B, b0, b1, p->d_S, k, Y, 0);
         }
         RFX_LAUNCH_CHECK("pv_gather_kernel");
     }
@@ -659,6 +690,7 @@ int rfx_pv_plan_destroy(rfx_pv_plan* p) {
     if (p->d_big) (void)hipFree(p->d_big);
     if (p->d_big_bounds) (void)hipFree(p->d_big_bounds);
     if (p->d_part) (void)hipFree(p->d_part);
+    if (p->d_gather_part) (void)hipFree(p->d_gather_part);
     if (p->d_S) (void)hipFree(p->d_S);
     if (p->d_count) (void)hipFree(p->d_count);
     if (p->d_flags) (void)hipFree(p->d_flags);
@@ -764,6 +796,12 @@ int rfx_pv_plan_create(const uint32_t* leaf, int64_t N, int32_t B, int32_t leaf_
         p->big_base[c] = max_big;
         max_big += (int64_t)trees * N / kBigLeaf + 1;
     }
+    // pieces of a group's tree range in the gather when the sample tiles are few: enough (tile, piece) pairs for about 4096
+    // waves, at least 4 trees per piece, at most 16 pieces
+    {
+        const int64_t tiles = rfx::ceil_div(N, kGatherTile), group_trees = B / p->n_chunks;
+        p->gather_pieces = (int32_t)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, group_trees / 4), kGatherWaves / tiles));
+    }
     // 1: 32-bit LDS counters; 2: 16-bit pairs (up to 65,536 leaves, parts below 65,536 samples); 0: global atomics
     p->lds_hist = Lb <= kHistLdsLeaves ? 1 : ((Lb <= 65536 && part_len < 65536) ? 2 : 0);
     hipError_t e = hipMalloc((void**)&p->d_slot, sizeof(uint32_t) * (size_t)B * (size_t)N);
@@ -820,6 +858,10 @@ int rfx_pv_plan_reserve(rfx_pv_plan* p, int32_t k) {
     for (int c = 0; c < p->n_chunks; ++c) n_big_all += p->big_cnt[c];
     p->part_cap = n_big_all + n_big_all / 4 + 64;
     RFX_HIP(hipMalloc((void**)&p->d_part, sizeof(float) * (size_t)p->part_cap * rfx_pv_plan::kRanges * (size_t)k));
+    if (p->d_gather_part) (void)hipFree(p->d_gather_part);
+    p->d_gather_part = nullptr;
+    if (p->gather_pieces > 1)
+        RFX_HIP(hipMalloc((void**)&p->d_gather_part, sizeof(float) * (size_t)p->gather_pieces * (size_t)p->N * (size_t)k));
     p->k_cap = k;
     return RFX_OK;
 }
