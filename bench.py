@@ -106,7 +106,6 @@ class Workload:
         self.d_leaf_class = torch.from_numpy(leaf_class).to(dev)
         self.d_inbag = torch.from_numpy(F.inbag.view(np.int16)).to(dev)
         self.dV0 = torch.from_numpy(ri.start_block(N, self.k)).to(dev)
-        self.dx0 = torch.from_numpy(ri.start_block(N, self.m, seed=ri.mixture.START_SEED + 1)).to(dev)
         self.leaf = torch.empty((B, N), dtype=torch.int32, device=dev)
         self.lib = rfx.load()
         self.stream = torch.cuda.current_stream().cuda_stream
@@ -217,9 +216,10 @@ class Workload:
                                                                  self.Q, self.scales, self.status))
         if self.mds_iters == 0:
             # first warm-up step: the tolerance-driven call fixes the number of applications for the timed steps
-            _, _, self.mds_iters = rfx.mds3d(self.Q, self.scales, self.dx0, rfx.MDS_SQUARED, max_iters=200, tol=MDS_TOL)
-        self.timed("mds3d", lambda: rfx.mds3d_ws(self.Q, self.scales, self.dx0, self.mds_iters, self.ws_mds, self.coords,
-                                                 self.ev, self.mds_rel))
+            _, _, self.mds_iters = rfx.mds3d(self.Q, self.scales, None, rfx.MDS_SQUARED, max_iters=200, tol=MDS_TOL, m=self.m)
+        # no start block: the library begins from the leading columns of the factor
+        self.timed("mds3d", lambda: rfx.mds3d_ws(self.Q, self.scales, None, self.mds_iters, self.ws_mds, self.coords,
+                                                 self.ev, self.mds_rel, m=self.m))
 
 
 def calibration_copy(w):

@@ -437,9 +437,11 @@ int rfx_dequantise_factor(const void* codes, const float* scales, int64_t N, int
  * an error: dependent directions are dropped and their Ritz values are 0.
  *   Q [device] int8 [N][k], scales [device] float32 [k], 1 <= k <= 128
  *   m          block width, 3..32, m <= N (extra vectors speed up convergence)
- *   x0         [device] float32 [N][m] start block
+ *   x0         [device] nullable float32 [N][m] start block; null: the m leading columns of the
+ *              factor (the columns of the largest eigenvalues of P nearly span the subspace wanted, so
+ *              few applications are left to do), filled up with fixed pseudo-random columns where m > k
  *   coords     [device] float32 [N][3] out;  eigvals [device] float32 [3] out
- * rfx_mds3d (synchronous): max_iters >= 1; tol >= 0: the host looks at the iteration every 4
+ * rfx_mds3d (synchronous): max_iters >= 1; tol >= 0: the host looks at the iteration every 2
  *   applications of G and stops when, in the last one, the three leading Ritz values changed by
  *   at most tol * |value|;  iters_done [host] nullable out: applications of G performed.
  * rfx_mds3d_ws (asynchronous, scratch of rfx_mds3d_workspace_bytes(N, k, m, dissim_mode)):

@@ -449,11 +449,12 @@ def quantise_int8(V, eigvals):
     return Q, s
 
 
-def mds3d(Q, scales, x0, mode: int = MDS_SQUARED, max_iters: int = 300, tol: float = 1e-6) -> Tuple:
-    """rfx_mds3d: returns (coords float32 [N][3], eigvals float32 [3], iterations done)."""
+def mds3d(Q, scales, x0=None, mode: int = MDS_SQUARED, max_iters: int = 300, tol: float = 1e-6, m: int = 16) -> Tuple:
+    """rfx_mds3d: returns (coords float32 [N][3], eigvals float32 [3], iterations done).  x0 None: the library's own
+    start block of width m (the leading columns of the factor)."""
     import torch
     N, k = Q.shape
-    m = x0.shape[1]
+    m = x0.shape[1] if x0 is not None else min(m, N)
     coords = torch.empty((N, 3), dtype=torch.float32, device=Q.device)
     ev = torch.empty(3, dtype=torch.float32, device=Q.device)
     it = ctypes.c_int32(0)
@@ -491,11 +492,11 @@ def dequantise_factor(codes, scales, N: int, k: int, encoding: int):
     return A
 
 
-def mds3d_factor(A, x0, mode: int = MDS_SQUARED, max_iters: int = 300, tol: float = 1e-6) -> Tuple:
+def mds3d_factor(A, x0=None, mode: int = MDS_SQUARED, max_iters: int = 300, tol: float = 1e-6, m: int = 16) -> Tuple:
     """rfx_mds3d_factor: as mds3d, from a float32 factor."""
     import torch
     N, k = A.shape
-    m = x0.shape[1]
+    m = x0.shape[1] if x0 is not None else min(m, N)
     coords = torch.empty((N, 3), dtype=torch.float32, device=A.device)
     ev = torch.empty(3, dtype=torch.float32, device=A.device)
     it = ctypes.c_int32(0)
@@ -653,11 +654,12 @@ def mds3d_workspace_bytes(N: int, k: int, m: int, mode: int = MDS_SQUARED) -> in
     return out.value
 
 
-def mds3d_ws(Q, scales, x0, iters: int, workspace, coords, eigvals, rel_change=None, mode: int = MDS_SQUARED):
-    """rfx_mds3d_ws: exactly `iters` applications of the Gram operator; asynchronous."""
+def mds3d_ws(Q, scales, x0, iters: int, workspace, coords, eigvals, rel_change=None, mode: int = MDS_SQUARED, m: int = 16):
+    """rfx_mds3d_ws: exactly `iters` applications of the Gram operator; asynchronous.  x0 None: the library's own start
+    block of width m."""
     import torch
     N, k = Q.shape
-    m = x0.shape[1]
+    m = x0.shape[1] if x0 is not None else min(m, N)
     wp, wb = _ws_ptr(workspace)
     _check(load().rfx_mds3d_ws(_dev(Q, torch.int8), _dev(scales, torch.float32, (k,)), N, k, mode, m, iters,
                                _dev(x0, torch.float32, (N, m)), _dev(coords, torch.float32, (N, 3)),

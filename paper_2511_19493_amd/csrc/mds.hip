@@ -581,7 +581,8 @@ int apply_gram(const TA* A, const float* scales, int64_t N, int k, int m, int sq
 
 int check_args(const void* A, int64_t N, int32_t k, int dissim_mode, int32_t m, int32_t iters, const float* x0,
                const float* coords, const float* eigvals) {
-    if (!A || !x0 || !coords || !eigvals) return rfx::fail(RFX_ERR_NULL, "rfx_mds3d: null argument");
+    (void)x0;  // null: the block starts from the leading columns of the factor
+    if (!A || !coords || !eigvals) return rfx::fail(RFX_ERR_NULL, "rfx_mds3d: null argument");
     if (N < 3 || N * 32 / 256 > 0x7fffffffLL) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: N=%lld", (long long)N);
     if (k < 1 || k > rfx::kMaxRank) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: k=%d outside 1..%d", k, rfx::kMaxRank);
     if (m < 3 || m > 32 || m > N) return rfx::fail(RFX_ERR_INVALID_ARG, "rfx_mds3d: m=%d outside 3..min(32, N)", m);
@@ -592,8 +593,30 @@ int check_args(const void* A, int64_t N, int32_t k, int dissim_mode, int32_t m, 
 }
 
 // The host looks at the convergence state every kCheckEvery applications (one 8-byte copy and one wait), not after
-// each of them.
-constexpr int kCheckEvery = 4;
+// each of them (the relative change needs two applications anyway).
+constexpr int kCheckEvery = 2;
+
+// Start block when the caller gives none: the m leading columns of the factor.  G is H A A^T H plus (squared mode) a term of the
+// same column space squared, so the columns of A that belong to the largest eigenvalues of P nearly span the subspace wanted
+// and the iteration has little left to do.  Where m > k the block is filled up with fixed pseudo-random columns (a mixing
+// function of row and column: the same block on every call).
+template <class TA>
+__global__ __launch_bounds__(256) void mds_start_kernel(const TA* __restrict__ A, const float* __restrict__ scales, int64_t N,
+                                                       int32_t k, int32_t m, float* __restrict__ X0) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= N * m) return;
+    const int64_t i = e / m;
+    const int c = (int)(e % m);
+    if (c < k) {
+        X0[e] = factor_at(A, scales, i * k + c, c);
+    } else {
+        unsigned long long z = (unsigned long long)e * 0x9e3779b97f4a7c15ull + 0xbf58476d1ce4e5b9ull;
+        z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+        z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+        z ^= z >> 31;
+        X0[e] = (float)(z >> 40) * (1.0f / 8388608.0f) - 1.0f;   // 24 bits -> [-1, 1)
+    }
+}
 
 // Simultaneous iteration on the block.  tol < 0: exactly max_iters applications and no host read-back (nothing in
 // this function waits for the device); otherwise the run stops at the first check that finds the last application's
@@ -605,6 +628,11 @@ int mds_iterate(const TA* A, const float* scales, int64_t N, int32_t k, int squa
     rfx::SmallWs& ws = w.small;
     float *X = w.X, *Y = w.Y, *Z = w.Z;
     int rc;
+    if (!x0) {
+        hipLaunchKernelGGL(mds_start_kernel<TA>, dim3((unsigned)rfx::ceil_div(N * m, 256)), dim3(256), 0, st, A, scales, N, k, m, Y);
+        RFX_LAUNCH_CHECK("mds_start_kernel");
+        x0 = Y;
+    }
     if ((rc = rfx::orthonormalise(x0, N, m, ws, Z, X, st, 2)) != RFX_OK) return rc;
     int it = 0;
     while (true) {

@@ -285,3 +285,33 @@ def test_mds3d_against_dense_torgerson_scaling(torch_cuda, request, which, k, mo
     # invariants of classical scaling: centred, mutually orthogonal columns with |col|^2 = lambda
     assert np.abs(coords.sum(axis=0)).max() <= 1e-3 * np.abs(coords).max() * np.sqrt(N)
     np.testing.assert_allclose(coords.T @ coords, np.diag(ev), atol=2e-4 * ev[0])
+    # without a start block the library begins from the leading columns of the factor: the same answer, and it gets
+    # there in no more applications than from the random block
+    c2, ev2, it2 = rfx.mds3d(torch.from_numpy(Qh).cuda(), torch.from_numpy(sh).cuda(), None, gmode, max_iters=500, tol=1e-7, m=m)
+    c2, ev2 = c2.cpu().numpy().astype(np.float64), ev2.cpu().numpy().astype(np.float64)
+    print(f"  own start block: iterations={it2} eig={ev2}", flush=True)
+    assert it2 <= iters
+    np.testing.assert_allclose(ev2, ev_ref, rtol=1e-4)
+    assert np.linalg.norm(_align(c2, ref, ev_ref) - ref) / np.linalg.norm(ref) <= 1e-3
+
+
+def test_mds3d_own_start_block_wider_than_the_factor(torch_cuda, cfg1):
+    """m > k: the start block is the k columns of the factor filled up with the library's fixed pseudo-random columns;
+    the result is the dense scaling's, the same on every call."""
+    import oracle
+    import paper_2511_19493_amd as rfx
+    import rfx_inputs as ri
+    torch = torch_cuda
+    leaf = cfg1["leaf"]
+    B, N = leaf.shape
+    k, m = 4, 12
+    lam, V = oracle.block_iteration(leaf, ri.start_block(N, k), 8)
+    Qh, sh = oracle.quantise_int8(V, lam)
+    ref, ev_ref = oracle.mds3d_dense(Qh, sh, oracle.SQUARED)
+    dQ, ds = torch.from_numpy(Qh).cuda(), torch.from_numpy(sh).cuda()
+    c1, ev1, it1 = rfx.mds3d(dQ, ds, None, rfx.MDS_SQUARED, max_iters=500, tol=1e-7, m=m)
+    c2, ev2, it2 = rfx.mds3d(dQ, ds, None, rfx.MDS_SQUARED, max_iters=500, tol=1e-7, m=m)
+    assert it1 == it2 < 500 and torch.equal(c1, c2) and torch.equal(ev1, ev2)
+    c1, ev1 = c1.cpu().numpy().astype(np.float64), ev1.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(ev1, ev_ref, rtol=1e-4)
+    assert np.linalg.norm(_align(c1, ref, ev_ref) - ref) / np.linalg.norm(ref) <= 1e-3
